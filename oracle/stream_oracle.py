@@ -1,0 +1,233 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only tests, the smoke check and the bench's CPU-baseline leg may import this.
+It wraps oracle/stream_oracle.c (Algorithm 2 of the paper and Eq. (2) on the
+retained blocks, fp64) and adds what the listing leaves to the caller:
+
+  * one call per query head: the mask is estimated "for each attention head"
+    (Section 3); with grouped-query attention query head h reads key/value head
+    h // (heads // kv_heads) (Section 2, background on GQA);
+  * a packed ragged batch is a set of independent sequences: each is sliced out
+    and handled on its own, block ids are local to the sequence.
+
+Inputs are numpy float32 arrays that hold exactly the workload dtype's values.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "stream_oracle.c")
+_LIB = os.path.join(_HERE, "libstream_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over independent rows only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int)
+        up = ctypes.POINTER(ctypes.c_ubyte)
+        lib.stream_oracle_block_score.restype = ctypes.c_double
+        lib.stream_oracle_block_score.argtypes = [fp, fp, up, ctypes.c_long, ctypes.c_int,
+                                                  ctypes.c_int, ctypes.c_long, ctypes.c_long]
+        lib.stream_oracle_n_it.restype = ctypes.c_long
+        lib.stream_oracle_n_it.argtypes = [ctypes.c_long, ctypes.c_int]
+        lib.stream_oracle_prune_head.restype = ctypes.c_int
+        lib.stream_oracle_prune_head.argtypes = [fp, fp, up, ctypes.c_long, ctypes.c_int,
+                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ip,
+                                                 ctypes.c_int, ip, ip, dp, ip,
+                                                 ctypes.POINTER(ctypes.c_longlong)]
+        lib.stream_oracle_attn_head.restype = ctypes.c_int
+        lib.stream_oracle_attn_head.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int,
+                                                ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
+                                                ctypes.c_int, ip, ip, dp, dp, dp]
+        _lib = lib
+    return _lib
+
+
+def _f32(a) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _ptr(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def n_it(T: int, block: int) -> int:
+    """n_it = ceil(log2(T_p / b_k)) (iteration count line of Alg. 2)."""
+    return int(_load().stream_oracle_n_it(int(T), int(block)))
+
+
+def block_score(Qh: np.ndarray, Kh: np.ndarray, block: int, q: int, r: int, C=None) -> float:
+    """Score of key block r for query block q of one head: masked max of the b x b dot products."""
+    Qh, Kh = _f32(Qh), _f32(Kh)
+    Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
+    return float(_load().stream_oracle_block_score(_ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float),
+                                                   _ptr(Cc, ctypes.c_ubyte), Qh.shape[0],
+                                                   Qh.shape[1], int(block), int(q), int(r)))
+
+
+def prune_head(Qh, Kh, block: int, topk: int, qblocks: Optional[Sequence[int]] = None,
+               n_levels: int = -1, C=None, want_trace: bool = False):
+    """Algorithm 2 for one head / one sequence.  Returns dict(idx, cnt, score, trace, evals)."""
+    Qh, Kh = _f32(Qh), _f32(Kh)
+    T, d = Qh.shape
+    N = (T + block - 1) // block
+    ql = np.arange(N, dtype=np.int32) if qblocks is None else np.ascontiguousarray(qblocks, dtype=np.int32)
+    nq = len(ql)
+    idx = np.full((nq, topk), -1, dtype=np.int32)
+    cnt = np.zeros((nq,), dtype=np.int32)
+    score = np.full((nq, topk), -np.inf, dtype=np.float64)
+    levels = n_it(T, block) if n_levels < 0 else n_levels
+    trace = np.full((nq, levels, topk, 2), -1, dtype=np.int32) if want_trace else None
+    evals = np.zeros(2, dtype=np.int64)
+    Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
+    rc = _load().stream_oracle_prune_head(
+        _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Cc, ctypes.c_ubyte), T, d,
+        int(block), int(topk), int(n_levels), _ptr(ql, ctypes.c_int), nq,
+        _ptr(idx, ctypes.c_int), _ptr(cnt, ctypes.c_int), _ptr(score, ctypes.c_double),
+        _ptr(trace, ctypes.c_int), _ptr(evals, ctypes.c_longlong))
+    if rc != 0:
+        raise ValueError("stream_oracle_prune_head: bad arguments")
+    return {"idx": idx, "cnt": cnt, "score": score, "trace": trace, "evals": evals}
+
+
+def block_table(cu_seqlens: Sequence[int], block: int):
+    """(sequence id, local block id) of every global query block of a packed batch."""
+    seq, loc = [], []
+    for s in range(len(cu_seqlens) - 1):
+        L = cu_seqlens[s + 1] - cu_seqlens[s]
+        nb = (L + block - 1) // block
+        seq += [s] * nb
+        loc += list(range(nb))
+    return np.asarray(seq, dtype=np.int64), np.asarray(loc, dtype=np.int64)
+
+
+def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
+          rows: Optional[Sequence[Sequence[int]]] = None, n_levels: int = -1,
+          want_trace: bool = False):
+    """Stream for every (head, query block), or for the listed rows only.
+
+    Q [heads, T, d], K [kv_heads, T, d]; topk is an int or one int per sequence.
+    rows: optional list of (head, global query block).  Output arrays are
+    [heads, NB, kmax] (full) or [len(rows), kmax] (rows), block ids sequence-local.
+    """
+    Q, K = _f32(Q), _f32(K)
+    H, T, d = Q.shape
+    g = heads // kv_heads
+    cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
+    nseq = len(cu) - 1
+    ks = [int(topk)] * nseq if np.isscalar(topk) else [int(x) for x in topk]
+    kmax = max(ks)
+    bseq, bloc = block_table(cu, block)
+    NB = len(bseq)
+    blk_off = np.concatenate([[0], np.cumsum(np.bincount(bseq, minlength=nseq))])
+    if rows is None:
+        rows_arr = np.asarray([(h, gb) for h in range(H) for gb in range(NB)], dtype=np.int64)
+        full = True
+    else:
+        rows_arr = np.asarray(rows, dtype=np.int64).reshape(-1, 2)
+        full = False
+    R = len(rows_arr)
+    idx = np.full((R, kmax), -1, dtype=np.int32)
+    cnt = np.zeros((R,), dtype=np.int32)
+    score = np.full((R, kmax), -np.inf, dtype=np.float64)
+    traces = [None] * R
+    evals = np.zeros(2, dtype=np.int64)
+    hs, ss = rows_arr[:, 0], bseq[rows_arr[:, 1]]
+    for h in np.unique(hs):
+        for s in np.unique(ss[hs == h]):
+            sel = np.nonzero((hs == h) & (ss == s))[0]
+            ql = bloc[rows_arr[sel, 1]].astype(np.int32)
+            Qh = Q[h, cu[s]:cu[s + 1]]
+            Kh = K[h // g, cu[s]:cu[s + 1]]
+            out = prune_head(Qh, Kh, block, ks[s], ql, n_levels=n_levels, want_trace=want_trace)
+            idx[sel, :ks[s]] = out["idx"]
+            cnt[sel] = out["cnt"]
+            score[sel, :ks[s]] = out["score"]
+            evals += out["evals"]
+            if want_trace:
+                for a, r in enumerate(sel):
+                    traces[r] = out["trace"][a]
+    if full:
+        idx = idx.reshape(H, NB, kmax)
+        cnt = cnt.reshape(H, NB)
+        score = score.reshape(H, NB, kmax)
+    return {"idx": idx, "cnt": cnt, "score": score, "trace": traces if want_trace else None,
+            "evals": evals, "rows": rows_arr, "blk_off": blk_off}
+
+
+def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
+                cu_seqlens=None, rows: Optional[Sequence[Sequence[int]]] = None,
+                want_mass: bool = True):
+    """Eq. (2) over the retained blocks given by idx/cnt.
+
+    idx/cnt are [heads, NB, kmax]/[heads, NB] (full) or aligned with `rows`.
+    Returns dict(O [heads, T, d], lse [heads, T], mass [heads, T]) in fp64; with `rows`,
+    only the tokens of the listed query blocks are written in O / lse, and mass holds
+    the contribution of those rows only.
+    """
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    H, T, d = Q.shape
+    g = heads // kv_heads
+    cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
+    bseq, bloc = block_table(cu, block)
+    NB = len(bseq)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    cnt = np.ascontiguousarray(cnt, dtype=np.int32)
+    kmax = idx.shape[-1]
+    if rows is None:
+        rows_arr = np.asarray([(h, gb) for h in range(H) for gb in range(NB)], dtype=np.int64)
+        idx2, cnt2 = idx.reshape(H * NB, kmax), cnt.reshape(H * NB)
+    else:
+        rows_arr = np.asarray(rows, dtype=np.int64).reshape(-1, 2)
+        idx2, cnt2 = idx.reshape(len(rows_arr), kmax), cnt.reshape(len(rows_arr))
+    O = np.zeros((H, T, d), dtype=np.float64)
+    lse = np.full((H, T), np.nan, dtype=np.float64)
+    mass = np.zeros((H, T), dtype=np.float64)
+    hs, ss = rows_arr[:, 0], bseq[rows_arr[:, 1]]
+    lib = _load()
+    for h in np.unique(hs):
+        for s in np.unique(ss[hs == h]):
+            sel = np.nonzero((hs == h) & (ss == s))[0]
+            ql = bloc[rows_arr[sel, 1]].astype(np.int32)
+            a, b_ = cu[s], cu[s + 1]
+            Qh, Kh, Vh = (np.ascontiguousarray(Q[h, a:b_]), np.ascontiguousarray(K[h // g, a:b_]),
+                          np.ascontiguousarray(V[h // g, a:b_]))
+            Oh = np.zeros((b_ - a, d), dtype=np.float64)
+            lh = np.full((b_ - a,), np.nan, dtype=np.float64)
+            mh = np.zeros((b_ - a,), dtype=np.float64)
+            i2 = np.ascontiguousarray(idx2[sel])
+            c2 = np.ascontiguousarray(cnt2[sel])
+            rc = lib.stream_oracle_attn_head(
+                _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Vh, ctypes.c_float),
+                b_ - a, d, int(block), kmax, float(scale), _ptr(ql, ctypes.c_int), len(ql),
+                _ptr(i2, ctypes.c_int), _ptr(c2, ctypes.c_int), _ptr(Oh, ctypes.c_double),
+                _ptr(lh, ctypes.c_double), _ptr(mh if want_mass else None, ctypes.c_double))
+            if rc != 0:
+                raise ValueError("stream_oracle_attn_head: bad arguments")
+            for qb in ql:
+                t0, t1 = qb * block, min((qb + 1) * block, b_ - a)
+                O[h, a + t0:a + t1] = Oh[t0:t1]
+                lse[h, a + t0:a + t1] = lh[t0:t1]
+            mass[h, a:b_] += mh
+    return {"O": O, "lse": lse, "mass": mass}
