@@ -1,0 +1,144 @@
+/*
+ * stream.h - C ABI of the MI355X (gfx950) Stream library.
+ *
+ * Two operations of the paper's method, each a sequence of HIP kernels:
+ *
+ *   stream_prune        Algorithm 2 ("Stream", Appendix C; prose in Section 3):
+ *                       hierarchical, binary-search-style estimation of a
+ *                       per-head block-sparse attention mask that keeps the
+ *                       top-k key blocks of every query block under the causal
+ *                       mask C, in O(T log T) time and O(T) memory.
+ *   stream_sparse_attn  Eq. (2): softmax attention restricted to the retained
+ *                       blocks (mask M, causal inside blocks), plus the column
+ *                       sums of the probabilities (the "vertical attention
+ *                       scores" of Section 4.1 = attention mass received by
+ *                       every key).
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless it is
+ *     marked HOST.  The library allocates nothing, frees nothing and never
+ *     synchronises: all work is enqueued on `hip_stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream).  Scratch memory comes from the
+ *     caller as `workspace` (256-byte aligned, size from the *_workspace_bytes
+ *     query); its contents are undefined afterwards.
+ *   - Layouts: Q and O are [heads, T, head_dim], K and V are
+ *     [kv_heads, T, head_dim], last dimension contiguous; the head and token
+ *     strides (in elements) are given in stream_shape, 0 meaning the contiguous
+ *     default.  Query head h reads key/value head h / (heads / kv_heads).
+ *   - A ragged batch is packed along the token axis; cu_seqlens (HOST,
+ *     int32[batch+1], cu[0] = 0, cu[batch] = T) gives the boundaries.  Blocks
+ *     never straddle sequences: sequence s has N_s = ceil(L_s / block) query
+ *     (= key) blocks, the last one possibly partial, and NB = sum_s N_s.
+ *     Key-block ids in `idx` are local to their sequence.
+ *   - b_q = b_k = block; the mask C is the causal mask.
+ *   - Every entry point validates its arguments on the host before any launch
+ *     and returns a stream_status; nothing is thrown or logged.  Outputs are
+ *     fully overwritten on STREAM_OK and untouched on an argument error.
+ */
+#ifndef STREAM_H_
+#define STREAM_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    STREAM_OK = 0,
+    STREAM_EINVAL = 1,       /* null pointer, non-positive size, inconsistent shape          */
+    STREAM_EUNSUPPORTED = 2, /* valid but outside what the kernels are built for             */
+    STREAM_EWORKSPACE = 3,   /* workspace missing, misaligned or smaller than the query says */
+    STREAM_EDEVICE = 4       /* a HIP call (launch, copy) reported an error                  */
+} stream_status;
+
+typedef enum { STREAM_F32 = 0, STREAM_BF16 = 1 } stream_dtype;
+
+typedef struct {
+    int heads;       /* query heads H                                                  */
+    int kv_heads;    /* key/value heads, divides H                                     */
+    int head_dim;    /* 64 or 128                                                      */
+    int block;       /* b_q = b_k: 32, 64 or 128                                       */
+    int dtype;       /* stream_dtype of Q, K, V, O                                     */
+    int batch;       /* sequences in the packed batch, >= 1                            */
+    long long T;     /* total tokens                                                   */
+    const int *cu_seqlens; /* HOST int32[batch+1]; may be NULL when batch == 1         */
+    long long q_stride_h, q_stride_t; /* element strides; 0 = contiguous default       */
+    long long k_stride_h, k_stride_t;
+    long long v_stride_h, v_stride_t; /* stream_sparse_attn only                        */
+    long long o_stride_h, o_stride_t; /* stream_sparse_attn only                        */
+} stream_shape;
+
+/* Optional diagnostics of stream_prune (all device pointers, each may be NULL). */
+typedef struct {
+    /* (f, l) of the nodes kept after every level, int32 [levels, heads, NB, topk_max, 2],
+       -1 where a slot holds no live node; `levels` = stream_prune_levels().  Lets a checker
+       replay a row level by level (the final list alone does not show which branches were
+       kept at one level and dropped at the next).                                           */
+    int *trace;
+    /* unsigned 64-bit counter, incremented by the number of block scores (b x b x d tile
+       products) the kernels computed; the caller zeroes it.                                 */
+    unsigned long long *tiles_scored;
+} stream_prune_diag;
+
+/* NB = total number of query blocks of the (packed) shape, or -1 on a bad shape. */
+long long stream_num_blocks(const stream_shape *shape);
+
+/* Number of refinement levels stream_prune runs for these arguments (max over sequences):
+   max(1, ceil(log2(ceil(N_s / k_s)))).  The listing's n_it = ceil(log2 N) iterations give the
+   same result: once every node is a single block a level maps the node set to itself.
+   Returns -1 on bad arguments. */
+int stream_prune_levels(const stream_shape *shape, int topk, const int *topk_per_seq);
+
+size_t stream_prune_workspace_bytes(const stream_shape *shape, int topk_max);
+
+/*
+ * Algorithm 2 for every (query head, query block).
+ *
+ *   Q, K          inputs (device), layouts above
+ *   topk          k, the number of key blocks kept per query block (>= 1); k > N_s keeps every
+ *                 causal block
+ *   topk_per_seq  HOST int[batch] overriding topk per sequence, or NULL
+ *   topk_max      row length of idx/score (>= every k in use, <= 64)
+ *   idx           int32 [heads, NB, topk_max]: retained key-block ids, ascending, padded with -1
+ *   cnt           int32 [heads, NB]: number of retained blocks = min(k, q+1)
+ *   score         float [heads, NB, topk_max] or NULL: block score (max masked dot product,
+ *                 Eq. (4), unscaled) of each retained block, padded with -inf
+ *   diag          optional diagnostics or NULL
+ *
+ * Levels after the first reuse the parent's score for the child that contains the parent's
+ * representative (same block, same score) and compute one new block score per kept node.
+ * Ties in "top-k" go to the lower branch position.
+ */
+stream_status stream_prune(const void *Q, const void *K, const stream_shape *shape,
+                           int topk, const int *topk_per_seq, int topk_max,
+                           int *idx, int *cnt, float *score, const stream_prune_diag *diag,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_max);
+
+/*
+ * Eq. (2) on the retained blocks:  for every real query token t of query block q,
+ *     S~[t,u] = scale * <Q_t, K_u>  for keys u of the blocks idx[h, q, 0..cnt-1] with u <= t,
+ *     P~ = softmax(S~),  O_t = sum_u P~[t,u] V_u.
+ *
+ *   idx, cnt      as written by stream_prune (any ascending block lists with ids <= q work)
+ *   scale         multiplies the dot products (the paper's Eq. (2) has scale = 1; models use
+ *                 1/sqrt(head_dim))
+ *   O             [heads, T, head_dim] in the input dtype
+ *   lse           float [heads, T] or NULL: log-sum-exp of each row of S~
+ *   mass          float [heads, T] or NULL: mass[h,u] = sum_t P~[t,u]; zeroed by the library,
+ *                 accumulated with floating-point atomics (summation order not fixed)
+ */
+stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
+                                 const stream_shape *shape,
+                                 const int *idx, const int *cnt, int topk_max, float scale,
+                                 void *O, float *lse, float *mass,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+const char *stream_status_str(stream_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STREAM_H_ */

@@ -1,0 +1,200 @@
+"""ctypes binding of the C ABI in include/stream.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch supplies
+device memory and the current stream.  There is no fallback: if the library has not been built
+(python __graft_entry__.py) loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libstream_hip.so")
+
+STREAM_OK, STREAM_EINVAL, STREAM_EUNSUPPORTED, STREAM_EWORKSPACE, STREAM_EDEVICE = range(5)
+STREAM_F32, STREAM_BF16 = 0, 1
+
+EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
+           "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
+           "stream_status_str"]
+
+
+class StreamShape(ctypes.Structure):
+    _fields_ = [("heads", ctypes.c_int), ("kv_heads", ctypes.c_int), ("head_dim", ctypes.c_int),
+                ("block", ctypes.c_int), ("dtype", ctypes.c_int), ("batch", ctypes.c_int),
+                ("T", ctypes.c_longlong), ("cu_seqlens", ctypes.POINTER(ctypes.c_int)),
+                ("q_stride_h", ctypes.c_longlong), ("q_stride_t", ctypes.c_longlong),
+                ("k_stride_h", ctypes.c_longlong), ("k_stride_t", ctypes.c_longlong),
+                ("v_stride_h", ctypes.c_longlong), ("v_stride_t", ctypes.c_longlong),
+                ("o_stride_h", ctypes.c_longlong), ("o_stride_t", ctypes.c_longlong)]
+
+
+class StreamPruneDiag(ctypes.Structure):
+    _fields_ = [("trace", ctypes.c_void_p), ("tiles_scored", ctypes.c_void_p)]
+
+
+class StreamError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load().stream_status_str(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} (status {code})")
+
+
+_lib = None
+
+
+def load():
+    """Load the HIP library and declare every exported symbol (no GPU call)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python __graft_entry__.py` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    sp = ctypes.POINTER(StreamShape)
+    vp, ip = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)
+    lib.stream_num_blocks.restype = ctypes.c_longlong
+    lib.stream_num_blocks.argtypes = [sp]
+    lib.stream_prune_levels.restype = ctypes.c_int
+    lib.stream_prune_levels.argtypes = [sp, ctypes.c_int, ip]
+    lib.stream_prune_workspace_bytes.restype = ctypes.c_size_t
+    lib.stream_prune_workspace_bytes.argtypes = [sp, ctypes.c_int]
+    lib.stream_prune.restype = ctypes.c_int
+    lib.stream_prune.argtypes = [vp, vp, sp, ctypes.c_int, ip, ctypes.c_int, vp, vp, vp,
+                                 ctypes.POINTER(StreamPruneDiag), vp, ctypes.c_size_t, vp]
+    lib.stream_sparse_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.stream_sparse_attn_workspace_bytes.argtypes = [sp, ctypes.c_int]
+    lib.stream_sparse_attn.restype = ctypes.c_int
+    lib.stream_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int, ctypes.c_float,
+                                       vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.stream_status_str.restype = ctypes.c_char_p
+    lib.stream_status_str.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return STREAM_F32
+    if t.dtype == torch.bfloat16:
+        return STREAM_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def make_shape(heads, kv_heads, head_dim, block, dtype_code, T, cu_seqlens=None, Q=None, K=None,
+               V=None, O=None):
+    """Build a stream_shape; returns (shape, keepalive) - keepalive owns the host cu_seqlens array."""
+    s = StreamShape()
+    s.heads, s.kv_heads, s.head_dim, s.block, s.dtype = heads, kv_heads, head_dim, block, dtype_code
+    s.T = int(T)
+    keep = None
+    if cu_seqlens is not None:
+        cu = [int(x) for x in cu_seqlens]
+        keep = (ctypes.c_int * len(cu))(*cu)
+        s.cu_seqlens = ctypes.cast(keep, ctypes.POINTER(ctypes.c_int))
+        s.batch = len(cu) - 1
+    else:
+        s.batch = 1
+    for name, t in (("q", Q), ("k", K), ("v", V), ("o", O)):
+        if t is not None:
+            if t.stride(-1) != 1:
+                raise ValueError("last dimension must be contiguous")
+            setattr(s, f"{name}_stride_h", t.stride(0))
+            setattr(s, f"{name}_stride_t", t.stride(1))
+    return s, keep
+
+
+def _stream_ptr() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def num_blocks(shape: StreamShape) -> int:
+    return int(load().stream_num_blocks(ctypes.byref(shape)))
+
+
+def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
+                 topk, cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
+                 want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None):
+    """Algorithm 2 for every (head, query block).  Q [H, T, d], K [Hkv, T, d] on the GPU.
+
+    topk: int, or one int per sequence.  Returns dict(idx [H, NB, kmax] int32, cnt [H, NB] int32,
+    score (optional) fp32, trace (optional) int32 [levels, H, NB, kmax, 2], tiles (optional)).
+    """
+    lib = load()
+    if not (Q.is_cuda and K.is_cuda):
+        raise ValueError("Q and K must be device tensors (the library has no CPU path)")
+    H, T, d = Q.shape
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K)
+    nseq = shape.batch
+    if isinstance(topk, int):
+        ks, kmax, k_arr = None, int(topk), None
+    else:
+        ks = [int(x) for x in topk]
+        kmax = max(ks)
+        k_arr = (ctypes.c_int * nseq)(*ks)
+    NB = num_blocks(shape)
+    if NB < 0:
+        raise StreamError(STREAM_EINVAL, "stream_num_blocks")
+    dev = Q.device
+    if out is None:
+        idx = torch.empty((H, NB, kmax), dtype=torch.int32, device=dev)
+        cnt = torch.empty((H, NB), dtype=torch.int32, device=dev)
+        score = torch.empty((H, NB, kmax), dtype=torch.float32, device=dev) if want_score else None
+    else:
+        idx, cnt, score = out["idx"], out["cnt"], out.get("score")
+    need = lib.stream_prune_workspace_bytes(ctypes.byref(shape), kmax)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+    diag = StreamPruneDiag()
+    trace = tiles = None
+    levels = lib.stream_prune_levels(ctypes.byref(shape), kmax if ks is None else 0,
+                                     k_arr if k_arr is not None else None)
+    if want_trace:
+        trace = torch.empty((max(levels, 0), H, NB, kmax, 2), dtype=torch.int32, device=dev)
+        diag.trace = trace.data_ptr()
+    if want_tiles:
+        tiles = torch.zeros((1,), dtype=torch.int64, device=dev)
+        diag.tiles_scored = tiles.data_ptr()
+    rc = lib.stream_prune(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape),
+                          kmax if ks is None else 0, k_arr, kmax,
+                          idx.data_ptr(), cnt.data_ptr(), score.data_ptr() if score is not None else None,
+                          ctypes.byref(diag) if (want_trace or want_tiles) else None,
+                          workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_prune")
+    return {"idx": idx, "cnt": cnt, "score": score, "trace": trace, "tiles": tiles,
+            "levels": levels, "workspace": workspace, "_keep": keep}
+
+
+def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
+                       cu_seqlens=None, want_lse: bool = False, want_mass: bool = False,
+                       workspace=None, out=None):
+    """Eq. (2) on the retained blocks.  Returns dict(O [H, T, d], lse [H, T], mass [H, T])."""
+    lib = load()
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda):
+        raise ValueError("Q, K, V must be device tensors (the library has no CPU path)")
+    H, T, d = Q.shape
+    dev = Q.device
+    O = torch.empty_like(Q) if out is None else out["O"]
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K, V=V, O=O)
+    kmax = idx.shape[-1]
+    if idx.dtype != torch.int32 or cnt.dtype != torch.int32 or not idx.is_contiguous() or not cnt.is_contiguous():
+        raise ValueError("idx/cnt must be contiguous int32 device tensors")
+    lse = (torch.empty((H, T), dtype=torch.float32, device=dev) if out is None else out.get("lse")) if want_lse else None
+    mass = (torch.empty((H, T), dtype=torch.float32, device=dev) if out is None else out.get("mass")) if want_mass else None
+    need = lib.stream_sparse_attn_workspace_bytes(ctypes.byref(shape), kmax)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+    rc = lib.stream_sparse_attn(Q.data_ptr(), K.data_ptr(), V.data_ptr(), ctypes.byref(shape),
+                                idx.data_ptr(), cnt.data_ptr(), kmax, float(scale), O.data_ptr(),
+                                lse.data_ptr() if lse is not None else None,
+                                mass.data_ptr() if mass is not None else None,
+                                workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_sparse_attn")
+    return {"O": O, "lse": lse, "mass": mass, "workspace": workspace, "_keep": keep}

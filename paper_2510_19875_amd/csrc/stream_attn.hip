@@ -1,0 +1,496 @@
+// stream_sparse_attn: Eq. (2) of the paper on the retained key blocks, gfx950.
+//
+// A wavefront owns up to 64 query tokens of one (head, query block) and walks the block's
+// retained key blocks in ascending order with a running softmax.  K tiles come from the same
+// packed layout the pruning kernels use; V tiles are packed transposed so that a lane's 16
+// bytes hold one feature of the 8 (bf16) or 4 (fp32) keys its MFMA contraction slots cover.
+//
+// Pass 1 computes S^T = K Q^T with 32x32 MFMAs: a lane then owns one query column and 16 key
+// rows per accumulator, so the softmax statistics are per lane (plus one exchange between the
+// two lane halves) and the probabilities already sit in B-operand order for O^T += V^T P^T.
+// Pass 2 (only when the received mass is requested) recomputes S = Q K^T, where a lane owns one
+// key column, turns it into probabilities with the final row normalisers and adds the column
+// sums to mass[] with atomics.
+#include "stream_common.h"
+
+#include <math.h>
+
+namespace stream {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// ---------------------------------------------------------------------------------------------
+// V packing.  Per 32-key group and per 32-feature block db, fragment vf holds for lane
+// (mrow = lane % 32, gh = lane / 32) the values V[key][db*32 + mrow] of the keys
+//     bf16: element e of fragment vf (2 per group): key = (2*vf + e/4)*8 + gh*4 + e%4
+//     fp32: element e of fragment vf (4 per group): key = vf*8 + gh*4 + e
+// which are exactly the key rows a lane's S^T accumulator elements cover, in order.
+// Layout: [kv_head][global block][group][db][vf][lane] x 16 bytes.
+// ---------------------------------------------------------------------------------------------
+struct PackVParams {
+    const char *src;
+    char *dst;
+    long long stride_h_bytes, stride_t_bytes;
+    int d, esize, b, NB;
+    SeqTable seqs;
+};
+
+__global__ void __launch_bounds__(256) pack_v_kernel(PackVParams p)
+{
+    const int groups = p.b / 32;
+    const int ndb = p.d / 32;
+    const int nvf = p.esize == 2 ? 2 : 4;
+    const long long grp = blockIdx.x;
+    const int gi = (int)(grp % groups);
+    const long long t = grp / groups;
+    const int gb = (int)(t % p.NB);
+    const int kvh = (int)(t / p.NB);
+    const int s = seq_of_block(p.seqs, gb);
+    const SeqDesc sd = p.seqs.d[s];
+    const int tok0 = (gb - sd.blk0) * p.b + gi * 32;
+    char *dst = p.dst + grp * (32LL * p.d * p.esize);
+    const char *src = p.src + kvh * p.stride_h_bytes;
+    for (int c = threadIdx.x; c < ndb * nvf * 64; c += blockDim.x) {
+        const int lane = c & 63, vf = (c >> 6) % nvf, db = (c >> 6) / nvf;
+        const int mrow = lane & 31, gh = lane >> 5;
+        uint4 out = make_uint4(0, 0, 0, 0);
+        if (p.esize == 2) {
+            unsigned short v[8];
+            for (int e = 0; e < 8; ++e) {
+                const int key = (2 * vf + (e >> 2)) * 8 + gh * 4 + (e & 3);
+                const int tok = tok0 + key;
+                v[e] = tok < sd.len ? *reinterpret_cast<const unsigned short *>(
+                                          src + (sd.tok0 + tok) * p.stride_t_bytes + (db * 32 + mrow) * 2)
+                                    : (unsigned short)0;
+            }
+            out.x = v[0] | ((unsigned)v[1] << 16); out.y = v[2] | ((unsigned)v[3] << 16);
+            out.z = v[4] | ((unsigned)v[5] << 16); out.w = v[6] | ((unsigned)v[7] << 16);
+        } else {
+            unsigned v[4];
+            for (int e = 0; e < 4; ++e) {
+                const int key = vf * 8 + gh * 4 + e;
+                const int tok = tok0 + key;
+                v[e] = tok < sd.len ? *reinterpret_cast<const unsigned *>(
+                                          src + (sd.tok0 + tok) * p.stride_t_bytes + (db * 32 + mrow) * 4)
+                                    : 0u;
+            }
+            out = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+        *reinterpret_cast<uint4 *>(dst + (long long)c * 16) = out;
+    }
+}
+
+struct AttnParams {
+    const char *Q;
+    const char *Kp, *Vp;
+    char *O;
+    long long q_sh_b, q_st_b, o_sh_b, o_st_b;
+    const int *idx, *cnt;
+    float *lse, *mass;           // nullable
+    long long T;
+    int H, g, NB, kmax;
+    float scale_log2e;           // scale * log2(e): softmax runs in base 2
+    WgMap map;
+    SeqTable seqs;
+};
+
+template <bool BF16>
+__device__ __forceinline__ floatx16 mfma16(const uint4 &a, const uint4 &b, floatx16 c)
+{
+    if constexpr (BF16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.y), __builtin_bit_cast(float, b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.z), __builtin_bit_cast(float, b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.w), __builtin_bit_cast(float, b.w), c, 0, 0, 0);
+        return c;
+    }
+}
+
+// Bit pattern of a float taken BY VALUE.  (__builtin_bit_cast applied directly to an element of
+// an ext_vector_type lvalue reads element 0 whatever the index, with this compiler.)
+__device__ __forceinline__ unsigned f2u(float v) { return __builtin_bit_cast(unsigned, v); }
+
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
+{
+    // round-to-nearest-even conversion of two floats to bf16 (finite inputs in [0, 1])
+    unsigned a = __builtin_bit_cast(unsigned, lo), b = __builtin_bit_cast(unsigned, hi);
+    a += 0x7fffu + ((a >> 16) & 1u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (a >> 16) | (b & 0xffff0000u);
+}
+
+// NQ: 32-query groups per wavefront, NK: 32-key groups per key sub-tile, B: block size.
+template <bool BF16, int D, int NQ, int NK, int B, int OCC>
+__global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int FR = D * ES / 32;            // K/Q fragments per 32-token group
+    constexpr int NDB = D / 32;                // 32-feature blocks of the output
+    constexpr int NVF = BF16 ? 2 : 4;          // V fragments per (group, feature block)
+    constexpr int QT = 32 * NQ;                // queries per wavefront
+    constexpr int KT = 32 * NK;                // keys per sub-tile
+    constexpr int QSUB = B / QT;               // wavefronts per row
+    constexpr int KSUB = B / KT;               // key sub-tiles per block
+    constexpr long long TILE_BYTES = (long long)B * D * ES;
+    constexpr int GROUP_BYTES = 32 * D * ES;
+    __shared__ float s_lse[4][QT];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 31, gh = lane >> 5;
+    int kvh, slot;
+    if (!wg_decode(p.map, blockIdx.x, kvh, slot)) return;
+    const long long items_per_kv = (long long)p.NB * p.g * QSUB;
+    const long long it = (long long)slot * 4 + wave;
+    if (it >= items_per_kv) return;
+    const int qs = (int)(it % QSUB);
+    const long long rk = it / QSUB;
+    const int gb = p.NB - 1 - (int)(rk / p.g);
+    const int h = kvh * p.g + (int)(rk % p.g);
+    const int sq = seq_of_block(p.seqs, gb);
+    const SeqDesc sd = p.seqs.d[sq];
+    const int q = gb - sd.blk0, L = sd.len;
+    const long long row = (long long)h * p.NB + gb;
+    const int qtok0 = q * B + qs * QT;          // first query token (sequence-local) of this wavefront
+    if (qtok0 >= L) return;
+    const int n_blk = p.cnt[row];
+    const int *my_idx = p.idx + row * p.kmax;
+
+    // Q fragments (usable as A or B operand): lane (col, gh), fragment fr -> chunk 2*fr+gh of row col
+    uint4 qf[NQ][FR];
+#pragma unroll
+    for (int cq = 0; cq < NQ; ++cq) {
+        const int tok = qtok0 + cq * 32 + col;
+        const bool ok = tok < L;
+        const char *src = p.Q + (long long)h * p.q_sh_b + (sd.tok0 + (ok ? tok : 0)) * p.q_st_b + gh * 16;
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (ok) v = *reinterpret_cast<const uint4 *>(src + fr * 32);
+            qf[cq][fr] = v;
+        }
+    }
+    const char *kbase = p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES + lane * 16;
+    const char *vbase = p.Vp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES + lane * 16;
+
+    floatx16 acc_o[NDB][NQ];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc_o[db][cq][i] = 0.f;
+    float m_run[NQ], l_run[NQ];
+#pragma unroll
+    for (int cq = 0; cq < NQ; ++cq) { m_run[cq] = -INFINITY; l_run[cq] = 0.f; }
+
+    const int n_tiles = n_blk * KSUB;
+    // ------------------------------------------------------------------ pass 1: O and lse
+    for (int t = 0; t < n_tiles; ++t) {
+        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
+        const int ks = t % KSUB;
+        const int ktok0 = r * B + ks * KT;
+        if (ktok0 > qtok0 + QT - 1) continue;             // sub-tile entirely in the future
+        const char *ksrc = kbase + (long long)r * TILE_BYTES + (long long)ks * NK * GROUP_BYTES;
+        const char *vsrc = vbase + (long long)r * TILE_BYTES + (long long)ks * NK * GROUP_BYTES;
+        floatx16 acc_s[NK][NQ];
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_s[rb][cq][i] = 0.f;
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb) {
+                const uint4 kf = *reinterpret_cast<const uint4 *>(ksrc + (rb * FR + fr) * 1024);
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq)
+                    acc_s[rb][cq] = mfma16<BF16>(kf, qf[cq][fr], acc_s[rb][cq]);
+            }
+        // scale into base-2 logits; mask: causal inside the tile, padded keys
+        const bool need_mask = (ktok0 + KT - 1 > qtok0) || (ktok0 + KT > L);
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float v = acc_s[rb][cq][i] * p.scale_log2e;
+                    if (need_mask) {
+                        const int tk = ktok0 + rb * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
+                        const int tq = qtok0 + cq * 32 + col;
+                        if (tk > tq || tk >= L) v = -INFINITY;
+                    }
+                    acc_s[rb][cq][i] = v;
+                }
+        // running softmax per query column
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[rb][cq][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[cq], mx);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = exp2f(m_run[cq] - m_use);
+            float sum = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pr = exp2f(acc_s[rb][cq][i] - m_use);
+                    acc_s[rb][cq][i] = pr;
+                    sum += pr;
+                }
+            l_run[cq] = l_run[cq] * alpha + sum;   // per-lane partial; halves are added at the end
+            m_run[cq] = m_new;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_o[db][cq][i] *= alpha;
+        }
+        // O^T += V^T P^T
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int vf = 0; vf < NVF; ++vf) {
+                uint4 pf[NQ];
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq) {
+                    if constexpr (BF16) {
+                        const int o = vf * 8;
+                        pf[cq].x = pack_bf16x2(acc_s[rb][cq][o + 0], acc_s[rb][cq][o + 1]);
+                        pf[cq].y = pack_bf16x2(acc_s[rb][cq][o + 2], acc_s[rb][cq][o + 3]);
+                        pf[cq].z = pack_bf16x2(acc_s[rb][cq][o + 4], acc_s[rb][cq][o + 5]);
+                        pf[cq].w = pack_bf16x2(acc_s[rb][cq][o + 6], acc_s[rb][cq][o + 7]);
+                    } else {
+                        const int o = vf * 4;
+                        pf[cq].x = f2u(acc_s[rb][cq][o + 0]);
+                        pf[cq].y = f2u(acc_s[rb][cq][o + 1]);
+                        pf[cq].z = f2u(acc_s[rb][cq][o + 2]);
+                        pf[cq].w = f2u(acc_s[rb][cq][o + 3]);
+                    }
+                }
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) {
+                    const uint4 vfrag = *reinterpret_cast<const uint4 *>(
+                        vsrc + (long long)rb * GROUP_BYTES + ((db * NVF + vf) * 64) * 16);
+#pragma unroll
+                    for (int cq = 0; cq < NQ; ++cq)
+                        acc_o[db][cq] = mfma16<BF16>(vfrag, pf[cq], acc_o[db][cq]);
+                }
+            }
+    }
+
+    // ------------------------------------------------------------------ normalise, store O, lse
+    float lse2[NQ];   // log2-domain log-sum-exp of each query column
+#pragma unroll
+    for (int cq = 0; cq < NQ; ++cq) {
+        const float l_tot = l_run[cq] + __shfl_xor(l_run[cq], 32);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        lse2[cq] = l_tot > 0.f ? m_run[cq] + log2f(l_tot) : -INFINITY;
+        const int tok = qtok0 + cq * 32 + col;
+        if (tok < L) {
+            char *dst = p.O + (long long)h * p.o_sh_b + (sd.tok0 + tok) * p.o_st_b;
+            // O^T accumulator: lane holds query `col`; element i of block db is feature
+            // db*32 + 8*(i/4) + 4*gh + (i%4): four consecutive features per group of 4
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int feat = db * 32 + i4 * 8 + gh * 4;
+                    const float a = acc_o[db][cq][i4 * 4 + 0] * inv, b = acc_o[db][cq][i4 * 4 + 1] * inv;
+                    const float c = acc_o[db][cq][i4 * 4 + 2] * inv, d = acc_o[db][cq][i4 * 4 + 3] * inv;
+                    if constexpr (BF16) {
+                        uint2 v;
+                        v.x = pack_bf16x2(a, b);
+                        v.y = pack_bf16x2(c, d);
+                        *reinterpret_cast<uint2 *>(dst + feat * 2) = v;
+                    } else {
+                        *reinterpret_cast<float4 *>(dst + feat * 4) = make_float4(a, b, c, d);
+                    }
+                }
+            if (p.lse && gh == 0)
+                p.lse[(long long)h * p.T + sd.tok0 + tok] = lse2[cq] * 0.6931471805599453f;
+        }
+        if (gh == 0) s_lse[wave][cq * 32 + col] = lse2[cq];
+    }
+    if (!p.mass) return;
+
+    // ------------------------------------------------------------------ pass 2: received mass
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float *mass_h = p.mass + (long long)h * p.T + sd.tok0;
+    for (int t = 0; t < n_tiles; ++t) {
+        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
+        const int ks = t % KSUB;
+        const int ktok0 = r * B + ks * KT;
+        if (ktok0 > qtok0 + QT - 1) continue;
+        const char *ksrc = kbase + (long long)r * TILE_BYTES + (long long)ks * NK * GROUP_BYTES;
+        floatx16 acc_s[NQ][NK];   // S = Q K^T: rows = queries, lane column = key
+#pragma unroll
+        for (int rq = 0; rq < NQ; ++rq)
+#pragma unroll
+            for (int ck = 0; ck < NK; ++ck)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_s[rq][ck][i] = 0.f;
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+            for (int ck = 0; ck < NK; ++ck) {
+                const uint4 kf = *reinterpret_cast<const uint4 *>(ksrc + (ck * FR + fr) * 1024);
+#pragma unroll
+                for (int rq = 0; rq < NQ; ++rq)
+                    acc_s[rq][ck] = mfma16<BF16>(qf[rq][fr], kf, acc_s[rq][ck]);
+            }
+#pragma unroll
+        for (int ck = 0; ck < NK; ++ck) {
+            const int tk = ktok0 + ck * 32 + col;
+            float colsum = 0.f;
+#pragma unroll
+            for (int rq = 0; rq < NQ; ++rq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int qi = rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
+                    const int tq = qtok0 + qi;
+                    const float e = exp2f(acc_s[rq][ck][i] * p.scale_log2e - s_lse[wave][qi]);
+                    colsum += (tq < L && tk <= tq) ? e : 0.f;
+                }
+            colsum += __shfl_xor(colsum, 32);
+            if (gh == 0 && tk < L && colsum != 0.f) atomicAdd(mass_h + tk, colsum);
+        }
+    }
+}
+
+typedef void (*attn_fn)(const AttnParams);
+
+static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
+{
+    const bool bf = pb.dtype == STREAM_BF16;
+    qsub = pb.b == 128 ? 2 : 1;
+    if (pb.b == 32) {
+        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 1, 1, 32, 1> : attn_kernel<true, 64, 1, 1, 32, 1>;
+        return pb.d == 128 ? attn_kernel<false, 128, 1, 1, 32, 1> : attn_kernel<false, 64, 1, 1, 32, 1>;
+    }
+    if (pb.b == 64) {
+        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 2, 64, 1> : attn_kernel<true, 64, 2, 2, 64, 1>;
+        return pb.d == 128 ? attn_kernel<false, 128, 2, 2, 64, 1> : attn_kernel<false, 64, 2, 2, 64, 1>;
+    }
+    if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 2, 128, 1> : attn_kernel<true, 64, 2, 2, 128, 1>;
+    return pb.d == 128 ? attn_kernel<false, 128, 2, 2, 128, 1> : attn_kernel<false, 64, 2, 2, 128, 1>;
+}
+
+struct AttnWorkspace {
+    size_t kp, vp, total;
+};
+
+static AttnWorkspace attn_layout(const Problem &pb)
+{
+    AttnWorkspace w;
+    const size_t tile = align_up((size_t)pb.Hkv * pb.NB * pb.b * pb.d * pb.esize, 256);
+    w.kp = 0;
+    w.vp = tile;
+    w.total = 2 * tile;
+    return w;
+}
+
+__global__ void __launch_bounds__(256) zero_kernel(float *p, long long n)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+}  // namespace stream
+
+using namespace stream;
+
+extern "C" {
+
+size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_max)
+{
+    Problem pb;
+    if (topk_max < 1) return 0;
+    if (make_problem(shape, 0, nullptr, 0, &pb) != STREAM_OK) return 0;
+    return attn_layout(pb).total;
+}
+
+stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
+                                 const stream_shape *shape,
+                                 const int *idx, const int *cnt, int topk_max, float scale,
+                                 void *O, float *lse, float *mass,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!Q || !K || !V || !shape || !idx || !cnt || !O) return STREAM_EINVAL;
+    if (topk_max < 1 || !(scale > 0.f) || !isfinite(scale)) return STREAM_EINVAL;
+    Problem pb;
+    stream_status rc = make_problem(shape, 0, nullptr, 0, &pb);
+    if (rc != STREAM_OK) return rc;
+    pb.kmax = topk_max;
+    const long long dflt_h = pb.T * pb.d;
+    const long long q_sh = shape->q_stride_h ? shape->q_stride_h : dflt_h;
+    const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;
+    const long long k_sh = shape->k_stride_h ? shape->k_stride_h : dflt_h;
+    const long long k_st = shape->k_stride_t ? shape->k_stride_t : pb.d;
+    const long long v_sh = shape->v_stride_h ? shape->v_stride_h : dflt_h;
+    const long long v_st = shape->v_stride_t ? shape->v_stride_t : pb.d;
+    const long long o_sh = shape->o_stride_h ? shape->o_stride_h : dflt_h;
+    const long long o_st = shape->o_stride_t ? shape->o_stride_t : pb.d;
+    if (q_st < pb.d || k_st < pb.d || v_st < pb.d || o_st < pb.d) return STREAM_EINVAL;
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return STREAM_EINVAL;
+    if (((q_sh | q_st | k_sh | k_st | v_sh | v_st | o_sh | o_st) * pb.esize) & 15) return STREAM_EINVAL;
+    const AttnWorkspace w = attn_layout(pb);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return STREAM_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+
+    rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st);
+    if (rc != STREAM_OK) return rc;
+    {
+        PackVParams pv;
+        pv.src = (const char *)V;
+        pv.dst = ws + w.vp;
+        pv.stride_h_bytes = v_sh * pb.esize;
+        pv.stride_t_bytes = v_st * pb.esize;
+        pv.d = pb.d; pv.esize = pb.esize; pv.b = pb.b; pv.NB = pb.NB;
+        pv.seqs = pb.seqs;
+        const long long grid = (long long)pb.Hkv * pb.NB * (pb.b / 32);
+        if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
+        hipLaunchKernelGGL(pack_v_kernel, dim3((unsigned)grid), dim3(256), 0, st, pv);
+        if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+    }
+    if (mass) {
+        const long long n = (long long)pb.H * pb.T;
+        hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, mass, n);
+        if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+    }
+    AttnParams p;
+    p.Q = (const char *)Q;
+    p.Kp = ws + w.kp;
+    p.Vp = ws + w.vp;
+    p.O = (char *)O;
+    p.q_sh_b = q_sh * pb.esize; p.q_st_b = q_st * pb.esize;
+    p.o_sh_b = o_sh * pb.esize; p.o_st_b = o_st * pb.esize;
+    p.idx = idx; p.cnt = cnt; p.lse = lse; p.mass = mass;
+    p.T = pb.T; p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.kmax = topk_max;
+    p.scale_log2e = scale * 1.4426950408889634f;
+    p.seqs = pb.seqs;
+    int qsub = 1;
+    attn_fn fn = pick_attn_kernel(pb, qsub);
+    const long long items_per_kv = (long long)pb.NB * pb.g * qsub;
+    const long long per_kv = (items_per_kv + 3) / 4;
+    if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
+    p.map = make_wg_map(pb.Hkv, (int)per_kv);
+    hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
+    return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+}
+
+}  // extern "C"

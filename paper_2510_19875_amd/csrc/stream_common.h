@@ -1,0 +1,110 @@
+// Shared declarations of the gfx950 Stream kernels (device + host side of the library).
+// Nothing in here is used by the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "stream.h"
+
+namespace stream {
+
+constexpr int kMaxBatch = 32;   // sequence descriptors travel as kernel arguments
+constexpr int kMaxTopk = 64;    // one node per lane of a 64-wide wavefront
+constexpr int kXcds = 8;        // MI355X: 8 XCDs, workgroups are dealt to them round-robin
+
+// One sequence of the packed batch.
+struct SeqDesc {
+    long long tok0;  // first token in the packed token axis
+    int len;         // L_s real tokens
+    int nblk;        // N_s = ceil(L_s / block)
+    int blk0;        // first global block id
+    int k;           // k_s
+    int levels;      // refinement levels to run: max(1, ceil(log2(ceil(N_s / k_s))))
+    int pad_;
+};
+
+struct SeqTable {
+    int n;
+    int pad_[3];
+    SeqDesc d[kMaxBatch];
+};
+
+// Workgroup -> (kv head, slot) mapping that keeps each XCD's L2 on as few key heads as it can.
+enum MapMode { kMapPlain = 0, kMapKvMultipleOfXcd = 1, kMapKvDividesXcd = 2 };
+
+struct WgMap {
+    int mode;
+    int per_kv;   // work items (workgroups) per kv head
+    int kv_heads;
+    int grid;     // workgroups to launch
+};
+
+inline WgMap make_wg_map(int kv_heads, int per_kv)
+{
+    WgMap m;
+    m.kv_heads = kv_heads;
+    m.per_kv = per_kv;
+    if (kv_heads % kXcds == 0) {
+        m.mode = kMapKvMultipleOfXcd;
+        m.grid = kv_heads * per_kv;
+    } else if (kXcds % kv_heads == 0) {
+        m.mode = kMapKvDividesXcd;
+        int r = kXcds / kv_heads;
+        m.grid = kXcds * ((per_kv + r - 1) / r);
+    } else {
+        m.mode = kMapPlain;
+        m.grid = kv_heads * per_kv;
+    }
+    return m;
+}
+
+// Returns false when this workgroup has no work.
+__device__ __forceinline__ bool wg_decode(const WgMap &m, int wg, int &kvh, int &slot)
+{
+    if (m.mode == kMapKvMultipleOfXcd) {
+        int x = wg % kXcds, i = wg / kXcds;
+        kvh = x + kXcds * (i / m.per_kv);
+        slot = i % m.per_kv;
+        return true;
+    }
+    if (m.mode == kMapKvDividesXcd) {
+        int x = wg % kXcds, i = wg / kXcds;
+        int r = kXcds / m.kv_heads;
+        kvh = x % m.kv_heads;
+        slot = i * r + x / m.kv_heads;
+        return slot < m.per_kv;
+    }
+    kvh = wg / m.per_kv;
+    slot = wg % m.per_kv;
+    return true;
+}
+
+// Sequence that owns global block gb (linear scan: the table is tiny and the scan is scalar).
+__device__ __forceinline__ int seq_of_block(const SeqTable &t, int gb)
+{
+    int s = 0;
+    while (s + 1 < t.n && gb >= t.d[s + 1].blk0) ++s;
+    return s;
+}
+
+// Host-side validated problem description shared by both entry points.
+struct Problem {
+    int H, Hkv, g, d, b, dtype, esize, batch, kmax;
+    long long T;
+    int NB;
+    SeqTable seqs;
+    int max_levels;
+};
+
+stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_seq, int topk_max,
+                           Problem *out);
+
+size_t align_up(size_t x, size_t a);
+
+// Packs a [kv_heads, T, d] tensor into block tiles whose 16-byte chunks are ordered the way the
+// 32x32 MFMA operand fragments are read: see pack_kernel in stream_pack.hip.
+stream_status launch_pack(const void *src, long long stride_h, long long stride_t, void *dst,
+                          const Problem &pb, hipStream_t st);
+
+}  // namespace stream

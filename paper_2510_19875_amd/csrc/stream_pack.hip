@@ -1,0 +1,168 @@
+// Host-side argument validation shared by the entry points, and the K/V tile packer.
+#include "stream_common.h"
+
+namespace stream {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int ceil_log2_ll(long long n)
+{
+    int it = 0;
+    long long v = 1;
+    while (v < n) { v <<= 1; ++it; }
+    return it;
+}
+
+// Validates a shape (+ optional top-k arguments; topk_max <= 0 skips them) and derives the
+// per-sequence block geometry of the preamble of Alg. 2: T_p = ceil(T / b) * b per sequence.
+stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_seq, int topk_max,
+                           Problem *out)
+{
+    if (!s || !out) return STREAM_EINVAL;
+    if (s->heads <= 0 || s->kv_heads <= 0 || s->T <= 0 || s->batch <= 0) return STREAM_EINVAL;
+    if (s->heads % s->kv_heads != 0) return STREAM_EINVAL;
+    if (s->dtype != STREAM_F32 && s->dtype != STREAM_BF16) return STREAM_EINVAL;
+    if (s->batch > 1 && !s->cu_seqlens) return STREAM_EINVAL;
+    if (s->head_dim != 64 && s->head_dim != 128) return STREAM_EUNSUPPORTED;
+    if (s->block != 32 && s->block != 64 && s->block != 128) return STREAM_EUNSUPPORTED;
+    if (s->batch > kMaxBatch) return STREAM_EUNSUPPORTED;
+    if (s->T > (1LL << 31) - 4096) return STREAM_EUNSUPPORTED;
+
+    Problem &p = *out;
+    p.H = s->heads; p.Hkv = s->kv_heads; p.g = s->heads / s->kv_heads;
+    p.d = s->head_dim; p.b = s->block; p.dtype = s->dtype;
+    p.esize = s->dtype == STREAM_BF16 ? 2 : 4;
+    p.batch = s->batch; p.T = s->T; p.kmax = topk_max;
+    p.seqs.n = s->batch;
+    long long nb = 0, tok = 0;
+    int maxlev = 0;
+    for (int i = 0; i < s->batch; ++i) {
+        long long a = s->cu_seqlens ? s->cu_seqlens[i] : 0;
+        long long e = s->cu_seqlens ? s->cu_seqlens[i + 1] : s->T;
+        if (a != tok || e <= a) return STREAM_EINVAL;  // cu[0] = 0, strictly increasing
+        SeqDesc &sd = p.seqs.d[i];
+        sd.tok0 = a;
+        sd.len = (int)(e - a);
+        sd.nblk = (int)((e - a + s->block - 1) / s->block);
+        sd.blk0 = (int)nb;
+        sd.k = 0; sd.levels = 0; sd.pad_ = 0;
+        if (topk_max > 0) {
+            int k = topk_per_seq ? topk_per_seq[i] : topk;
+            if (k < 1) return STREAM_EINVAL;
+            if (k > topk_max) return STREAM_EINVAL;
+            sd.k = k;
+            long long per = (sd.nblk + (long long)k - 1) / k;
+            int lv = ceil_log2_ll(per);
+            sd.levels = lv < 1 ? 1 : lv;
+            if (sd.levels > maxlev) maxlev = sd.levels;
+        }
+        nb += sd.nblk;
+        tok = e;
+    }
+    if (tok != s->T) return STREAM_EINVAL;
+    if (nb > (1LL << 30)) return STREAM_EUNSUPPORTED;
+    if (topk_max > kMaxTopk) return STREAM_EUNSUPPORTED;
+    p.NB = (int)nb;
+    p.max_levels = maxlev;
+    return STREAM_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tile packing.
+//
+// A 32x32 MFMA reads, per lane, 16 contiguous bytes of one operand row: lane (n = lane % 32,
+// g = lane / 32) supplies row n, and the g-th half of the fragment's slice of the contraction
+// axis.  Reading those 16 bytes straight from a row-major [token, d] tensor makes every lane of
+// a load instruction touch a different row.  The packer therefore rewrites each group of 32
+// tokens so that the 64 lanes' chunks of fragment `fr` are contiguous (1 KiB per fragment):
+//
+//     dst chunk (fr * 64 + g * 32 + n)  <-  src row n, 16-byte chunk (2 * fr + g)
+//
+// A block of b tokens is b/32 consecutive groups; tokens past the end of a sequence are zero
+// (they are masked out wherever they could matter).  Layout: [kv_head][global block][b * d].
+// The permutation is per 32-token group, so the same packed tensor serves every block size.
+// ---------------------------------------------------------------------------------------------
+struct PackParams {
+    const char *src;
+    char *dst;
+    long long stride_h_bytes, stride_t_bytes;
+    int row_bytes;   // d * esize
+    int b, NB, Hkv;
+    SeqTable seqs;
+};
+
+__global__ void __launch_bounds__(256) pack_kernel(PackParams p)
+{
+    const int cpr = p.row_bytes / 16;         // 16-byte chunks per row
+    const int groups = p.b / 32;
+    const long long grp = blockIdx.x;          // (kvh * NB + gb) * groups + gi
+    const int gi = (int)(grp % groups);
+    const long long t = grp / groups;
+    const int gb = (int)(t % p.NB);
+    const int kvh = (int)(t / p.NB);
+    const int s = seq_of_block(p.seqs, gb);
+    const SeqDesc sd = p.seqs.d[s];
+    const int r = gb - sd.blk0;
+    const int tok_in_seq0 = r * p.b + gi * 32;
+    char *dst = p.dst + grp * (32LL * p.row_bytes);
+    for (int c = threadIdx.x; c < 32 * cpr; c += blockDim.x) {
+        const int n = c / cpr, cc = c % cpr;
+        const int fr = cc >> 1, g = cc & 1;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        const int tok = tok_in_seq0 + n;
+        if (tok < sd.len)
+            v = *reinterpret_cast<const uint4 *>(p.src + kvh * p.stride_h_bytes +
+                                                 (sd.tok0 + tok) * p.stride_t_bytes + cc * 16);
+        *reinterpret_cast<uint4 *>(dst + ((fr * 64 + g * 32 + n) * 16)) = v;
+    }
+}
+
+stream_status launch_pack(const void *src, long long stride_h, long long stride_t, void *dst,
+                          const Problem &pb, hipStream_t st)
+{
+    PackParams p;
+    p.src = (const char *)src;
+    p.dst = (char *)dst;
+    p.stride_h_bytes = stride_h * pb.esize;
+    p.stride_t_bytes = stride_t * pb.esize;
+    p.row_bytes = pb.d * pb.esize;
+    p.b = pb.b; p.NB = pb.NB; p.Hkv = pb.Hkv;
+    p.seqs = pb.seqs;
+    long long grid = (long long)pb.Hkv * pb.NB * (pb.b / 32);
+    if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)grid), dim3(256), 0, st, p);
+    return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+}
+
+}  // namespace stream
+
+extern "C" {
+
+long long stream_num_blocks(const stream_shape *shape)
+{
+    stream::Problem pb;
+    if (stream::make_problem(shape, 0, nullptr, 0, &pb) != STREAM_OK) return -1;
+    return pb.NB;
+}
+
+int stream_prune_levels(const stream_shape *shape, int topk, const int *topk_per_seq)
+{
+    stream::Problem pb;
+    if (stream::make_problem(shape, topk, topk_per_seq, stream::kMaxTopk, &pb) != STREAM_OK)
+        return -1;
+    return pb.max_levels;
+}
+
+const char *stream_status_str(stream_status s)
+{
+    switch (s) {
+    case STREAM_OK: return "ok";
+    case STREAM_EINVAL: return "invalid argument";
+    case STREAM_EUNSUPPORTED: return "unsupported configuration";
+    case STREAM_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case STREAM_EDEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

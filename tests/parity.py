@@ -1,0 +1,118 @@
+"""Comparison rule GPU <-> oracle for the pruning path.
+
+Index lists must be equal.  Where a row differs, the row is replayed level by level along the
+GPU's own choices (its per-level node trace) with the oracle's fp64 block scores, and accepted
+only if every level is a correct top-k up to a relative score gap of 1e-3 (fp32 accumulation
+on the GPU): the kept branches are children of the previous level's nodes, as many as the
+listing keeps, and no dropped valid branch beats a kept one by more than the tolerance.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+from oracle import stream_oracle as so
+
+TIE_RTOL = 1e-3
+
+
+def certify_row(Qh, Kh, block, k, q, trace_row):
+    """trace_row: int array [levels, k, 2] of (f, l) kept after each GPU level (-1 = dead).
+    Returns (ok, reason)."""
+    T = Qh.shape[0]
+    N = -(-T // block)
+    nodes = [((j * N) // k, ((j + 1) * N) // k - 1) for j in range(k)]
+    nodes = [(f, l) for (f, l) in nodes if f <= l]
+    for lv in range(trace_row.shape[0]):
+        children = []
+        for (f, l) in nodes:
+            m = (f + l + 1) // 2
+            for (cf, cl) in ((f, m - 1), (m, l)):
+                if cf <= cl and cf <= q:
+                    children.append((cf, cl))
+        kept = [(int(f), int(l)) for f, l in trace_row[lv] if f >= 0]
+        if len(set(kept)) != len(kept) or kept != sorted(kept):
+            return False, f"level {lv}: kept nodes not distinct/ascending"
+        if not set(kept) <= set(children):
+            return False, f"level {lv}: kept a branch that is not a valid child"
+        if len(kept) != min(k, len(children)):
+            return False, f"level {lv}: kept {len(kept)} of {len(children)} valid, k={k}"
+        dropped = [c for c in children if c not in set(kept)]
+        if dropped:
+            s_keep = min(so.block_score(Qh, Kh, block, q, f) for f, _ in kept)
+            s_drop = max(so.block_score(Qh, Kh, block, q, f) for f, _ in dropped)
+            if s_keep < s_drop - TIE_RTOL * max(abs(s_drop), abs(s_keep)):
+                return False, f"level {lv}: dropped {s_drop} > kept {s_keep}"
+        nodes = kept
+    if any(f != l for f, l in nodes):
+        return False, "final nodes are not single blocks"
+    return True, ""
+
+
+def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None, rows=None):
+    """gpu: dict of numpy arrays idx [H,NB,kmax], cnt [H,NB], optional score, trace
+    [levels,H,NB,kmax,2].  ref: output of so.prune(...) for the same rows (or all).
+    Q, K: numpy float32 (exact input values).  Returns dict with counts; raises on failure."""
+    H = heads
+    g = heads // kv_heads
+    T = Q.shape[1]
+    cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
+    nseq = len(cu) - 1
+    ks = [int(topk)] * nseq if np.isscalar(topk) else [int(x) for x in topk]
+    bseq, bloc = so.block_table(cu, block)
+    NB = len(bseq)
+    if rows is None:
+        rows_arr = np.asarray([(h, gb) for h in range(H) for gb in range(NB)], dtype=np.int64)
+        ridx = ref["idx"].reshape(H * NB, -1)
+        rcnt = ref["cnt"].reshape(H * NB)
+        rscore = ref["score"].reshape(H * NB, -1)
+    else:
+        rows_arr = np.asarray(rows, dtype=np.int64).reshape(-1, 2)
+        ridx, rcnt, rscore = ref["idx"], ref["cnt"], ref["score"]
+    equal = ties = 0
+    for i, (h, gb) in enumerate(rows_arr):
+        s, q = int(bseq[gb]), int(bloc[gb])
+        k = ks[s]
+        gi, gc = gpu["idx"][h, gb], int(gpu["cnt"][h, gb])
+        assert gc == int(rcnt[i]) == min(k, q + 1), (h, gb, gc, int(rcnt[i]))
+        assert np.all(gi[gc:] == -1), (h, gb)
+        assert np.all(np.diff(gi[:gc]) > 0) and (gc == 0 or (gi[0] >= 0 and gi[gc - 1] <= q)), (h, gb)
+        Qh = Q[h, cu[s]:cu[s + 1]]
+        Kh = K[h // g, cu[s]:cu[s + 1]]
+        if np.array_equal(gi, ridx[i]):
+            equal += 1
+            if gpu.get("score") is not None:
+                gs = gpu["score"][h, gb]
+                np.testing.assert_allclose(gs[:gc], rscore[i, :gc], rtol=1e-4,
+                                           atol=1e-4 * float(np.abs(rscore[i, :gc]).max()))
+                assert np.all(np.isneginf(gs[gc:]))
+        else:
+            assert gpu.get("trace") is not None, f"row {(h, gb)} differs and no trace was taken"
+            tr = gpu["trace"][:, h, gb, :k, :]
+            n_eff = max(1, math.ceil(math.log2(math.ceil((-(-Qh.shape[0] // block)) / k))))
+            tr = tr[:n_eff]
+            ok, why = certify_row(Qh, Kh, block, k, q, tr)
+            assert ok, f"row (h={h}, block={gb}): {why}; gpu={gi[:gc]} oracle={ridx[i][:gc]}"
+            assert list(tr[-1][:gc, 0]) == list(gi[:gc])
+            ties += 1
+    return {"rows": len(rows_arr), "equal": equal, "tie_rows": ties}
+
+
+def sample_rows(w, n, seed=0, heads=None):
+    """Seeded sample of (head, global block) rows that always holds the edge rows of every sequence."""
+    rng = np.random.default_rng(seed)
+    heads = list(range(w.heads)) if heads is None else list(heads)
+    rows = set()
+    off = 0
+    for s, nb in enumerate(w.blocks_per_seq):
+        k = w.topk[s]
+        for q in {0, 1, k - 1, k, nb // 2, nb - 1}:
+            if 0 <= q < nb:
+                rows.add((heads[int(rng.integers(len(heads)))], off + q))
+        off += nb
+    NB = off
+    n = min(n, len(heads) * NB)
+    while len(rows) < n:
+        rows.add((heads[int(rng.integers(len(heads)))], int(rng.integers(NB))))
+    return sorted(rows)

@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_19875_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load()
+
+
+def shape(**kw):
+    s = B.StreamShape()
+    s.heads, s.kv_heads, s.head_dim, s.block, s.dtype, s.batch, s.T = 8, 2, 128, 64, B.STREAM_BF16, 1, 1000
+    for k, v in kw.items():
+        setattr(s, k, v)
+    return s
+
+
+def test_exports_every_declared_symbol(lib):
+    hdr = open(os.path.join(ROOT, "include", "stream.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(stream_[a-z_]+)\s*\(", hdr))
+    assert names == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings(lib):
+    for code in range(5):
+        assert lib.stream_status_str(code)
+    assert lib.stream_status_str(B.STREAM_OK) == b"ok"
+
+
+def test_block_geometry(lib):
+    assert lib.stream_num_blocks(ctypes.byref(shape())) == 16  # ceil(1000/64)
+    cu = (ctypes.c_int * 4)(0, 100, 164, 1000)
+    s = shape(batch=3, cu_seqlens=ctypes.cast(cu, ctypes.POINTER(ctypes.c_int)))
+    assert lib.stream_num_blocks(ctypes.byref(s)) == 2 + 1 + 14
+    # levels = max(1, ceil(log2(ceil(N/k))))
+    assert lib.stream_prune_levels(ctypes.byref(shape(T=131072)), 32, None) == 6
+    assert lib.stream_prune_levels(ctypes.byref(shape(T=1048576, block=128)), 64, None) == 7
+    assert lib.stream_prune_levels(ctypes.byref(shape(T=4096)), 8, None) == 3
+    assert lib.stream_prune_levels(ctypes.byref(shape(T=4096)), 64, None) == 1
+    ks = (ctypes.c_int * 3)(1, 1, 2)
+    assert lib.stream_prune_levels(ctypes.byref(s), 0, ks) == 3  # 14 blocks, k=2 -> ceil(log2 7)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(heads=0), B.STREAM_EINVAL),
+    (dict(kv_heads=3), B.STREAM_EINVAL),
+    (dict(T=0), B.STREAM_EINVAL),
+    (dict(dtype=7), B.STREAM_EINVAL),
+    (dict(batch=2), B.STREAM_EINVAL),            # batch > 1 without cu_seqlens
+    (dict(head_dim=96), B.STREAM_EUNSUPPORTED),
+    (dict(block=48), B.STREAM_EUNSUPPORTED),
+    (dict(batch=33), B.STREAM_EINVAL),
+])
+def test_bad_shapes_are_rejected_on_the_host(lib, kw, code):
+    s = shape(**kw)
+    assert lib.stream_num_blocks(ctypes.byref(s)) == -1
+    assert lib.stream_prune_workspace_bytes(ctypes.byref(s), 8) == 0
+    fake = ctypes.c_void_p(4096)
+    rc = lib.stream_prune(fake, fake, ctypes.byref(s), 8, None, 8, fake, fake, None, None,
+                          ctypes.c_void_p(256 * 16), 1 << 40, None)
+    assert rc == code
+    rc = lib.stream_sparse_attn(fake, fake, fake, ctypes.byref(s), fake, fake, 8, 1.0, fake, None,
+                                None, ctypes.c_void_p(256 * 16), 1 << 40, None)
+    assert rc == code
+
+
+def test_bad_arguments_of_prune(lib):
+    s = shape()
+    fake = ctypes.c_void_p(4096)
+    ws = ctypes.c_void_p(256 * 16)
+    need = lib.stream_prune_workspace_bytes(ctypes.byref(s), 8)
+    assert need > 0 and need % 256 == 0
+
+    def call(Q=fake, K=fake, topk=8, per=None, kmax=8, idx=fake, cnt=fake, wsp=ws, wsz=need, sh=s):
+        return lib.stream_prune(Q, K, ctypes.byref(sh), topk, per, kmax, idx, cnt, None, None, wsp, wsz, None)
+
+    assert call(Q=None) == B.STREAM_EINVAL
+    assert call(K=None) == B.STREAM_EINVAL
+    assert call(idx=None) == B.STREAM_EINVAL
+    assert call(cnt=None) == B.STREAM_EINVAL
+    assert call(topk=0) == B.STREAM_EINVAL
+    assert call(topk=9, kmax=8) == B.STREAM_EINVAL          # k beyond the row length of idx
+    assert call(topk=65, kmax=65) == B.STREAM_EUNSUPPORTED  # more than one node per lane
+    assert call(Q=ctypes.c_void_p(4100)) == B.STREAM_EINVAL  # not 16-byte aligned
+    assert call(sh=shape(q_stride_t=100)) == B.STREAM_EINVAL  # rows shorter than head_dim
+    assert call(sh=shape(q_stride_t=132)) == B.STREAM_EINVAL  # rows not 16-byte aligned
+    assert call(wsp=None) == B.STREAM_EWORKSPACE
+    assert call(wsp=ctypes.c_void_p(4096 + 64)) == B.STREAM_EWORKSPACE
+    assert call(wsz=need - 1) == B.STREAM_EWORKSPACE
+    cu = (ctypes.c_int * 3)(0, 600, 900)  # does not end at T
+    bad = shape(batch=2, cu_seqlens=ctypes.cast(cu, ctypes.POINTER(ctypes.c_int)))
+    assert call(sh=bad) == B.STREAM_EINVAL
+
+
+def test_bad_arguments_of_sparse_attn(lib):
+    s = shape()
+    fake = ctypes.c_void_p(4096)
+    ws = ctypes.c_void_p(256 * 16)
+    need = lib.stream_sparse_attn_workspace_bytes(ctypes.byref(s), 8)
+    assert need > 0
+
+    def call(Q=fake, V=fake, idx=fake, O=fake, kmax=8, scale=1.0, wsz=need):
+        return lib.stream_sparse_attn(Q, fake, V, ctypes.byref(s), idx, fake, kmax, scale, O, None,
+                                      None, ws, wsz, None)
+
+    assert call(Q=None) == B.STREAM_EINVAL
+    assert call(V=None) == B.STREAM_EINVAL
+    assert call(idx=None) == B.STREAM_EINVAL
+    assert call(O=None) == B.STREAM_EINVAL
+    assert call(kmax=0) == B.STREAM_EINVAL
+    assert call(scale=0.0) == B.STREAM_EINVAL
+    assert call(scale=float("nan")) == B.STREAM_EINVAL
+    assert call(wsz=need - 1) == B.STREAM_EWORKSPACE
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    Q = torch.zeros(2, 64, 64)
+    with pytest.raises(ValueError):
+        B.stream_prune(Q, Q, 2, 2, 64, 1)

@@ -1,0 +1,95 @@
+"""GPU parity of stream_sparse_attn against the CPU oracle (through the C ABI)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import stream_oracle as so
+from paper_2510_19875_amd import binding, workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 1e-4}
+
+
+def run_case(w, rows=None, full_mask=False):
+    print(f"[attn] {w.name} T={w.T} H={w.heads}/{w.kv_heads} d={w.head_dim} {w.dtype} b={w.block} "
+          f"k={w.topk}", flush=True)
+    dev = torch.device("cuda:0")
+    Q, K, V, meta = wl.make_inputs(w)
+    cu = w.cu_seqlens if w.batch > 1 else None
+    topk = list(w.topk) if w.batch > 1 else w.topk[0]
+    Qf, Kf, Vf = Q.float().numpy(), K.float().numpy(), V.float().numpy()
+    ref_p = so.prune(Qf, Kf, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    # the oracle's lists feed the GPU attention, so near-ties of the prune cannot leak in here
+    idx_t = torch.from_numpy(ref_p["idx"]).to(dev)
+    cnt_t = torch.from_numpy(ref_p["cnt"]).to(dev)
+    out = binding.stream_sparse_attn(Q.to(dev), K.to(dev), V.to(dev), w.heads, w.kv_heads, w.block,
+                                     idx_t, cnt_t, scale, cu_seqlens=cu, want_lse=True, want_mass=True)
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Qf, Kf, Vf, w.heads, w.kv_heads, w.block, ref_p["idx"], ref_p["cnt"], scale,
+                         cu_seqlens=cu)
+    O = out["O"].float().cpu().numpy()
+    err = np.abs(O - ref["O"]).max()
+    lerr = np.abs(out["lse"].cpu().numpy() - ref["lse"]).max()
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    merr = (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max()
+    print(f"[attn] max|dO|={err:.3e} max|dlse|={lerr:.3e} mass rel err={merr:.3e}", flush=True)
+    assert err <= TOL[w.dtype]
+    assert lerr <= 1e-3
+    assert merr <= 1e-3
+    np.testing.assert_allclose(mass.sum(axis=1), w.T, rtol=1e-4)   # every real row of P sums to 1
+    return out, ref, meta
+
+
+def test_config1_full_fp32_sink_dominates():
+    w = wl.config(1)
+    out, ref, meta = run_case(w)
+    mass = out["mass"].cpu().numpy()
+    assert np.all(mass[:, 0] >= 0.5 * mass.max(axis=1))   # the sink column is (about) the largest
+
+
+@pytest.mark.parametrize("block,k,T,dtype,d,H,Hkv", [
+    (64, 8, 4096 + 37, "bf16", 128, 8, 2),
+    (128, 4, 4096 + 100, "bf16", 128, 4, 2),
+    (32, 8, 2048 + 5, "bf16", 128, 4, 2),
+    (64, 8, 3000, "bf16", 64, 4, 4),
+    (64, 4, 1500, "f32", 128, 2, 1),
+    (32, 3, 1000, "f32", 64, 2, 2),
+    (128, 5, 3000, "f32", 64, 2, 1),
+    (64, 64, 64 * 40, "bf16", 128, 2, 1),   # k >= N: dense causal attention
+])
+def test_shapes(block, k, T, dtype, d, H, Hkv):
+    w = wl.scaled(wl.config(2), (T,), topk=k, heads=H, kv_heads=Hkv, block=block, dtype=dtype,
+                  head_dim=d, needles_per_kv_head=2)
+    run_case(w)
+
+
+def test_ragged_anchor_batch():
+    w = wl.scaled(wl.config(5), (700, 1300, 64, 33, 2049), topk=(2, 3, 1, 4, 2), heads=14, kv_heads=2,
+                  anchors_per_seq=3)
+    out, ref, meta = run_case(w)
+    # anchors collect far more attention than a typical key
+    mass = out["mass"].cpu().numpy()
+    cu = w.cu_seqlens
+    for s in (1, 4):
+        a = [cu[s] + t for t in meta["anchors"][s]]
+        assert np.median(mass[:, a]) > 5 * np.median(mass[:, cu[s]:cu[s + 1]])
+
+
+def test_full_mask_equals_torch_causal_attention_on_gpu():
+    """k >= N: Eq. (2) with the full causal mask is ordinary causal attention."""
+    w = wl.scaled(wl.config(2), (2048,), topk=32, heads=4, kv_heads=2, needles_per_kv_head=0)
+    dev = torch.device("cuda:0")
+    Q, K, V, _ = wl.make_inputs(w)
+    Qd, Kd, Vd = Q.to(dev), K.to(dev), V.to(dev)
+    p = binding.stream_prune(Qd, Kd, w.heads, w.kv_heads, w.block, 32)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    a = binding.stream_sparse_attn(Qd, Kd, Vd, w.heads, w.kv_heads, w.block, p["idx"], p["cnt"], scale)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        Q.double()[None], K.double().repeat_interleave(2, 0)[None], V.double().repeat_interleave(2, 0)[None],
+        is_causal=True)[0]
+    assert (a["O"].double().cpu() - ref).abs().max() <= 2e-2

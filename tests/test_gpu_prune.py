@@ -1,0 +1,150 @@
+"""GPU parity of stream_prune against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stream_oracle as so
+from paper_2510_19875_amd import binding, workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(w, rows=None, n_rows=None, seed=0, heads_for_sample=None):
+    print(f"[case] {w.name} T={w.T} H={w.heads}/{w.kv_heads} d={w.head_dim} {w.dtype} b={w.block} "
+          f"k={w.topk}", flush=True)
+    dev = torch.device("cuda:0")
+    Q, K, _, meta = wl.make_inputs(w, with_v=False)
+    cu = w.cu_seqlens if w.batch > 1 else None
+    topk = list(w.topk) if w.batch > 1 else w.topk[0]
+    out = binding.stream_prune(Q.to(dev), K.to(dev), w.heads, w.kv_heads, w.block, topk,
+                               cu_seqlens=cu, want_score=True, want_trace=True, want_tiles=True)
+    torch.cuda.synchronize()
+    gpu = {k: out[k].cpu().numpy() for k in ("idx", "cnt", "score", "trace")}
+    Qf, Kf = Q.float().numpy(), K.float().numpy()
+    if rows is None and n_rows is not None:
+        rows = parity.sample_rows(w, n_rows, seed=seed, heads=heads_for_sample)
+    ref = so.prune(Qf, Kf, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu, rows=rows)
+    res = parity.compare_prune(gpu, ref, Qf, Kf, w.heads, w.kv_heads, w.block, topk,
+                               cu_seqlens=cu, rows=rows)
+    print(f"[case] rows={res['rows']} equal={res['equal']} tie_rows={res['tie_rows']} "
+          f"tiles={int(out['tiles'].item())} oracle_new_evals={int(ref['evals'][1])}", flush=True)
+    # the kernels compute exactly the evaluations that cannot be inherited
+    # (a single-block sequence has n_it = 0 in the listing: the oracle scores nothing there)
+    if rows is None and res["tie_rows"] == 0 and min(w.blocks_per_seq) > 1:
+        assert int(out["tiles"].item()) == int(ref["evals"][1])
+    # all but a few rows are bit-equal; the rest are certified ties
+    assert res["tie_rows"] <= max(2, res["rows"] // 100)
+    return gpu, ref, meta, res
+
+
+def test_config1_full_fp32():
+    w = wl.config(1)
+    gpu, ref, meta, res = run_case(w)
+    # (with the rotating diagonal bias of this workload the sink only wins for queries in phase
+    # with token 0, so its retention is data, not law; the Gaussian workloads assert it)
+    # needles sit in blocks that are representatives at every level (multiples of N/k)
+    for nd in meta["needles"]:
+        qb, nb = nd["t_q"] // w.block, nd["t_n"] // w.block
+        assert nb in gpu["idx"][nd["head"], qb], nd
+
+
+def test_config2_shape_small_gqa_ragged_tail():
+    w = wl.scaled(wl.config(2), (8192 + 37,), topk=16, heads=8, kv_heads=2, needles_per_kv_head=4)
+    gpu, ref, meta, res = run_case(w, n_rows=300)
+    assert np.all(gpu["idx"][:, :, 0] == 0)
+
+
+@pytest.mark.parametrize("block,k,T,dtype,d", [
+    (128, 4, 4096 + 100, "bf16", 128),
+    (128, 64, 128 * 160 + 1, "bf16", 128),
+    (32, 8, 2048 + 5, "bf16", 128),
+    (64, 8, 3000, "bf16", 64),
+    (64, 4, 2500, "f32", 128),
+    (32, 3, 1000, "f32", 64),
+    (128, 5, 3000, "f32", 64),
+])
+def test_block_sizes_and_dtypes(block, k, T, dtype, d):
+    w = wl.scaled(wl.config(2), (T,), topk=k, heads=4, kv_heads=2, block=block, dtype=dtype,
+                  head_dim=d, needles_per_kv_head=2)
+    run_case(w, n_rows=120)
+
+
+@pytest.mark.parametrize("k,T", [(1, 4096), (64, 64 * 300), (7, 64 * 50 + 1), (16, 64 * 16), (40, 64 * 30), (3, 1)])
+def test_topk_edges(k, T):
+    """k = 1, the largest k, k not dividing N, N <= k (full causal mask), a single token."""
+    w = wl.scaled(wl.config(2), (T,), topk=k, heads=2, kv_heads=1, needles_per_kv_head=0)
+    gpu, ref, meta, res = run_case(w, n_rows=100 if T > 4096 else None)
+    N = w.total_blocks
+    if k >= N:
+        for q in range(N):
+            assert list(gpu["idx"][0, q, :q + 1]) == list(range(q + 1))
+
+
+def test_ragged_batch_with_group_of_seven():
+    w = wl.scaled(wl.config(5), (700, 1300, 64, 33, 2049), topk=(2, 3, 1, 4, 2), heads=14, kv_heads=2,
+                  anchors_per_seq=3)
+    run_case(w)
+
+
+def test_strided_inputs():
+    """Token-major [T, H, d] storage viewed as [H, T, d]."""
+    w = wl.scaled(wl.config(2), (2048 + 11,), topk=4, heads=4, kv_heads=2, needles_per_kv_head=0)
+    dev = torch.device("cuda:0")
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    Qs = Q.to(dev).transpose(0, 1).contiguous().transpose(0, 1)
+    Ks = K.to(dev).transpose(0, 1).contiguous().transpose(0, 1)
+    assert not Qs.is_contiguous()
+    a = binding.stream_prune(Q.to(dev), K.to(dev), w.heads, w.kv_heads, w.block, 4)
+    b = binding.stream_prune(Qs, Ks, w.heads, w.kv_heads, w.block, 4)
+    assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["cnt"], b["cnt"])
+
+
+def test_deterministic_and_stream_ordered():
+    w = wl.scaled(wl.config(2), (4096,), topk=8, heads=8, kv_heads=2)
+    dev = torch.device("cuda:0")
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    Qd, Kd = Q.to(dev), K.to(dev)
+    a = binding.stream_prune(Qd, Kd, w.heads, w.kv_heads, w.block, 8, want_score=True)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        b = binding.stream_prune(Qd, Kd, w.heads, w.kv_heads, w.block, 8, want_score=True)
+    st.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["score"], b["score"])
+
+
+def test_config3_full_size_sampled_rows():
+    """The headline shape (T = 131072, 32/8 heads, k = 32), as the bench launches it."""
+    w = wl.config(3)
+    dev = torch.device("cuda:0")
+    Q, K, _, _ = wl.make_inputs(w, device=dev, with_v=False)
+    out = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, w.topk[0], want_score=True,
+                               want_trace=True, want_tiles=True)
+    torch.cuda.synchronize()
+    cnt = out["cnt"].cpu().numpy()
+    N, k = w.total_blocks, w.topk[0]
+    assert np.array_equal(cnt, np.broadcast_to(np.minimum(k, np.arange(N) + 1), cnt.shape))
+    idx = out["idx"]
+    assert bool((idx[:, :, 0] == 0).all())                       # sink kept in every row
+    qq = torch.arange(N, device=dev)[None, :, None]
+    assert bool(((idx <= qq) & ((idx >= 0) | (torch.arange(k, device=dev)[None, None, :] >= out["cnt"][:, :, None]))).all())
+    heads = [0, 13, 31]
+    rows = parity.sample_rows(w, 48, seed=3, heads=heads)
+    Qf = np.zeros((w.heads, 1, 1), np.float32)
+    Qfull = {h: Q[h].float().cpu().numpy() for h in heads}
+    Kfull = {h // 4: K[h // 4].float().cpu().numpy() for h in heads}
+    gpu = {"idx": idx.cpu().numpy(), "cnt": cnt, "score": out["score"].cpu().numpy(),
+           "trace": out["trace"].cpu().numpy()}
+    equal = ties = 0
+    for (h, gb) in rows:
+        r = so.prune_head(Qfull[h], Kfull[h // 4], w.block, k, qblocks=[gb])
+        if np.array_equal(r["idx"][0], gpu["idx"][h, gb]):
+            equal += 1
+            np.testing.assert_allclose(gpu["score"][h, gb, :r["cnt"][0]], r["score"][0, :r["cnt"][0]], rtol=1e-4)
+        else:
+            ok, why = parity.certify_row(Qfull[h], Kfull[h // 4], w.block, k, gb, gpu["trace"][:, h, gb])
+            assert ok, (h, gb, why)
+            ties += 1
+    print(f"[cfg3] sampled rows={len(rows)} equal={equal} ties={ties} tiles={int(out['tiles'].item())}", flush=True)
+    assert ties <= 2
