@@ -1,0 +1,247 @@
+"""Benchmark of the Stream hot path on one MI355X.
+
+One step = one pass of the whole path over one layer's synthetic Q, K, V at the headline
+workload (T = 131072, 32 query / 8 KV heads, head_dim 128, bf16, block 64, top-k 32):
+stream_prune (K tile packing + the refinement levels, fused select/compaction/emit) followed by
+stream_sparse_attn with the received-mass read-out.  Layers are independently seeded and
+resident in HBM before the timed region; consecutive steps walk through them.
+
+Prints ONE JSON line: whole-path throughput in query-tokens x heads per second, the roofline of
+the dominant kernel (the level scorer: algorithmic FLOP of the block scores it had to compute /
+its launch time, measured with HIP events recorded on the launch stream inside the timed
+region, against the dense bf16 MFMA peak), and the CPU oracle timed on a bounded row sample.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0
+# HBM bytes per level-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
+# copy kernel of known size (profiles/level_kernel_cfg3_pmc.txt); None until measured.
+LEVEL_KERNEL_HBM_BYTES = None
+
+
+class HipEvents:
+    """hipEvent_t handles for the per-level timing hooks of stream_prune (plumbing only)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.arr = (ctypes.c_void_p * n)()
+        for i in range(n):
+            ev = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(ev))
+            assert rc == 0, f"hipEventCreate -> {rc}"
+            self.arr[i] = ev
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(self.arr[a]),
+                                          ctypes.c_void_p(self.arr[b]))
+        assert rc == 0, f"hipEventElapsedTime -> {rc}"
+        return ms.value
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="named workload (default: the headline one)")
+    ap.add_argument("--layers", type=int, default=0, help="resident input layers (default min(steps, 32))")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=96)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding code); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2510_19875_amd import binding, workloads as wl
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = wl.config(args.config)
+    if w.batch != 1:
+        cu, topk = w.cu_seqlens, list(w.topk)
+    else:
+        cu, topk = None, w.topk[0]
+    H, Hkv, b, d, T = w.heads, w.kv_heads, w.block, w.head_dim, w.T
+    kmax = w.topk_max
+    scale = 1.0 / math.sqrt(d)
+    n_layers = args.layers or max(1, min(args.steps, 32))
+    layers = [wl.make_inputs(w.with_layer(i), device=dev)[:3] for i in range(n_layers)]
+    torch.cuda.synchronize()
+
+    NB = w.total_blocks
+    out_p = {"idx": torch.empty((H, NB, kmax), dtype=torch.int32, device=dev),
+             "cnt": torch.empty((H, NB), dtype=torch.int32, device=dev),
+             "score": torch.empty((H, NB, kmax), dtype=torch.float32, device=dev)}
+    out_a = {"O": torch.empty((H, T, d), dtype=w.torch_dtype, device=dev),
+             "lse": torch.empty((H, T), dtype=torch.float32, device=dev),
+             "mass": torch.empty((H, T), dtype=torch.float32, device=dev)}
+    ws_p = ws_a = None
+    tiles = torch.zeros((1,), dtype=torch.int64, device=dev)
+
+    def step(i, events=None, count_tiles=False):
+        nonlocal ws_p, ws_a
+        Q, K, V = layers[i % n_layers]
+        r = binding.stream_prune(Q, K, H, Hkv, b, topk, cu_seqlens=cu, want_score=True,
+                                 workspace=ws_p, out=out_p, level_events=events,
+                                 want_tiles=count_tiles)
+        ws_p = r["workspace"]
+        a = binding.stream_sparse_attn(Q, K, V, H, Hkv, b, out_p["idx"], out_p["cnt"], scale,
+                                       cu_seqlens=cu, want_lse=True, want_mass=True,
+                                       workspace=ws_a, out=out_a)
+        ws_a = a["workspace"]
+        return r
+
+    levels = None
+    for i in range(args.warmup):
+        r = step(i)
+        levels = r["levels"]
+    if levels is None:
+        levels = step(0)["levels"]
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+
+    # algorithmic work: block scores the path has to compute (those no parent score supplies),
+    # counted by the kernels themselves on one untimed pass per resident layer
+    tile_counts = []
+    for i in range(n_layers):
+        r = step(i, count_tiles=True)
+        torch.cuda.synchronize()
+        tile_counts.append(int(r["tiles"].item()))
+
+    K_steps = args.steps
+    ev = HipEvents(2 * levels * K_steps)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(2 * K_steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K_steps):
+        Q, K, V = layers[i % n_layers]
+        sub = ctypes.cast(ctypes.byref(ev.arr, 2 * levels * i * ctypes.sizeof(ctypes.c_void_p)),
+                          ctypes.POINTER(ctypes.c_void_p * (2 * levels))).contents
+        marks[2 * i].record()
+        r = binding.stream_prune(Q, K, H, Hkv, b, topk, cu_seqlens=cu, want_score=True,
+                                 workspace=ws_p, out=out_p, level_events=sub)
+        marks[2 * i + 1].record()
+        binding.stream_sparse_attn(Q, K, V, H, Hkv, b, out_p["idx"], out_p["cnt"], scale,
+                                   cu_seqlens=cu, want_lse=True, want_mass=True,
+                                   workspace=ws_a, out=out_a)
+    marks[2 * K_steps].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    total_s = t1 - t0
+    ms_per_step = total_s * 1e3 / K_steps
+    prune_ms = [marks[2 * i].elapsed_time(marks[2 * i + 1]) for i in range(K_steps)]
+    attn_ms = [marks[2 * i + 1].elapsed_time(marks[2 * i + 2]) for i in range(K_steps)]
+    level_ms = np.array([[ev.elapsed_ms(2 * levels * i + 2 * l, 2 * levels * i + 2 * l + 1)
+                          for l in range(levels)] for i in range(K_steps)])
+    tok_heads = float(T) * H
+    value = tok_heads / (ms_per_step * 1e-3)
+
+    tile_flop = 2.0 * b * b * d
+    flops_per_step = np.array([tile_counts[i % n_layers] for i in range(K_steps)]) * tile_flop
+    level_total_s = level_ms.sum() * 1e-3
+    launches = levels * K_steps
+    achieved_tflops = flops_per_step.sum() / level_total_s / 1e12
+    peak_mem = torch.cuda.max_memory_allocated()
+    tensor_bytes = sum(t.numel() * t.element_size() for t in layers[0]) + \
+        sum(t.numel() * t.element_size() for t in list(out_p.values()) + list(out_a.values()))
+
+    result = {
+        "metric": "query-tokens·heads/s pruned at T=131k bf16 GQA; % MFMA / HBM peak",
+        "value": value,
+        "unit": "query-tokens*heads/s",
+        "n_gpus": 1,
+        "steps": K_steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "T": T, "heads": H, "kv_heads": Hkv, "head_dim": d,
+                   "block": b, "topk": kmax, "resident_layers": n_layers,
+                   "step": "stream_prune + stream_sparse_attn (O, lse, mass)"},
+        "prune_ms": float(np.mean(prune_ms)),
+        "attn_ms": float(np.mean(attn_ms)),
+        "prune_only_value": tok_heads / (float(np.mean(prune_ms)) * 1e-3),
+        "level_kernel_ms": [float(x) for x in level_ms.mean(axis=0)],
+        "tiles_scored_per_step": float(np.mean(tile_counts)),
+        "peak_device_bytes": int(peak_mem),
+        "workspace_plus_state_bytes": int(ws_p.numel() + ws_a.numel()),
+        "tensor_bytes_one_layer": int(tensor_bytes),
+        "roofline": {
+            "kernel": "level_kernel (branch scorer + top-k select + in-place compaction)",
+            "bound": "mfma",
+            "achieved": achieved_tflops,
+            "peak": PEAK_BF16_MFMA_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
+            "flop_per_launch": float(flops_per_step.sum() / launches),
+            "avg_launch_ms": float(level_ms.sum() / launches),
+            "launches": launches,
+            "traffic": LEVEL_KERNEL_HBM_BYTES,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, layer, n_rows, scale):
+    """The oracle as it stands (fp64, OpenMP over rows), timed on a seeded row sample of the same
+    workload: prune + attention of those rows.  A reported baseline, not a target."""
+    import numpy as np
+
+    from oracle import stream_oracle as so
+
+    Q, K, V = layer
+    rng = np.random.default_rng(12345)
+    NB = w.total_blocks
+    heads = sorted(set(int(x) for x in rng.integers(0, w.heads, size=3)))
+    rows = sorted(set((heads[int(rng.integers(len(heads)))], int(rng.integers(NB))) for _ in range(n_rows)))
+    g = w.heads // w.kv_heads
+    Qh = {h: Q[h].float().cpu().numpy() for h in heads}
+    Kh = {h // g: K[h // g].float().cpu().numpy() for h in heads}
+    Vh = {h // g: V[h // g].float().cpu().numpy() for h in heads}
+    cu = w.cu_seqlens
+    bseq, bloc = so.block_table(cu, w.block)
+    t0 = time.perf_counter()
+    tokens = 0
+    for h in heads:
+        for s in range(w.batch):
+            ql = [int(bloc[gb]) for (hh, gb) in rows if hh == h and bseq[gb] == s]
+            if not ql:
+                continue
+            a, e = cu[s], cu[s + 1]
+            p = so.prune_head(Qh[h][a:e], Kh[h // g][a:e], w.block, w.topk[s], qblocks=ql)
+            so.sparse_attn(Qh[h][None, a:e], Kh[h // g][None, a:e], Vh[h // g][None, a:e], 1, 1, w.block,
+                           p["idx"], p["cnt"], scale, rows=[(0, qb) for qb in ql])
+            tokens += sum(min(w.block, (e - a) - qb * w.block) for qb in ql)
+    dt = time.perf_counter() - t0
+    return {"value": tokens / dt, "unit": "query-tokens*heads/s", "cores": so.threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"{len(rows)} seeded (head, query block) rows of {w.name}: Alg. 2 as printed "
+                      f"(n_it levels, no score reuse) + Eq. (2) on the retained blocks, fp64"}
+
+
+if __name__ == "__main__":
+    main()

@@ -69,7 +69,7 @@ typedef struct {
     long long o_stride_h, o_stride_t; /* stream_sparse_attn only                        */
 } stream_shape;
 
-/* Optional diagnostics of stream_prune (all device pointers, each may be NULL). */
+/* Optional diagnostics of stream_prune (each member may be NULL). */
 typedef struct {
     /* (f, l) of the nodes kept after every level, int32 [levels, heads, NB, topk_max, 2],
        -1 where a slot holds no live node; `levels` = stream_prune_levels().  Lets a checker
@@ -79,6 +79,11 @@ typedef struct {
     /* unsigned 64-bit counter, incremented by the number of block scores (b x b x d tile
        products) the kernels computed; the caller zeroes it.                                 */
     unsigned long long *tiles_scored;
+    /* HOST array of 2 * stream_prune_levels() hipEvent_t handles created by the caller, or NULL:
+       event 2i is recorded on hip_stream right before the launch of level i+1's kernel and event
+       2i+1 right after it, so the caller can read each level kernel's duration after its own
+       synchronisation.  Nothing is waited on.                                                  */
+    void *const *level_events;
 } stream_prune_diag;
 
 /* NB = total number of query blocks of the (packed) shape, or -1 on a bad shape. */

@@ -72,6 +72,13 @@ def _ptr(a, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
 
 
+def threads() -> int:
+    """Host threads the oracle's row loops use."""
+    lib = _load()
+    lib.stream_oracle_threads.restype = ctypes.c_int
+    return int(lib.stream_oracle_threads())
+
+
 def n_it(T: int, block: int) -> int:
     """n_it = ceil(log2(T_p / b_k)) (iteration count line of Alg. 2)."""
     return int(_load().stream_oracle_n_it(int(T), int(block)))

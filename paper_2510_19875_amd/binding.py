@@ -34,7 +34,8 @@ class StreamShape(ctypes.Structure):
 
 
 class StreamPruneDiag(ctypes.Structure):
-    _fields_ = [("trace", ctypes.c_void_p), ("tiles_scored", ctypes.c_void_p)]
+    _fields_ = [("trace", ctypes.c_void_p), ("tiles_scored", ctypes.c_void_p),
+                ("level_events", ctypes.POINTER(ctypes.c_void_p))]
 
 
 class StreamError(RuntimeError):
@@ -119,7 +120,8 @@ def num_blocks(shape: StreamShape) -> int:
 
 def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
                  topk, cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
-                 want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None):
+                 want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None,
+                 level_events=None):
     """Algorithm 2 for every (head, query block).  Q [H, T, d], K [Hkv, T, d] on the GPU.
 
     topk: int, or one int per sequence.  Returns dict(idx [H, NB, kmax] int32, cnt [H, NB] int32,
@@ -160,10 +162,14 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
     if want_tiles:
         tiles = torch.zeros((1,), dtype=torch.int64, device=dev)
         diag.tiles_scored = tiles.data_ptr()
+    if level_events is not None:
+        if len(level_events) < 2 * levels:
+            raise ValueError("level_events needs 2 events per level")
+        diag.level_events = ctypes.cast(level_events, ctypes.POINTER(ctypes.c_void_p))
     rc = lib.stream_prune(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape),
                           kmax if ks is None else 0, k_arr, kmax,
                           idx.data_ptr(), cnt.data_ptr(), score.data_ptr() if score is not None else None,
-                          ctypes.byref(diag) if (want_trace or want_tiles) else None,
+                          ctypes.byref(diag) if (want_trace or want_tiles or level_events is not None) else None,
                           workspace.data_ptr(), workspace.numel(), _stream_ptr())
     if rc != STREAM_OK:
         raise StreamError(rc, "stream_prune")

@@ -395,8 +395,11 @@ stream_status stream_prune(const void *Q, const void *K, const stream_shape *sha
     const long long rows = (long long)pb.H * pb.NB;
     for (int level = 1; level <= pb.max_levels; ++level) {
         p.level = level;
+        void *const *ev = diag ? diag->level_events : nullptr;
+        if (ev && hipEventRecord((hipEvent_t)ev[2 * (level - 1)], st) != hipSuccess) return STREAM_EDEVICE;
         hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
         if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+        if (ev && hipEventRecord((hipEvent_t)ev[2 * (level - 1) + 1], st) != hipSuccess) return STREAM_EDEVICE;
         if (diag && diag->trace) {
             const long long n = rows * pb.kmax;
             hipLaunchKernelGGL(trace_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
