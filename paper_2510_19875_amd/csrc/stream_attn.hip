@@ -95,6 +95,8 @@ struct AttnParams {
     SeqTable seqs;
 };
 
+typedef float floatx8 __attribute__((ext_vector_type(8)));
+
 template <bool BF16>
 __device__ __forceinline__ floatx16 mfma16(const uint4 &a, const uint4 &b, floatx16 c)
 {
@@ -114,16 +116,29 @@ __device__ __forceinline__ floatx16 mfma16(const uint4 &a, const uint4 &b, float
 // an ext_vector_type lvalue reads element 0 whatever the index, with this compiler.)
 __device__ __forceinline__ unsigned f2u(float v) { return __builtin_bit_cast(unsigned, v); }
 
+// Eight probabilities -> one bf16 B-operand fragment (round to nearest even, v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint4 to_bf16_frag(float a, float b, float c, float d, float e, float f,
+                                               float g, float h)
+{
+    floatx8 t = {a, b, c, d, e, f, g, h};
+    return __builtin_bit_cast(uint4, __builtin_convertvector(t, bf16x8));
+}
+
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
 {
-    // round-to-nearest-even conversion of two floats to bf16 (finite inputs in [0, 1])
-    unsigned a = __builtin_bit_cast(unsigned, lo), b = __builtin_bit_cast(unsigned, hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    floatx2 t = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
 }
 
 // NQ: 32-query groups per wavefront, NK: 32-key groups per key sub-tile, B: block size.
+//
+// Software pipeline of pass 1, per key sub-tile t (the K fragments of t are already in registers):
+//   issue the V fragment loads of t  ->  S^T = K Q^T, refilling each K fragment's registers with
+//   sub-tile t+1 as soon as its last MFMA is issued  ->  softmax update  ->  O^T += V^T P^T.
+// Loads return in issue order, so V(t) is complete before K(t+1) and each wait is a count of
+// younger loads still allowed in flight.
 template <bool BF16, int D, int NQ, int NK, int B, int OCC>
 __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 {
@@ -140,7 +155,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     __shared__ float s_lse[4][QT];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keep it scalar
     const int col = lane & 31, gh = lane >> 5;
     int kvh, slot;
     if (!wg_decode(p.map, blockIdx.x, kvh, slot)) return;
@@ -160,6 +175,20 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     const int n_blk = p.cnt[row];
     const int *my_idx = p.idx + row * p.kmax;
 
+    // key sub-tiles to visit: all of every listed block, except that sub-tiles of the diagonal
+    // block lying entirely after this wavefront's queries are dropped (lists are ascending, so the
+    // diagonal block, if present, is the last one)
+    int n_tiles = n_blk * KSUB;
+    if (n_blk > 0) {
+        const int last_r = my_idx[n_blk - 1];
+        if (last_r * B + (KSUB - 1) * KT > qtok0 + QT - 1) {
+            int vis = (qtok0 + QT - 1 - last_r * B) / KT + 1;
+            vis = vis < 0 ? 0 : (vis > KSUB ? KSUB : vis);
+            n_tiles = (n_blk - 1) * KSUB + vis;
+        }
+    }
+    n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
+
     // Q fragments (usable as A or B operand): lane (col, gh), fragment fr -> chunk 2*fr+gh of row col
     uint4 qf[NQ][FR];
 #pragma unroll
@@ -174,8 +203,21 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
             qf[cq][fr] = v;
         }
     }
-    const char *kbase = p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES + lane * 16;
-    const char *vbase = p.Vp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES + lane * 16;
+    // packed K and V tiles of this (kv head, sequence)
+    const unsigned region_bytes = (unsigned)((long long)sd.nblk * TILE_BYTES);
+    const __amdgpu_buffer_rsrc_t krs =
+        make_tile_rsrc(p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES, region_bytes);
+    const __amdgpu_buffer_rsrc_t vrs =
+        make_tile_rsrc(p.Vp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES, region_bytes);
+    const unsigned lane_off = lane * 16;
+    auto tile_off = [&](int t) -> unsigned {
+        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
+        return (unsigned)r * (unsigned)TILE_BYTES + (unsigned)(t % KSUB) * NK * GROUP_BYTES;
+    };
+    auto tile_ktok0 = [&](int t) -> int {
+        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
+        return r * B + (t % KSUB) * KT;
+    };
 
     floatx16 acc_o[NDB][NQ];
 #pragma unroll
@@ -187,16 +229,33 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     float m_run[NQ], l_run[NQ];
 #pragma unroll
     for (int cq = 0; cq < NQ; ++cq) { m_run[cq] = -INFINITY; l_run[cq] = 0.f; }
+    const float c2 = p.scale_log2e;
 
-    const int n_tiles = n_blk * KSUB;
+    uint4 kreg[NK][FR];
+    if (n_tiles > 0) {
+        const unsigned off0 = tile_off(0);
+        // same order as the refills inside the loop: waits count loads in issue order
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb) {
+                kreg[rb][fr] = load_frag(krs, lane_off, off0, rb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
     // ------------------------------------------------------------------ pass 1: O and lse
     for (int t = 0; t < n_tiles; ++t) {
-        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
-        const int ks = t % KSUB;
-        const int ktok0 = r * B + ks * KT;
-        if (ktok0 > qtok0 + QT - 1) continue;             // sub-tile entirely in the future
-        const char *ksrc = kbase + (long long)r * TILE_BYTES + (long long)ks * NK * GROUP_BYTES;
-        const char *vsrc = vbase + (long long)r * TILE_BYTES + (long long)ks * NK * GROUP_BYTES;
+        const unsigned off = tile_off(t);
+        const int ktok0 = tile_ktok0(t);
+        const unsigned knext = tile_off(t + 1 < n_tiles ? t + 1 : t);
+        uint4 vreg[NK][NDB * NVF];
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int j = 0; j < NDB * NVF; ++j)
+                vreg[rb][j] = load_frag(vrs, lane_off, off, rb * NDB * NVF + j);
+        __builtin_amdgcn_sched_barrier(0);
+
         floatx16 acc_s[NK][NQ];
 #pragma unroll
         for (int rb = 0; rb < NK; ++rb)
@@ -208,28 +267,30 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         for (int fr = 0; fr < FR; ++fr)
 #pragma unroll
             for (int rb = 0; rb < NK; ++rb) {
-                const uint4 kf = *reinterpret_cast<const uint4 *>(ksrc + (rb * FR + fr) * 1024);
 #pragma unroll
                 for (int cq = 0; cq < NQ; ++cq)
-                    acc_s[rb][cq] = mfma16<BF16>(kf, qf[cq][fr], acc_s[rb][cq]);
+                    acc_s[rb][cq] = mfma16<BF16>(kreg[rb][fr], qf[cq][fr], acc_s[rb][cq]);
+                __builtin_amdgcn_sched_barrier(0);
+                kreg[rb][fr] = load_frag(krs, lane_off, knext, rb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
             }
-        // scale into base-2 logits; mask: causal inside the tile, padded keys
+        // mask (raw scores): causal inside the tile, padded keys
         const bool need_mask = (ktok0 + KT - 1 > qtok0) || (ktok0 + KT > L);
+        if (need_mask) {
 #pragma unroll
-        for (int rb = 0; rb < NK; ++rb)
+            for (int rb = 0; rb < NK; ++rb)
 #pragma unroll
-            for (int cq = 0; cq < NQ; ++cq)
+                for (int cq = 0; cq < NQ; ++cq)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float v = acc_s[rb][cq][i] * p.scale_log2e;
-                    if (need_mask) {
+                    for (int i = 0; i < 16; ++i) {
                         const int tk = ktok0 + rb * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
                         const int tq = qtok0 + cq * 32 + col;
-                        if (tk > tq || tk >= L) v = -INFINITY;
+                        if (tk > tq || tk >= L) acc_s[rb][cq][i] = -INFINITY;
                     }
-                    acc_s[rb][cq][i] = v;
-                }
-        // running softmax per query column
+        }
+        // running softmax per query column, in base 2: logit = raw * c2
+        float alpha[NQ];
+        bool grew = false;
 #pragma unroll
         for (int cq = 0; cq < NQ; ++cq) {
             float mx = -INFINITY;
@@ -237,25 +298,31 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
             for (int rb = 0; rb < NK; ++rb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[rb][cq][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
             const float m_new = fmaxf(m_run[cq], mx);
             const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = exp2f(m_run[cq] - m_use);
+            grew = grew || (m_new > m_run[cq]);
+            alpha[cq] = __builtin_amdgcn_exp2f(m_run[cq] - m_use);
+            m_run[cq] = m_new;
             float sum = 0.f;
 #pragma unroll
             for (int rb = 0; rb < NK; ++rb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float pr = exp2f(acc_s[rb][cq][i] - m_use);
+                    const float pr = __builtin_amdgcn_exp2f(fmaf(acc_s[rb][cq][i], c2, -m_use));
                     acc_s[rb][cq][i] = pr;
                     sum += pr;
                 }
-            l_run[cq] = l_run[cq] * alpha + sum;   // per-lane partial; halves are added at the end
-            m_run[cq] = m_new;
+            l_run[cq] = l_run[cq] * alpha[cq] + sum;   // per-lane partial; halves are added at the end
+        }
+        // rescale the output accumulators only when some column's maximum moved
+        if (__any(grew)) {
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
+            for (int cq = 0; cq < NQ; ++cq)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc_o[db][cq][i] *= alpha;
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc_o[db][cq][i] *= alpha[cq];
         }
         // O^T += V^T P^T
 #pragma unroll
@@ -267,10 +334,10 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 for (int cq = 0; cq < NQ; ++cq) {
                     if constexpr (BF16) {
                         const int o = vf * 8;
-                        pf[cq].x = pack_bf16x2(acc_s[rb][cq][o + 0], acc_s[rb][cq][o + 1]);
-                        pf[cq].y = pack_bf16x2(acc_s[rb][cq][o + 2], acc_s[rb][cq][o + 3]);
-                        pf[cq].z = pack_bf16x2(acc_s[rb][cq][o + 4], acc_s[rb][cq][o + 5]);
-                        pf[cq].w = pack_bf16x2(acc_s[rb][cq][o + 6], acc_s[rb][cq][o + 7]);
+                        pf[cq] = to_bf16_frag(acc_s[rb][cq][o + 0], acc_s[rb][cq][o + 1],
+                                              acc_s[rb][cq][o + 2], acc_s[rb][cq][o + 3],
+                                              acc_s[rb][cq][o + 4], acc_s[rb][cq][o + 5],
+                                              acc_s[rb][cq][o + 6], acc_s[rb][cq][o + 7]);
                     } else {
                         const int o = vf * 4;
                         pf[cq].x = f2u(acc_s[rb][cq][o + 0]);
@@ -280,13 +347,10 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                     }
                 }
 #pragma unroll
-                for (int db = 0; db < NDB; ++db) {
-                    const uint4 vfrag = *reinterpret_cast<const uint4 *>(
-                        vsrc + (long long)rb * GROUP_BYTES + ((db * NVF + vf) * 64) * 16);
+                for (int db = 0; db < NDB; ++db)
 #pragma unroll
                     for (int cq = 0; cq < NQ; ++cq)
-                        acc_o[db][cq] = mfma16<BF16>(vfrag, pf[cq], acc_o[db][cq]);
-                }
+                        acc_o[db][cq] = mfma16<BF16>(vreg[rb][db * NVF + vf], pf[cq], acc_o[db][cq]);
             }
     }
 
@@ -329,14 +393,29 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // S = Q K^T: a lane owns key column `col`; element i of row block rq is query
+    // rq*32 + 8*(i/4) + 4*gh + (i%4).  Its normaliser:
+    float lq[NQ][16];
+#pragma unroll
+    for (int rq = 0; rq < NQ; ++rq)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) lq[rq][i] = s_lse[wave][rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3)];
     float *mass_h = p.mass + (long long)h * p.T + sd.tok0;
+    if (n_tiles > 0) {
+        const unsigned off0 = tile_off(0);
+        // same order as the refills inside the loop: waits count loads in issue order
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb) {
+                kreg[rb][fr] = load_frag(krs, lane_off, off0, rb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
     for (int t = 0; t < n_tiles; ++t) {
-        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
-        const int ks = t % KSUB;
-        const int ktok0 = r * B + ks * KT;
-        if (ktok0 > qtok0 + QT - 1) continue;
-        const char *ksrc = kbase + (long long)r * TILE_BYTES + (long long)ks * NK * GROUP_BYTES;
-        floatx16 acc_s[NQ][NK];   // S = Q K^T: rows = queries, lane column = key
+        const int ktok0 = tile_ktok0(t);
+        const unsigned knext = tile_off(t + 1 < n_tiles ? t + 1 : t);
+        floatx16 acc_s[NQ][NK];
 #pragma unroll
         for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
@@ -347,11 +426,14 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         for (int fr = 0; fr < FR; ++fr)
 #pragma unroll
             for (int ck = 0; ck < NK; ++ck) {
-                const uint4 kf = *reinterpret_cast<const uint4 *>(ksrc + (ck * FR + fr) * 1024);
 #pragma unroll
                 for (int rq = 0; rq < NQ; ++rq)
-                    acc_s[rq][ck] = mfma16<BF16>(qf[rq][fr], kf, acc_s[rq][ck]);
+                    acc_s[rq][ck] = mfma16<BF16>(qf[rq][fr], kreg[ck][fr], acc_s[rq][ck]);
+                __builtin_amdgcn_sched_barrier(0);
+                kreg[ck][fr] = load_frag(krs, lane_off, knext, ck * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        const bool need_mask = (ktok0 + KT - 1 > qtok0) || (ktok0 + KT > L) || (qtok0 + QT > L);
 #pragma unroll
         for (int ck = 0; ck < NK; ++ck) {
             const int tk = ktok0 + ck * 32 + col;
@@ -360,10 +442,12 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
             for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int qi = rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
-                    const int tq = qtok0 + qi;
-                    const float e = exp2f(acc_s[rq][ck][i] * p.scale_log2e - s_lse[wave][qi]);
-                    colsum += (tq < L && tk <= tq) ? e : 0.f;
+                    float e = __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
+                    if (need_mask) {
+                        const int tq = qtok0 + rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
+                        e = (tq < L && tk <= tq) ? e : 0.f;
+                    }
+                    colsum += e;
                 }
             colsum += __shfl_xor(colsum, 32);
             if (gh == 0 && tk < L && colsum != 0.f) atomicAdd(mass_h + tk, colsum);
@@ -375,6 +459,9 @@ typedef void (*attn_fn)(const AttnParams);
 
 static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
 {
+    // 64 queries per wavefront (32 for block 32) against 32-key sub-tiles: with one 32-key group
+    // in flight the scores, the K/V fragments and the Q tile fit the 256 architectural VGPRs and
+    // the output accumulators live in the accumulation registers.
     const bool bf = pb.dtype == STREAM_BF16;
     qsub = pb.b == 128 ? 2 : 1;
     if (pb.b == 32) {
@@ -382,11 +469,11 @@ static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
         return pb.d == 128 ? attn_kernel<false, 128, 1, 1, 32, 1> : attn_kernel<false, 64, 1, 1, 32, 1>;
     }
     if (pb.b == 64) {
-        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 2, 64, 1> : attn_kernel<true, 64, 2, 2, 64, 1>;
-        return pb.d == 128 ? attn_kernel<false, 128, 2, 2, 64, 1> : attn_kernel<false, 64, 2, 2, 64, 1>;
+        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 64, 1> : attn_kernel<true, 64, 2, 1, 64, 1>;
+        return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 64, 1> : attn_kernel<false, 64, 2, 1, 64, 1>;
     }
-    if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 2, 128, 1> : attn_kernel<true, 64, 2, 2, 128, 1>;
-    return pb.d == 128 ? attn_kernel<false, 128, 2, 2, 128, 1> : attn_kernel<false, 64, 2, 2, 128, 1>;
+    if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 128, 1> : attn_kernel<true, 64, 2, 1, 128, 1>;
+    return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 128, 1> : attn_kernel<false, 64, 2, 1, 128, 1>;
 }
 
 struct AttnWorkspace {

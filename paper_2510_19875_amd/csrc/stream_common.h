@@ -88,6 +88,27 @@ __device__ __forceinline__ int seq_of_block(const SeqTable &t, int gb)
     return s;
 }
 
+#if defined(__HIPCC__)
+// Packed K/V tiles are read with raw buffer loads: a scalar resource (base + size, so a read
+// past the region returns zeros instead of faulting), a scalar byte offset that selects the tile
+// and a per-lane offset.  One fragment = 64 lanes x 16 bytes = 1 KiB; fragment j of a tile sits
+// at byte j * 1024.  The split below keeps the per-lane part inside the 12-bit immediate.
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_tile_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ uint4 load_frag(__amdgpu_buffer_rsrc_t rs, unsigned lane_off,
+                                           unsigned tile_off, int j)
+{
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off + (j & 3) * 1024,
+                                                            tile_off + (j >> 2) * 4096, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+#endif
+
 // Host-side validated problem description shared by both entry points.
 struct Problem {
     int H, Hkv, g, d, b, dtype, esize, batch, kmax;

@@ -44,6 +44,8 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
         sd.tok0 = a;
         sd.len = (int)(e - a);
         sd.nblk = (int)((e - a + s->block - 1) / s->block);
+        // tile offsets inside one (kv head, sequence) region are 32-bit
+        if ((long long)sd.nblk * s->block * s->head_dim * p.esize >= (1LL << 31)) return STREAM_EUNSUPPORTED;
         sd.blk0 = (int)nb;
         sd.k = 0; sd.levels = 0; sd.pad_ = 0;
         if (topk_max > 0) {

@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     __shared__ float s_sc[4][2 * kMaxTopk];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keep it scalar
     int kvh, slot;
     if (!wg_decode(p.map, blockIdx.x, kvh, slot)) return;
     const long long rows_per_kv = (long long)p.NB * p.g;
@@ -170,26 +170,30 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         }
     }
 
-    const char *kbase = p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES +
-                        (long long)kh * NG * GROUP_BYTES + lane * 16;
+    // K tiles of this (kv head, sequence), from this wavefront's key half on
+    const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(
+        p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES + (long long)kh * NG * GROUP_BYTES,
+        (unsigned)((long long)N * TILE_BYTES - (long long)kh * NG * GROUP_BYTES));
+    const unsigned lane_off = lane * 16;
     const bool tail_row = (q == N - 1) && (L % B != 0);
     const int qtok0 = q * B + qh * 32 * MB;
 
     uint4 kf[NG][FR];
     if (nt > 0) {
         const int r0 = __builtin_amdgcn_readfirstlane(s_rep[wave][0]);
-        const char *src = kbase + (long long)r0 * TILE_BYTES;
+        // same order as the refills in the loop below: waits count loads in issue order
 #pragma unroll
-        for (int cb = 0; cb < NG; ++cb)
+        for (int fr = 0; fr < FR; ++fr)
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr)
-                kf[cb][fr] = *reinterpret_cast<const uint4 *>(src + (cb * FR + fr) * 1024);
+            for (int cb = 0; cb < NG; ++cb) {
+                kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
     }
     for (int t = 0; t < nt; ++t) {
         const int r = __builtin_amdgcn_readfirstlane(s_rep[wave][t]);
         const int tn = t + 1 < nt ? t + 1 : t;
-        const int rn = __builtin_amdgcn_readfirstlane(s_rep[wave][tn]);
-        const char *nxt = kbase + (long long)rn * TILE_BYTES;
+        const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[wave][tn]) * (unsigned)TILE_BYTES;
         floatx16 acc[MB][NG];
 #pragma unroll
         for (int rb = 0; rb < MB; ++rb)
@@ -204,8 +208,12 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
                     acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
-                // the fragment is consumed: refill its registers from the next tile
-                kf[cb][fr] = *reinterpret_cast<const uint4 *>(nxt + (cb * FR + fr) * 1024);
+                // the fragment is consumed: refill its registers from the next tile right here,
+                // so that every fragment of the next tile has a whole tile of MFMA time to arrive
+                // (the scheduling barriers stop the compiler from sinking the loads to the end)
+                __builtin_amdgcn_sched_barrier(0);
+                kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         float mx = -INFINITY;
