@@ -88,6 +88,7 @@ struct AttnParams {
     long long q_sh_b, q_st_b, o_sh_b, o_st_b;
     const int *idx, *cnt;
     float *lse, *mass;           // nullable
+    float *lse2;                 // workspace [H, T]: base-2 log-sum-exp, written by pass 1 for pass 2
     long long T;
     int H, g, NB, kmax;
     float scale_log2e;           // scale * log2(e): softmax runs in base 2
@@ -139,7 +140,9 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
 //   sub-tile t+1 as soon as its last MFMA is issued  ->  softmax update  ->  O^T += V^T P^T.
 // Loads return in issue order, so V(t) is complete before K(t+1) and each wait is a count of
 // younger loads still allowed in flight.
-template <bool BF16, int D, int NQ, int NK, int B, int OCC>
+// PASS 1: outputs O, lse (and the base-2 normalisers for pass 2).  PASS 2: received mass, a
+// separate launch with two wavefronts per SIMD so that one's exponentials overlap the other's MFMAs.
+template <bool BF16, int D, int NQ, int NK, int B, int PASS, int OCC>
 __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -152,7 +155,6 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     constexpr int KSUB = B / KT;               // key sub-tiles per block
     constexpr long long TILE_BYTES = (long long)B * D * ES;
     constexpr int GROUP_BYTES = 32 * D * ES;
-    __shared__ float s_lse[4][QT];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keep it scalar
@@ -219,6 +221,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         return r * B + (t % KSUB) * KT;
     };
 
+    if constexpr (PASS == 1) {
     floatx16 acc_o[NDB][NQ];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -299,9 +302,12 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[rb][cq][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
-            const float m_new = fmaxf(m_run[cq], mx);
+            // the reference exponent follows the running maximum lazily: it moves only when the
+            // maximum has grown by more than 2^8, so probabilities stay <= 256 (harmless in fp32
+            // and bf16) and the output accumulators are rescaled a handful of times per row
+            const float m_new = mx > m_run[cq] + 8.f ? mx : m_run[cq];
             const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            grew = grew || (m_new > m_run[cq]);
+            grew = grew || (m_new > m_run[cq] && m_run[cq] != -INFINITY);
             alpha[cq] = __builtin_amdgcn_exp2f(m_run[cq] - m_use);
             m_run[cq] = m_new;
             float sum = 0.f;
@@ -322,7 +328,20 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 #pragma unroll
                 for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc_o[db][cq][i] *= alpha[cq];
+                    for (int i = 0; i < 16; ++i) {
+                        // The accumulators live in the accumulation registers, where the MFMAs
+                        // update them; scale them there (read, multiply, write back) so that this
+                        // rare path does not drag all 128 of them through the vector registers
+                        // on every iteration.
+                        float t = acc_o[db][cq][i], tmp;
+                        asm volatile("v_accvgpr_read_b32 %1, %0\n\t"
+                                     "v_mul_f32 %1, %1, %2\n\t"
+                                     "v_accvgpr_write_b32 %0, %1"
+                                     : "+a"(t), "=&v"(tmp)
+                                     : "v"(alpha[cq]));
+                        acc_o[db][cq][i] = t;
+                    }
+            asm volatile("s_nop 7");
         }
         // O^T += V^T P^T
 #pragma unroll
@@ -384,22 +403,23 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 }
             if (p.lse && gh == 0)
                 p.lse[(long long)h * p.T + sd.tok0 + tok] = lse2[cq] * 0.6931471805599453f;
+            if (p.lse2 && gh == 0) p.lse2[(long long)h * p.T + sd.tok0 + tok] = lse2[cq];
         }
-        if (gh == 0) s_lse[wave][cq * 32 + col] = lse2[cq];
     }
-    if (!p.mass) return;
-
+    } else {
+    uint4 kreg[NK][FR];
+    const float c2 = p.scale_log2e;
     // ------------------------------------------------------------------ pass 2: received mass
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     // S = Q K^T: a lane owns key column `col`; element i of row block rq is query
     // rq*32 + 8*(i/4) + 4*gh + (i%4).  Its normaliser:
     float lq[NQ][16];
 #pragma unroll
     for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) lq[rq][i] = s_lse[wave][rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3)];
+        for (int i = 0; i < 16; ++i) {
+            const int tq = qtok0 + rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
+            lq[rq][i] = tq < L ? p.lse2[(long long)h * p.T + sd.tok0 + tq] : 0.f;
+        }
     float *mass_h = p.mass + (long long)h * p.T + sd.tok0;
     if (n_tiles > 0) {
         const unsigned off0 = tile_off(0);
@@ -438,25 +458,32 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         for (int ck = 0; ck < NK; ++ck) {
             const int tk = ktok0 + ck * 32 + col;
             float colsum = 0.f;
+            if (!need_mask) {   // wave-uniform: most sub-tiles are fully visible
 #pragma unroll
-            for (int rq = 0; rq < NQ; ++rq)
+                for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float e = __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
-                    if (need_mask) {
+                    for (int i = 0; i < 16; ++i)
+                        colsum += __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
+            } else {
+#pragma unroll
+                for (int rq = 0; rq < NQ; ++rq)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
                         const int tq = qtok0 + rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
-                        e = (tq < L && tk <= tq) ? e : 0.f;
+                        const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
+                        colsum += (tq < L && tk <= tq) ? e : 0.f;
                     }
-                    colsum += e;
-                }
+            }
             colsum += __shfl_xor(colsum, 32);
             if (gh == 0 && tk < L && colsum != 0.f) atomicAdd(mass_h + tk, colsum);
         }
+    }
     }
 }
 
 typedef void (*attn_fn)(const AttnParams);
 
+template <int PASS, int OCC>
 static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
 {
     // 64 queries per wavefront (32 for block 32) against 32-key sub-tiles: with one 32-key group
@@ -465,19 +492,19 @@ static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
     const bool bf = pb.dtype == STREAM_BF16;
     qsub = pb.b == 128 ? 2 : 1;
     if (pb.b == 32) {
-        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 1, 1, 32, 1> : attn_kernel<true, 64, 1, 1, 32, 1>;
-        return pb.d == 128 ? attn_kernel<false, 128, 1, 1, 32, 1> : attn_kernel<false, 64, 1, 1, 32, 1>;
+        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 1, 1, 32, PASS, OCC> : attn_kernel<true, 64, 1, 1, 32, PASS, OCC>;
+        return pb.d == 128 ? attn_kernel<false, 128, 1, 1, 32, PASS, OCC> : attn_kernel<false, 64, 1, 1, 32, PASS, OCC>;
     }
     if (pb.b == 64) {
-        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 64, 1> : attn_kernel<true, 64, 2, 1, 64, 1>;
-        return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 64, 1> : attn_kernel<false, 64, 2, 1, 64, 1>;
+        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 64, PASS, OCC> : attn_kernel<true, 64, 2, 1, 64, PASS, OCC>;
+        return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 64, PASS, 1> : attn_kernel<false, 64, 2, 1, 64, PASS, OCC>;
     }
-    if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 128, 1> : attn_kernel<true, 64, 2, 1, 128, 1>;
-    return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 128, 1> : attn_kernel<false, 64, 2, 1, 128, 1>;
+    if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 128, PASS, OCC> : attn_kernel<true, 64, 2, 1, 128, PASS, OCC>;
+    return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 128, PASS, 1> : attn_kernel<false, 64, 2, 1, 128, PASS, OCC>;
 }
 
 struct AttnWorkspace {
-    size_t kp, vp, total;
+    size_t kp, vp, lse2, total;
 };
 
 static AttnWorkspace attn_layout(const Problem &pb)
@@ -486,7 +513,8 @@ static AttnWorkspace attn_layout(const Problem &pb)
     const size_t tile = align_up((size_t)pb.Hkv * pb.NB * pb.b * pb.d * pb.esize, 256);
     w.kp = 0;
     w.vp = tile;
-    w.total = 2 * tile;
+    w.lse2 = 2 * tile;
+    w.total = 2 * tile + align_up((size_t)pb.H * pb.T * 4, 256);
     return w;
 }
 
@@ -570,14 +598,21 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
     p.T = pb.T; p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.kmax = topk_max;
     p.scale_log2e = scale * 1.4426950408889634f;
     p.seqs = pb.seqs;
+    p.lse2 = mass ? (float *)(ws + w.lse2) : nullptr;
     int qsub = 1;
-    attn_fn fn = pick_attn_kernel(pb, qsub);
+    attn_fn fn = pick_attn_kernel<1, 1>(pb, qsub);
     const long long items_per_kv = (long long)pb.NB * pb.g * qsub;
     const long long per_kv = (items_per_kv + 3) / 4;
     if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
     p.map = make_wg_map(pb.Hkv, (int)per_kv);
     hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
-    return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+    if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+    if (mass) {
+        attn_fn fn2 = pick_attn_kernel<2, 2>(pb, qsub);
+        hipLaunchKernelGGL(fn2, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
+        if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+    }
+    return STREAM_OK;
 }
 
 }  // extern "C"
