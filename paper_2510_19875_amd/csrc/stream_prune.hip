@@ -60,9 +60,11 @@ __device__ __forceinline__ float wave_max(float v)
     return fmaxf(fmaxf(a, b), fmaxf(c, d));
 }
 
-__device__ __forceinline__ float lane_bcast(float v, int src_lane)
+// Order-preserving map of a float's bit pattern to an unsigned integer (-inf lowest).
+__device__ __forceinline__ unsigned sortable_bits(float v)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
+    const unsigned u = __builtin_bit_cast(unsigned, v + 0.f);   // -0 -> +0: equal as scores
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
 // One operand fragment (16 bytes per lane) times another, accumulated into a 32x32 tile.
@@ -115,8 +117,31 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int qh = WPR == 4 ? (wave >> 1) : 0;            // query half / key half of this wavefront
     const int kh = WPR == 4 ? (wave & 1) : 0;
 
+    // ---- Q tile of this wavefront as A-operand fragments: lane (mrow = lane % 32, gh = lane / 32)
+    //      holds, for fragment fr, the 16 bytes at chunk 2*fr + gh of row mrow.  Issued first so
+    //      that the loads overlap the node-state loads below; rows past the end of the sequence
+    //      fall outside the buffer resource and read as zeros.
+    uint4 qf[MB][FR];
+    {
+        const int mrow = lane & 31, gh = lane >> 5;
+        const __amdgpu_buffer_rsrc_t qrs = make_tile_rsrc(
+            p.Q + (long long)h * p.q_sh_b + sd.tok0 * p.q_st_b,
+            (unsigned)((long long)(L - 1) * p.q_st_b + D * ES));
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb) {
+            const unsigned tok = (unsigned)(q * B + qh * 32 * MB + rb * 32 + mrow);
+            const unsigned voff = tok * (unsigned)p.q_st_b + gh * 16;
+#pragma unroll
+            for (int fr = 0; fr < FR; ++fr) {
+                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * 32, 0, 0);
+                qf[rb][fr] = make_uint4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
     // ---- node of this lane (node init line of Alg. 2 at the first level)
-    int f = 0, l = -1;
+    int f = 0, l = -1, n_src = k;                         // n_src: lanes that hold a node
     float sc = -INFINITY;
     bool live = false;
     if (first) {
@@ -126,13 +151,16 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             live = f <= l;
         }
     } else {
+        // all four loads are independent (slots past the live count hold stale but allocated data)
         const int c = p.ncnt[row];
-        if (lane < c) {
+        if (lane < p.kmax) {
             f = p.nf[row * p.kmax + lane];
             l = p.nl[row * p.kmax + lane];
             sc = p.ns[row * p.kmax + lane];
-            live = true;
         }
+        live = lane < c;
+        n_src = __builtin_amdgcn_readfirstlane(c);
+        if (!live) { f = 0; l = -1; sc = -INFINITY; }
     }
     // ---- split at the midpoint; causal validity: a branch is valid iff it is non-empty and
     //      starts at or before the query block; its representative is its first block.
@@ -149,26 +177,6 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     if (need0) s_rep[wave][pos0] = f;
     if (need1) s_rep[wave][pos1] = m;
     wave_sync();
-
-    // ---- Q tile of this wavefront as A-operand fragments: lane (mrow = lane % 32, gh = lane / 32)
-    //      holds, for fragment fr, the 16 bytes at chunk 2*fr + gh of row mrow.
-    uint4 qf[MB][FR];
-    {
-        const int mrow = lane & 31, gh = lane >> 5;
-        const char *qb = p.Q + (long long)h * p.q_sh_b;
-#pragma unroll
-        for (int rb = 0; rb < MB; ++rb) {
-            const int tok = q * B + qh * 32 * MB + rb * 32 + mrow;
-            const bool ok = tok < L;
-            const char *src = qb + (sd.tok0 + (ok ? tok : 0)) * p.q_st_b + gh * 16;
-#pragma unroll
-            for (int fr = 0; fr < FR; ++fr) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (ok) v = *reinterpret_cast<const uint4 *>(src + fr * 32);
-                qf[rb][fr] = v;
-            }
-        }
-    }
 
     // K tiles of this (kv head, sequence), from this wavefront's key half on
     const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(
@@ -256,16 +264,19 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     if (v0) s0 = need0 ? tile_score(pos0) : sc;
     if (v1) s1 = need1 ? tile_score(pos1) : sc;
 
-    // ---- top-k of the 2k branch scores: rank by counting; equal scores -> lower position.
-    //      Branch positions: 2*lane (left), 2*lane+1 (right).
+    // ---- top-k of the 2k branch scores: rank by counting.  A branch's key is 64 bits: the score
+    //      mapped to an order-preserving unsigned in the high word, the complemented branch
+    //      position (2*lane left, 2*lane+1 right) in the low word, so "larger key" means larger
+    //      score, and on equal scores the lower position.  Branch-free: one 64-bit compare per pair.
+    const unsigned long long key0 = ((unsigned long long)sortable_bits(s0) << 32) | (unsigned)~(2u * lane);
+    const unsigned long long key1 = ((unsigned long long)sortable_bits(s1) << 32) | (unsigned)~(2u * lane + 1u);
+    const int hi0 = (int)sortable_bits(s0), hi1 = (int)sortable_bits(s1);
     int r0 = 0, r1 = 0;
-    for (int j = 0; j < k; ++j) {
-        const float a0 = lane_bcast(s0, j), a1 = lane_bcast(s1, j);
-        const int pj = 2 * j;
-        r0 += (a0 > s0 || (a0 == s0 && pj < 2 * lane)) ? 1 : 0;
-        r0 += (a1 > s0 || (a1 == s0 && pj + 1 < 2 * lane)) ? 1 : 0;
-        r1 += (a0 > s1 || (a0 == s1 && pj < 2 * lane + 1)) ? 1 : 0;
-        r1 += (a1 > s1 || (a1 == s1 && pj + 1 < 2 * lane + 1)) ? 1 : 0;
+    for (int j = 0; j < n_src; ++j) {
+        const unsigned long long a0 = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi0, j) << 32) | (unsigned)~(2u * j);
+        const unsigned long long a1 = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi1, j) << 32) | (unsigned)~(2u * j + 1u);
+        r0 += (a0 > key0 ? 1 : 0) + (a1 > key0 ? 1 : 0);
+        r1 += (a0 > key1 ? 1 : 0) + (a1 > key1 ? 1 : 0);
     }
     const bool keep0 = v0 && r0 < k;
     const bool keep1 = v1 && r1 < k;
