@@ -27,9 +27,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per level-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
-# copy kernel of known size (profiles/level_kernel_cfg3_pmc.txt); None until measured.
-LEVEL_KERNEL_HBM_BYTES = None
+# HBM-side bytes per level-kernel launch (mean of the 6 levels) at the headline workload, from the
+# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/cfg3_pmc_counters.txt:
+# FETCH_SIZE 1.132e6 x 2.0 (the factor a plain 268 MB copy shows for this counter) + WRITE_SIZE
+# 2.663e4 x 1.0, in KiB.  Only meaningful for that workload.
+LEVEL_KERNEL_HBM_BYTES = {"cfg3_T131072_gqa32x8_d128_bf16": (1.132e6 * 2.0 + 2.663e4) * 1024.0}
 
 
 class HipEvents:
@@ -60,7 +62,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="named workload (default: the headline one)")
     ap.add_argument("--layers", type=int, default=0, help="resident input layers (default min(steps, 32))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=96)
+    ap.add_argument("--cpu-rows", type=int, default=1536)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding code); "
@@ -155,6 +157,10 @@ def main():
     tok_heads = float(T) * H
     value = tok_heads / (ms_per_step * 1e-3)
 
+    Q_BYTES = float(H) * T * d * layers[0][0].element_size()      # Q tile of every row, once per level
+    K_BYTES = float(Hkv) * T * d * layers[0][0].element_size()    # distinct K tiles: 1/64 .. 1/2 of K by level
+    retained = float(out_p["cnt"].sum().item())
+    attn_flop = retained * 6.0 * b * b * d                        # QK^T + PV + the QK^T of the mass pass
     tile_flop = 2.0 * b * b * d
     flops_per_step = np.array([tile_counts[i % n_layers] for i in range(K_steps)]) * tile_flop
     level_total_s = level_ms.sum() * 1e-3
@@ -183,6 +189,8 @@ def main():
         "prune_ms": float(np.mean(prune_ms)),
         "attn_ms": float(np.mean(attn_ms)),
         "prune_only_value": tok_heads / (float(np.mean(prune_ms)) * 1e-3),
+        "attn_tflops": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12,
+        "attn_frac_of_mfma_peak": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
         "level_kernel_ms": [float(x) for x in level_ms.mean(axis=0)],
         "tiles_scored_per_step": float(np.mean(tile_counts)),
         "peak_device_bytes": int(peak_mem),
@@ -198,7 +206,8 @@ def main():
             "flop_per_launch": float(flops_per_step.sum() / launches),
             "avg_launch_ms": float(level_ms.sum() / launches),
             "launches": launches,
-            "traffic": LEVEL_KERNEL_HBM_BYTES,
+            "traffic": LEVEL_KERNEL_HBM_BYTES.get(w.name),
+            "algorithmic_bytes_per_launch": float(Q_BYTES + K_BYTES * 0.25 + H * NB * (24 * kmax + 4)),
         },
     }
     if not args.no_cpu_baseline:

@@ -599,17 +599,14 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
     p.scale_log2e = scale * 1.4426950408889634f;
     p.seqs = pb.seqs;
     p.lse2 = mass ? (float *)(ws + w.lse2) : nullptr;
-    int qsub = 1;
-    attn_fn fn = pick_attn_kernel<1, 1>(pb, qsub);
-    const long long items_per_kv = (long long)pb.NB * pb.g * qsub;
-    const long long per_kv = (items_per_kv + 3) / 4;
-    if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
-    p.map = make_wg_map(pb.Hkv, (int)per_kv);
-    hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
-    if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
-    if (mass) {
-        attn_fn fn2 = pick_attn_kernel<2, 2>(pb, qsub);
-        hipLaunchKernelGGL(fn2, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
+    for (int pass = 1; pass <= (mass ? 2 : 1); ++pass) {
+        int qsub = 1;
+        attn_fn fn = pass == 1 ? pick_attn_kernel<1, 1>(pb, qsub) : pick_attn_kernel<2, 2>(pb, qsub);
+        const long long items_per_kv = (long long)pb.NB * pb.g * qsub;
+        const long long per_kv = (items_per_kv + 3) / 4;
+        if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
+        p.map = make_wg_map(pb.Hkv, (int)per_kv);
+        hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
         if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
     }
     return STREAM_OK;
