@@ -133,6 +133,32 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
 }
 
+// S^T += K-fragment x Q-fragment with the result in ordinary vector registers.  The compiler
+// keeps every MFMA result of a one-wave-per-SIMD kernel in the accumulation registers, from
+// where the softmax would have to copy each score out again; the scores are consumed by vector
+// instructions only, so the pipelined loop issues these MFMAs itself.  Callers keep two MFMAs
+// or more between the last of these and the first read of its result (the wait the hardware
+// does not enforce); accumulation onto the same registers back to back is interlocked.
+__device__ __forceinline__ void qk_mfma_bf16(floatx16 &c, const uint4 &a, const u32x4_t &bv, bool first)
+{
+    const u32x4_t av = {a.x, a.y, a.z, a.w};
+    if (first)
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(av), "a"(bv));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(av), "a"(bv));
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
+template <int I> struct IntC { static constexpr int value = I; };
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &f)
+{
+    if constexpr (I < N) {
+        f(IntC<I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 // NQ: 32-query groups per wavefront, NK: 32-key groups per key sub-tile, B: block size.
 //
 // Software pipeline of pass 1, per key sub-tile t (the K fragments of t are already in registers):
@@ -174,7 +200,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     const long long row = (long long)h * p.NB + gb;
     const int qtok0 = q * B + qs * QT;          // first query token (sequence-local) of this wavefront
     if (qtok0 >= L) return;
-    const int n_blk = p.cnt[row];
+    int n_blk = p.cnt[row];
+    n_blk = n_blk < 0 ? 0 : (n_blk > p.kmax ? p.kmax : n_blk);   // never read past the row's list
     const int *my_idx = p.idx + row * p.kmax;
 
     // key sub-tiles to visit: all of every listed block, except that sub-tiles of the diagonal
@@ -212,13 +239,18 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     const __amdgpu_buffer_rsrc_t vrs =
         make_tile_rsrc(p.Vp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES, region_bytes);
     const unsigned lane_off = lane * 16;
+    // the row's block list lives in one register (lane j holds entry j; lists have <= 64 entries)
+    // and is read with a scalar lane select: no memory access inside the tile loops
+    const int my_blk = lane < n_blk ? my_idx[lane] : 0;
     auto tile_off = [&](int t) -> unsigned {
-        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
-        return (unsigned)r * (unsigned)TILE_BYTES + (unsigned)(t % KSUB) * NK * GROUP_BYTES;
+        const int ts = __builtin_amdgcn_readfirstlane(t);
+        const int r = __builtin_amdgcn_readlane(my_blk, ts / KSUB);
+        return (unsigned)r * (unsigned)TILE_BYTES + (unsigned)(ts % KSUB) * NK * GROUP_BYTES;
     };
     auto tile_ktok0 = [&](int t) -> int {
-        const int r = __builtin_amdgcn_readfirstlane(my_idx[t / KSUB]);
-        return r * B + (t % KSUB) * KT;
+        const int ts = __builtin_amdgcn_readfirstlane(t);
+        const int r = __builtin_amdgcn_readlane(my_blk, ts / KSUB);
+        return r * B + (ts % KSUB) * KT;
     };
 
     if constexpr (PASS == 1) {
@@ -233,6 +265,22 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 #pragma unroll
     for (int cq = 0; cq < NQ; ++cq) { m_run[cq] = -INFINITY; l_run[cq] = 0.f; }
     const float c2 = p.scale_log2e;
+    // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
+    constexpr bool PIPE = NK == 1 && (BF16 || D == 64);
+    // The pipelined loop reads the Q fragments from the accumulation registers (an MFMA takes
+    // its B operand from either file), which leaves the vector registers to the scores.
+    u32x4_t qacc[NQ][FR];
+    if constexpr (PIPE && BF16) {
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+            for (int fr = 0; fr < FR; ++fr) {
+                u32x4_t v = {qf[cq][fr].x, qf[cq][fr].y, qf[cq][fr].z, qf[cq][fr].w};
+                asm volatile("" : "+a"(v));
+                qacc[cq][fr] = v;
+                qf[cq][fr] = make_uint4(v[0], v[1], v[2], v[3]);
+            }
+    }
 
     uint4 kreg[NK][FR];
     if (n_tiles > 0) {
@@ -247,7 +295,217 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
             }
     }
     // ------------------------------------------------------------------ pass 1: O and lse
-    for (int t = 0; t < n_tiles; ++t) {
+    // Leading sub-tiles that need no mask run in a software pipeline that keeps the matrix
+    // pipe busy while the vector ALUs do the softmax: iteration t issues, as one interleaved
+    // stream,  O^T += V(t-1)^T P(t-1)^T  and  S(t+1)^T = K(t+1) Q^T  (MFMA groups), the loads
+    // that refill each V / K fragment right after its last use, and between the MFMA groups
+    // the softmax of S(t) cut into small chunks.  S is double buffered by parity.
+    // Iteration 0 multiplies a zero P, the last one computes an S nobody reads: one loop body
+    // serves all iterations.  Masked sub-tiles (diagonal block, sequence tail) follow in the
+    // plain loop below.
+    int n_fast = 0;
+    if constexpr (PIPE) {
+        n_fast = n_tiles;
+        while (n_fast > 0) {
+            const int k0 = tile_ktok0(n_fast - 1);
+            if ((k0 + KT - 1 > qtok0) || (k0 + KT > L)) --n_fast; else break;
+        }
+        n_fast = __builtin_amdgcn_readfirstlane(n_fast);
+    }
+    if constexpr (PIPE) {
+    if (n_fast > 0) {
+        constexpr int GPV = NVF * NDB;          // MFMA groups of the PV product
+        constexpr int G = GPV + FR;             // + groups of the QK product
+        constexpr int C = 7 * NQ;               // softmax chunks
+        // P has one buffer: every PV group must be issued before the first chunk that writes P
+        static_assert(GPV * C / G <= 2 * NQ + 4, "P would be overwritten while PV still reads it");
+        floatx16 S[2][NQ];
+        uint4 Pf[NVF][NQ];
+        // V and K fragments are double buffered by parity as well: what iteration t loads is
+        // consumed by iteration t + 2, so a load has two iterations to arrive.
+        //   iteration t (parity sb): vr[sb] holds V(t-1), refilled with V(t+1);
+        //                            kb(sb) holds K(t+1), refilled with K(t+3).
+        uint4 vr[2][GPV];
+        uint4 k1r[FR];                          // parity 1 of the K buffer; parity 0 is kreg[0]
+        auto clampk = [&](int x) {              // K tile to prefetch: never past the first masked tile
+            x = x < n_fast ? x : n_fast;
+            return x < n_tiles ? x : n_tiles - 1;
+        };
+#pragma unroll
+        for (int vf = 0; vf < NVF; ++vf)
+#pragma unroll
+            for (int cq = 0; cq < NQ; ++cq) Pf[vf][cq] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < GPV; ++j) vr[0][j] = make_uint4(0, 0, 0, 0);   // iteration 0: 0 x 0
+        {   // S(0), then the fragments of iterations 0 and 1 in the order they are consumed
+            const unsigned k1 = tile_off(clampk(1));
+#pragma unroll
+            for (int fr = 0; fr < FR; ++fr) {
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq) {
+                    if constexpr (BF16) {
+                        qk_mfma_bf16(S[0][cq], kreg[0][fr], qacc[cq][fr], fr == 0);
+                    } else {
+                        floatx16 z;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) z[i] = 0.f;
+                        S[0][cq] = mfma16<BF16>(kreg[0][fr], qf[cq][fr], fr == 0 ? z : S[0][cq]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                kreg[0][fr] = load_frag(krs, lane_off, k1, fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const unsigned off0 = tile_off(0);
+#pragma unroll
+            for (int g = 0; g < GPV; ++g) {
+                const int vf = g / NDB, db = g % NDB;
+                vr[1][db * NVF + vf] = load_frag(vrs, lane_off, off0, db * NVF + vf);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const unsigned k2 = tile_off(clampk(2));
+#pragma unroll
+            for (int fr = 0; fr < FR; ++fr) {
+                k1r[fr] = load_frag(krs, lane_off, k2, fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        auto iter = [&](const int t, auto SBc) {
+            constexpr int sb = decltype(SBc)::value, ob = sb ^ 1;
+            const unsigned voff = tile_off(t + 1 < n_fast ? t + 1 : n_fast - 1);
+            const unsigned knext = tile_off(clampk(t + 3));
+            float sv[NQ][16], mx[NQ], mxo[NQ], m_use[NQ], alpha[NQ], sum[NQ];
+            bool grew = false;
+            auto chunk = [&](auto Cc) {
+                constexpr int c = decltype(Cc)::value;
+                // order: max(0..NQ-1), ref(0..NQ-1), then per column: 4 exp quarters + convert
+                if constexpr (c < NQ) {
+                    constexpr int cq = c;
+                    float m = -INFINITY;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) { sv[cq][i] = S[sb][cq][i]; m = fmaxf(m, sv[cq][i]); }
+                    mx[cq] = m;
+                    mxo[cq] = __shfl_xor(m, 32);
+                } else if constexpr (c < 2 * NQ) {
+                    constexpr int cq = c - NQ;
+                    const float m = fmaxf(mx[cq], mxo[cq]) * c2;
+                    const float m_new = m > m_run[cq] + 8.f ? m : m_run[cq];
+                    m_use[cq] = m_new == -INFINITY ? 0.f : m_new;
+                    grew = grew | ((m_new > m_run[cq]) & (m_run[cq] != -INFINITY));
+                    alpha[cq] = __builtin_amdgcn_exp2f(m_run[cq] - m_use[cq]);
+                    m_run[cq] = m_new;
+                    sum[cq] = 0.f;
+                } else {
+                    constexpr int cq = (c - 2 * NQ) / 5, part = (c - 2 * NQ) % 5;
+                    if constexpr (part < 4) {
+#pragma unroll
+                        for (int i = part * 4; i < part * 4 + 4; ++i) {
+                            sv[cq][i] = __builtin_amdgcn_exp2f(fmaf(sv[cq][i], c2, -m_use[cq]));
+                            sum[cq] += sv[cq][i];
+                            // keeps the chunk where it is written: its results are first used
+                            // after the branch below, and the compiler would otherwise sink
+                            // the arithmetic there, out of the shadow of the MFMAs
+                            asm volatile("" : "+v"(sv[cq][i]));
+                        }
+                        asm volatile("" : "+v"(sum[cq]));
+                    } else {
+#pragma unroll
+                        for (int vf = 0; vf < NVF; ++vf) {
+                            if constexpr (BF16) {
+                                const int o = vf * 8;
+                                Pf[vf][cq] = to_bf16_frag(sv[cq][o + 0], sv[cq][o + 1], sv[cq][o + 2],
+                                                              sv[cq][o + 3], sv[cq][o + 4], sv[cq][o + 5],
+                                                              sv[cq][o + 6], sv[cq][o + 7]);
+                            } else {
+                                const int o = vf * 4;
+                                Pf[vf][cq] = make_uint4(f2u(sv[cq][o + 0]), f2u(sv[cq][o + 1]),
+                                                            f2u(sv[cq][o + 2]), f2u(sv[cq][o + 3]));
+                            }
+                            asm volatile("" : "+v"(Pf[vf][cq].x), "+v"(Pf[vf][cq].y),
+                                             "+v"(Pf[vf][cq].z), "+v"(Pf[vf][cq].w));
+                        }
+                        l_run[cq] = l_run[cq] * alpha[cq] + sum[cq];
+                        asm volatile("" : "+v"(l_run[cq]));
+                    }
+                }
+            };
+            auto group = [&](auto Gc) {
+                constexpr int g = decltype(Gc)::value;
+                if constexpr (g < GPV) {
+                    constexpr int vf = g / NDB, db = g % NDB;
+#pragma unroll
+                    for (int cq = 0; cq < NQ; ++cq)
+                        acc_o[db][cq] = mfma16<BF16>(vr[sb][db * NVF + vf], Pf[vf][cq], acc_o[db][cq]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    vr[sb][db * NVF + vf] = load_frag(vrs, lane_off, voff, db * NVF + vf);
+                } else {
+                    constexpr int fr = g - GPV;
+                    uint4 &kb = sb == 0 ? kreg[0][fr] : k1r[fr];
+#pragma unroll
+                    for (int cq = 0; cq < NQ; ++cq) {
+                        if constexpr (BF16) {
+                            qk_mfma_bf16(S[ob][cq], kb, qacc[cq][fr], fr == 0);
+                        } else {
+                            floatx16 z;
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) z[i] = 0.f;
+                            S[ob][cq] = mfma16<BF16>(kb, qf[cq][fr], fr == 0 ? z : S[ob][cq]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    kb = load_frag(krs, lane_off, knext, fr);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // this group's share of the softmax chunks
+                constexpr int c0 = g * C / G, c1 = (g + 1) * C / G;
+                auto run = [&](auto Ic) { chunk(IntC<c0 + decltype(Ic)::value>{}); };
+                static_for<0, c1 - c0>(run);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            static_for<0, G>(group);
+            if (__any(grew)) {
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            float a = acc_o[db][cq][i], tmp;
+                            asm volatile("v_accvgpr_read_b32 %1, %0\n\t"
+                                         "v_mul_f32 %1, %1, %2\n\t"
+                                         "v_accvgpr_write_b32 %0, %1"
+                                         : "+a"(a), "=&v"(tmp)
+                                         : "v"(alpha[cq]));
+                            acc_o[db][cq][i] = a;
+                        }
+                asm volatile("s_nop 7");
+            }
+        };
+        auto drain = [&](auto SBc) {   // O^T += V(n_fast-1)^T P(n_fast-1)^T
+            constexpr int sb = decltype(SBc)::value;
+#pragma unroll
+            for (int vf = 0; vf < NVF; ++vf)
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int cq = 0; cq < NQ; ++cq)
+                        acc_o[db][cq] = mfma16<BF16>(vr[sb][db * NVF + vf], Pf[vf][cq], acc_o[db][cq]);
+        };
+        int t = 0;
+        for (; t + 1 < n_fast; t += 2) {
+            iter(t, IntC<0>{});
+            iter(t + 1, IntC<1>{});
+        }
+        // V(n_fast - 1) sits in the buffer of parity n_fast & 1; both K buffers hold K(n_fast)
+        if (t < n_fast) {
+            iter(t, IntC<0>{});
+            drain(IntC<1>{});
+        } else {
+            drain(IntC<0>{});
+        }
+    }
+    }
+    for (int t = n_fast; t < n_tiles; ++t) {
         const unsigned off = tile_off(t);
         const int ktok0 = tile_ktok0(t);
         const unsigned knext = tile_off(t + 1 < n_tiles ? t + 1 : t);
