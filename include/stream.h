@@ -141,6 +141,32 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
                                  void *O, float *lse, float *mass,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The "top-k indices" and "update" lines of Algorithm 2 (Appendix C) as a pass of their own.
+ * stream_prune performs this step inside its scoring kernels; this entry point applies it to
+ * branch scores that already sit in memory.
+ *
+ * For each of `rows` independent rows: the row's first node_count[row] nodes
+ * [node_first[row][j], node_last[row][j]] (key-block ranges, inclusive) are split at
+ * m = floor((first + last + 1) / 2) into a left branch [first, m-1] (position 2j) and a right
+ * branch [m, last] (position 2j+1) whose scores are branch_score[row][2j] and [2j+1].  An empty
+ * branch and a branch whose score is -inf (no valid block under the mask C) are dropped; of the
+ * others the `topk` with the largest scores are kept, equal scores going to the lower position.
+ * The kept branches, in position order, overwrite the head of the row's node list and
+ * node_count[row] becomes their number; list slots after it are left as they were.
+ *
+ *   branch_score  float [rows, 2 * topk_max], 8-byte aligned; must hold no NaN
+ *   node_first    int32 [rows, topk_max], in/out
+ *   node_last     int32 [rows, topk_max], in/out
+ *   node_count    int32 [rows], in/out; values outside [0, topk_max] are clamped
+ *   1 <= topk <= topk_max <= 64; rows >= 0 (0 is a no-op: the pointers are not looked at).
+ * Errors: STREAM_EINVAL (null pointer, misaligned scores, bad sizes), STREAM_EUNSUPPORTED
+ * (topk_max > 64, more than 2^36 rows), STREAM_EDEVICE.  No workspace, no synchronisation.
+ */
+stream_status stream_select_update(const float *branch_score, int *node_first, int *node_last,
+                                   int *node_count, long long rows, int topk, int topk_max,
+                                   void *hip_stream);
+
 const char *stream_status_str(stream_status s);
 
 #ifdef __cplusplus

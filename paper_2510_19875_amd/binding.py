@@ -20,7 +20,7 @@ STREAM_F32, STREAM_BF16 = 0, 1
 
 EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
            "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
-           "stream_status_str"]
+           "stream_select_update", "stream_status_str"]
 
 
 class StreamShape(ctypes.Structure):
@@ -73,6 +73,8 @@ def load():
     lib.stream_sparse_attn.restype = ctypes.c_int
     lib.stream_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int, ctypes.c_float,
                                        vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.stream_select_update.restype = ctypes.c_int
+    lib.stream_select_update.argtypes = [vp, vp, vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.stream_status_str.restype = ctypes.c_char_p
     lib.stream_status_str.argtypes = [ctypes.c_int]
     _lib = lib
@@ -204,3 +206,25 @@ def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt,
     if rc != STREAM_OK:
         raise StreamError(rc, "stream_sparse_attn")
     return {"O": O, "lse": lse, "mass": mass, "workspace": workspace, "_keep": keep}
+
+
+def stream_select_update(score, node_first, node_last, node_count, topk: int):
+    """Top-k selection + node update of Alg. 2 on branch scores held in memory, in place.
+
+    score [rows, 2*kmax] fp32, node_first/node_last [rows, kmax] int32, node_count [rows] int32,
+    all contiguous device tensors; the node tensors are updated in place."""
+    lib = load()
+    for t in (score, node_first, node_last, node_count):
+        if not t.is_cuda:
+            raise ValueError("all arguments must be device tensors (the library has no CPU path)")
+        if not t.is_contiguous():
+            raise ValueError("all arguments must be contiguous")
+    if score.dtype != torch.float32 or any(t.dtype != torch.int32 for t in (node_first, node_last, node_count)):
+        raise ValueError("score must be float32, the node tensors int32")
+    rows, kmax = node_first.shape
+    if tuple(score.shape) != (rows, 2 * kmax) or tuple(node_last.shape) != (rows, kmax) or tuple(node_count.shape) != (rows,):
+        raise ValueError("shape mismatch")
+    rc = lib.stream_select_update(score.data_ptr(), node_first.data_ptr(), node_last.data_ptr(),
+                                  node_count.data_ptr(), rows, int(topk), kmax, _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_select_update")

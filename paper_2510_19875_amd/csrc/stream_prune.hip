@@ -6,7 +6,7 @@
 // reduces each 32x32 accumulator set to the masked maximum (score line of Alg. 2 / Eq. (4)),
 // ranks the 2k branch scores across its lanes, and writes the surviving nodes back in place in
 // positional order.  The node lists [heads, NB, k] are the only state: O(T) memory.
-#include "stream_common.h"
+#include "stream_select.h"
 
 #include <math.h>
 
@@ -58,13 +58,6 @@ __device__ __forceinline__ float wave_max(float v)
     const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
     const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
     return fmaxf(fmaxf(a, b), fmaxf(c, d));
-}
-
-// Order-preserving map of a float's bit pattern to an unsigned integer (-inf lowest).
-__device__ __forceinline__ unsigned sortable_bits(float v)
-{
-    const unsigned u = __builtin_bit_cast(unsigned, v + 0.f);   // -0 -> +0: equal as scores
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
 // One operand fragment (16 bytes per lane) times another, accumulated into a 32x32 tile.
@@ -141,7 +134,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     }
 
     // ---- node of this lane (node init line of Alg. 2 at the first level)
-    int f = 0, l = -1, n_src = k;                         // n_src: lanes that hold a node
+    int f = 0, l = -1;
     float sc = -INFINITY;
     bool live = false;
     if (first) {
@@ -159,7 +152,6 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             sc = p.ns[row * p.kmax + lane];
         }
         live = lane < c;
-        n_src = __builtin_amdgcn_readfirstlane(c);
         if (!live) { f = 0; l = -1; sc = -INFINITY; }
     }
     // ---- split at the midpoint; causal validity: a branch is valid iff it is non-empty and
@@ -264,22 +256,12 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     if (v0) s0 = need0 ? tile_score(pos0) : sc;
     if (v1) s1 = need1 ? tile_score(pos1) : sc;
 
-    // ---- top-k of the 2k branch scores: rank by counting.  A branch's key is 64 bits: the score
-    //      mapped to an order-preserving unsigned in the high word, the complemented branch
-    //      position (2*lane left, 2*lane+1 right) in the low word, so "larger key" means larger
-    //      score, and on equal scores the lower position.  Branch-free: one 64-bit compare per pair.
-    const unsigned long long key0 = ((unsigned long long)sortable_bits(s0) << 32) | (unsigned)~(2u * lane);
-    const unsigned long long key1 = ((unsigned long long)sortable_bits(s1) << 32) | (unsigned)~(2u * lane + 1u);
-    const int hi0 = (int)sortable_bits(s0), hi1 = (int)sortable_bits(s1);
-    int r0 = 0, r1 = 0;
-    for (int j = 0; j < n_src; ++j) {
-        const unsigned long long a0 = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi0, j) << 32) | (unsigned)~(2u * j);
-        const unsigned long long a1 = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi1, j) << 32) | (unsigned)~(2u * j + 1u);
-        r0 += (a0 > key0 ? 1 : 0) + (a1 > key0 ? 1 : 0);
-        r1 += (a0 > key1 ? 1 : 0) + (a1 > key1 ? 1 : 0);
-    }
-    const bool keep0 = v0 && r0 < k;
-    const bool keep1 = v1 && r1 < k;
+    // ---- top-k of the 2k branch scores (ties to the lower position): see select_topk_wave
+    const float sel_s[2] = {s0, s1};
+    const bool sel_v[2] = {v0, v1};
+    bool sel_keep[2];
+    select_topk_wave<2>(sel_s, sel_v, k, lane, sel_keep);
+    const bool keep0 = sel_keep[0], keep1 = sel_keep[1];
     const unsigned long long kb0 = __ballot(keep0), kb1 = __ballot(keep1);
     const int before = __popcll(kb0 & lt) + __popcll(kb1 & lt);
     const int p0 = before, p1 = before + (keep0 ? 1 : 0);

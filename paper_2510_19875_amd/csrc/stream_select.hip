@@ -1,0 +1,125 @@
+// stream_select_update: the top-k selection and node update of Alg. 2 as a pass of its own.
+// stream_prune fuses this step into the scoring kernel (the branch scores never leave the
+// chip); this entry point runs it from a score tensor in memory so that the step can be used
+// and measured alone.  A wavefront ranks one row at a time, several rows in a row.
+#include "stream_select.h"
+
+#include <math.h>
+
+namespace stream {
+
+struct SelectParams {
+    const float *score;   // [rows, 2 * kmax]
+    int *nf, *nl;         // [rows, kmax]
+    int *ncnt;            // [rows]
+    long long rows;
+    int k, kmax;
+};
+
+// Rows a wavefront handles, one after the other; the loads of the next row are in flight while
+// the current one is ranked, so that a wavefront keeps two rows' worth of memory requests going.
+constexpr int kSelectRowsPerWave = 8;
+
+// NB = 1 (kmax <= 32): lane j holds branch position j, i.e. side j % 2 of node j / 2;
+// NB = 2: lane j holds both children of node j.
+template <int NB>
+struct SelectRow {
+    int c, f, l;
+    float s[NB];
+};
+
+template <int NB>
+__device__ __forceinline__ SelectRow<NB> select_load(const SelectParams &p, long long row, int lane)
+{
+    SelectRow<NB> r;
+    r.c = 0; r.f = 0; r.l = -1;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) r.s[i] = -INFINITY;
+    const int node = NB == 2 ? lane : lane >> 1;
+    if (row < p.rows && node < p.kmax) {
+        // none of the loads waits for another: slots past the live count are allocated, just unused
+        const long long o = row * p.kmax;
+        r.c = p.ncnt[row];
+        r.f = p.nf[o + node];
+        r.l = p.nl[o + node];
+        if constexpr (NB == 2) {
+            const float2 s = *reinterpret_cast<const float2 *>(p.score + 2 * (o + lane));
+            r.s[0] = s.x; r.s[1] = s.y;
+        } else {
+            r.s[0] = p.score[2 * o + lane];
+        }
+    }
+    return r;
+}
+
+template <int NB>
+__global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // consecutive wavefronts take consecutive rows; a wavefront's own rows are a grid apart
+    const long long stride = (long long)gridDim.x * 4;
+    long long row = (long long)blockIdx.x * 4 + wave;
+    const int node = NB == 2 ? lane : lane >> 1;
+    SelectRow<NB> nx = select_load<NB>(p, row, lane);
+    for (int i = 0; i < kSelectRowsPerWave && row < p.rows; ++i, row += stride) {
+        const SelectRow<NB> cur = nx;
+        nx = select_load<NB>(p, row + stride, lane);
+        int c = __builtin_amdgcn_readfirstlane(cur.c);
+        c = c < 0 ? 0 : (c > p.kmax ? p.kmax : c);
+        const int f = cur.f, l = cur.l;
+        const bool live = node < c && f <= l;
+        const int m = (f + l + 1) >> 1;                     // children [f, m-1] and [m, l]
+        bool v[NB], keep[NB];
+        int first[NB], last[NB];
+        if constexpr (NB == 2) {
+            v[0] = live && m > f && cur.s[0] > -INFINITY;
+            v[1] = live && cur.s[1] > -INFINITY;
+            first[0] = f; last[0] = m - 1; first[1] = m; last[1] = l;
+        } else {
+            const bool right = lane & 1;
+            v[0] = live && (right || m > f) && cur.s[0] > -INFINITY;
+            first[0] = right ? m : f; last[0] = right ? l : m - 1;
+        }
+        select_topk_wave<NB>(cur.s, v, p.k, lane, keep);
+        // update: survivors overwrite the row's node list in positional order
+        const unsigned long long lt = (1ull << lane) - 1ull;
+        unsigned long long kb[NB];
+        int pos = 0, total = 0;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            kb[j] = __ballot(keep[j]);
+            pos += __popcll(kb[j] & lt);
+            total += __popcll(kb[j]);
+        }
+        const long long o = row * p.kmax;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (keep[j]) { p.nf[o + pos] = first[j]; p.nl[o + pos] = last[j]; }
+            pos += keep[j] ? 1 : 0;
+        }
+        if (lane == 0) p.ncnt[row] = total;
+    }
+}
+
+}  // namespace stream
+
+using namespace stream;
+
+extern "C" stream_status stream_select_update(const float *branch_score, int *node_first, int *node_last,
+                                              int *node_count, long long rows, int topk, int topk_max,
+                                              void *hip_stream)
+{
+    if (rows < 0 || topk < 1 || topk > topk_max) return STREAM_EINVAL;
+    if (topk_max > kMaxTopk) return STREAM_EUNSUPPORTED;
+    const long long grid = (rows + 4 * kSelectRowsPerWave - 1) / (4 * kSelectRowsPerWave);
+    if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
+    if (rows == 0) return STREAM_OK;                           // empty tensors may have no address
+    if (!branch_score || !node_first || !node_last || !node_count) return STREAM_EINVAL;
+    if ((uintptr_t)branch_score & 7) return STREAM_EINVAL;     // scores are read in pairs
+    SelectParams p;
+    p.score = branch_score; p.nf = node_first; p.nl = node_last; p.ncnt = node_count;
+    p.rows = rows; p.k = topk; p.kmax = topk_max;
+    hipLaunchKernelGGL(topk_max <= 32 ? select_kernel<1> : select_kernel<2>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
+    return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+}

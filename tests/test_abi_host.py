@@ -125,6 +125,25 @@ def test_bad_arguments_of_sparse_attn(lib):
     assert call(wsz=need - 1) == B.STREAM_EWORKSPACE
 
 
+def test_bad_arguments_of_select_update(lib):
+    fake = ctypes.c_void_p(4096)
+
+    def call(sc=fake, nf=fake, nl=fake, nc=fake, rows=8, k=4, kmax=8):
+        return lib.stream_select_update(sc, nf, nl, nc, rows, k, kmax, None)
+
+    assert call(sc=None) == B.STREAM_EINVAL
+    assert call(nf=None) == B.STREAM_EINVAL
+    assert call(nl=None) == B.STREAM_EINVAL
+    assert call(nc=None) == B.STREAM_EINVAL
+    assert call(sc=ctypes.c_void_p(4100)) == B.STREAM_EINVAL      # scores are read in pairs
+    assert call(rows=-1) == B.STREAM_EINVAL
+    assert call(k=0) == B.STREAM_EINVAL
+    assert call(k=9) == B.STREAM_EINVAL
+    assert call(k=65, kmax=65) == B.STREAM_EUNSUPPORTED
+    assert call(rows=1 << 40) == B.STREAM_EUNSUPPORTED
+    assert call(rows=0) == B.STREAM_OK                            # nothing to do, nothing launched
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     Q = torch.zeros(2, 64, 64)
