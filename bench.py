@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="named workload (default: the headline one)")
     ap.add_argument("--layers", type=int, default=0, help="resident input layers (default min(steps, 32))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-select", action="store_true", help="skip the standalone select-kernel measurement")
     ap.add_argument("--cpu-rows", type=int, default=1536)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -210,9 +211,47 @@ def main():
             "algorithmic_bytes_per_launch": float(Q_BYTES + K_BYTES * 0.25 + H * NB * (24 * kmax + 4)),
         },
     }
+    if not args.no_select:
+        result["select_roofline"] = select_standalone(kmax)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale)
     print(json.dumps(result))
+
+
+def select_standalone(kmax, rows=1 << 21, launches=12):
+    """The top-k selection + node update as a pass of its own (inside stream_prune it is fused
+    into the scoring kernel and moves no bytes): stream_select_update on a synthetic score
+    tensor, against the HBM roofline.  Algorithmic bytes per row: 2k scores + k node ranges +
+    the count read, k node ranges + the count written = 24k + 8."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(2510_19875)
+    sc = torch.randn((rows, 2 * kmax), device=dev, generator=g)
+    dead = torch.rand(sc.shape, device=dev, generator=g) < 0.1          # 10% invalid branches
+    sc = torch.where(dead, torch.full_like(sc, -float("inf")), sc)
+    span = 1 << 20                                                        # nodes stay splittable
+    nf = (torch.arange(kmax, device=dev, dtype=torch.int32) * span).repeat(rows, 1).contiguous()
+    nl = nf + (span - 1)
+    nc = torch.full((rows,), kmax, dtype=torch.int32, device=dev)
+    binding.stream_select_update(sc, nf, nl, nc, kmax)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(launches):
+        binding.stream_select_update(sc, nf, nl, nc, kmax)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / launches
+    bytes_per_row = 24 * kmax + 8
+    gbs = rows * bytes_per_row / (ms * 1e-3) / 1e9
+    return {"kernel": "select_kernel (stream_select_update: top-k select + in-place compaction)",
+            "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": gbs / PEAK_HBM_GBS, "rows": rows, "topk": kmax, "bytes_per_row": bytes_per_row,
+            "bytes_per_launch": rows * bytes_per_row, "avg_launch_ms": ms, "launches": launches}
 
 
 def cpu_baseline(w, layer, n_rows, scale):
