@@ -28,10 +28,11 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per level-kernel launch (mean of the 6 levels) at the headline workload, from the
-# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/cfg3_pmc_counters.txt:
-# FETCH_SIZE 1.132e6 x 2.0 (the factor a plain 268 MB copy shows for this counter) + WRITE_SIZE
-# 2.663e4 x 1.0, in KiB.  Only meaningful for that workload.
-LEVEL_KERNEL_HBM_BYTES = {"cfg3_T131072_gqa32x8_d128_bf16": (1.132e6 * 2.0 + 2.663e4) * 1024.0}
+# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/cfg3_pmc_counters.txt, per
+# launch of the level kernel in its default form (all levels of a row in one launch):
+# FETCH_SIZE 4.576e6 x 2.0 (the factor a plain 268 MB copy shows for this counter) + WRITE_SIZE
+# 1.716e4 x 1.0, in KiB.  Only meaningful for that workload and launch form.
+LEVEL_KERNEL_HBM_BYTES = {"cfg3_T131072_gqa32x8_d128_bf16": (4.576e6 * 2.0 + 1.716e4) * 1024.0}
 
 
 class HipEvents:
@@ -63,6 +64,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="resident input layers (default min(steps, 32))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-select", action="store_true", help="skip the standalone select-kernel measurement")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the k-sweep (stream_prune_multi) measurement")
+    ap.add_argument("--levels-per-launch", type=int, default=0,
+                    help="refinement levels per kernel launch (0 = library default: all in one)")
     ap.add_argument("--cpu-rows", type=int, default=1536)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -99,12 +103,14 @@ def main():
     ws_p = ws_a = None
     tiles = torch.zeros((1,), dtype=torch.int64, device=dev)
 
+    lpl = args.levels_per_launch
+
     def step(i, events=None, count_tiles=False):
         nonlocal ws_p, ws_a
         Q, K, V = layers[i % n_layers]
         r = binding.stream_prune(Q, K, H, Hkv, b, topk, cu_seqlens=cu, want_score=True,
                                  workspace=ws_p, out=out_p, level_events=events,
-                                 want_tiles=count_tiles)
+                                 want_tiles=count_tiles, levels_per_launch=lpl)
         ws_p = r["workspace"]
         a = binding.stream_sparse_attn(Q, K, V, H, Hkv, b, out_p["idx"], out_p["cnt"], scale,
                                        cu_seqlens=cu, want_lse=True, want_mass=True,
@@ -140,7 +146,7 @@ def main():
                           ctypes.POINTER(ctypes.c_void_p * (2 * levels))).contents
         marks[2 * i].record()
         r = binding.stream_prune(Q, K, H, Hkv, b, topk, cu_seqlens=cu, want_score=True,
-                                 workspace=ws_p, out=out_p, level_events=sub)
+                                 workspace=ws_p, out=out_p, level_events=sub, levels_per_launch=lpl)
         marks[2 * i + 1].record()
         binding.stream_sparse_attn(Q, K, V, H, Hkv, b, out_p["idx"], out_p["cnt"], scale,
                                    cu_seqlens=cu, want_lse=True, want_mass=True,
@@ -153,8 +159,9 @@ def main():
     ms_per_step = total_s * 1e3 / K_steps
     prune_ms = [marks[2 * i].elapsed_time(marks[2 * i + 1]) for i in range(K_steps)]
     attn_ms = [marks[2 * i + 1].elapsed_time(marks[2 * i + 2]) for i in range(K_steps)]
+    n_launch = 1 if lpl <= 0 else -(-levels // lpl)              # refinement-kernel launches per step
     level_ms = np.array([[ev.elapsed_ms(2 * levels * i + 2 * l, 2 * levels * i + 2 * l + 1)
-                          for l in range(levels)] for i in range(K_steps)])
+                          for l in range(n_launch)] for i in range(K_steps)])
     tok_heads = float(T) * H
     value = tok_heads / (ms_per_step * 1e-3)
 
@@ -165,7 +172,7 @@ def main():
     tile_flop = 2.0 * b * b * d
     flops_per_step = np.array([tile_counts[i % n_layers] for i in range(K_steps)]) * tile_flop
     level_total_s = level_ms.sum() * 1e-3
-    launches = levels * K_steps
+    launches = n_launch * K_steps
     achieved_tflops = flops_per_step.sum() / level_total_s / 1e12
     peak_mem = torch.cuda.max_memory_allocated()
     tensor_bytes = sum(t.numel() * t.element_size() for t in layers[0]) + \
@@ -193,12 +200,15 @@ def main():
         "attn_tflops": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12,
         "attn_frac_of_mfma_peak": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
         "level_kernel_ms": [float(x) for x in level_ms.mean(axis=0)],
+        "levels": levels, "level_kernel_launches_per_step": n_launch,
         "tiles_scored_per_step": float(np.mean(tile_counts)),
         "peak_device_bytes": int(peak_mem),
         "workspace_plus_state_bytes": int(ws_p.numel() + ws_a.numel()),
         "tensor_bytes_one_layer": int(tensor_bytes),
         "roofline": {
-            "kernel": "level_kernel (branch scorer + top-k select + in-place compaction)",
+            "kernel": "level_kernel (branch scorer + top-k select + compaction, all levels of a row per launch)"
+                      if n_launch == 1 else
+                      "level_kernel (branch scorer + top-k select + in-place compaction)",
             "bound": "mfma",
             "achieved": achieved_tflops,
             "peak": PEAK_BF16_MFMA_TFLOPS,
@@ -207,15 +217,68 @@ def main():
             "flop_per_launch": float(flops_per_step.sum() / launches),
             "avg_launch_ms": float(level_ms.sum() / launches),
             "launches": launches,
-            "traffic": LEVEL_KERNEL_HBM_BYTES.get(w.name),
-            "algorithmic_bytes_per_launch": float(Q_BYTES + K_BYTES * 0.25 + H * NB * (24 * kmax + 4)),
+            "traffic": LEVEL_KERNEL_HBM_BYTES.get(w.name) if n_launch == 1 else None,
+            "algorithmic_bytes_per_launch": float(Q_BYTES + K_BYTES + H * NB * (8 * kmax + 4)) if n_launch == 1
+                                            else float(Q_BYTES + K_BYTES * 0.25 + H * NB * (24 * kmax + 4)),
         },
     }
     if not args.no_select:
         result["select_roofline"] = select_standalone(kmax)
+    if not args.no_sweep and w.batch == 1:
+        result["k_sweep"] = k_sweep(w, layers[0])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale)
     print(json.dumps(result))
+
+
+def k_sweep(w, layer, reps=4):
+    """stream_prune_multi over k, k/2, ..., 1 (the values a binary search over k visits) against
+    the same values as separate stream_prune calls: time and block scores computed."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, _ = layer
+    ks = []
+    k = w.topk[0]
+    while k >= 1:
+        ks.append(k)
+        k //= 2
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    st = {}
+
+    def multi():
+        r = binding.stream_prune_multi(Q, K, w.heads, w.kv_heads, w.block, ks, workspace=st.get("ws"),
+                                       out=st.get("out"), want_tiles=True)
+        st["ws"], st["out"], st["tiles"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}, r["tiles"]
+
+    multi_ms = timed(multi)
+    multi_tiles = int(st["tiles"].item())
+    sep_ms, sep_tiles = 0.0, 0
+    for k in ks:
+        s1 = {}
+
+        def one():
+            r = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, k, workspace=s1.get("ws"),
+                                     out=s1.get("out"), want_tiles=True)
+            s1["ws"], s1["out"], s1["tiles"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}, r["tiles"]
+
+        sep_ms += timed(one)
+        sep_tiles += int(s1["tiles"].item())
+    return {"topk_list": ks, "sweep_ms": multi_ms, "separate_calls_ms": sep_ms,
+            "speedup": sep_ms / multi_ms, "block_scores_sweep": multi_tiles,
+            "block_scores_separate_calls": sep_tiles}
 
 
 def select_standalone(kmax, rows=1 << 21, launches=12):

@@ -80,10 +80,14 @@ typedef struct {
        products) the kernels computed; the caller zeroes it.                                 */
     unsigned long long *tiles_scored;
     /* HOST array of 2 * stream_prune_levels() hipEvent_t handles created by the caller, or NULL:
-       event 2i is recorded on hip_stream right before the launch of level i+1's kernel and event
-       2i+1 right after it, so the caller can read each level kernel's duration after its own
-       synchronisation.  Nothing is waited on.                                                  */
+       event 2j is recorded on hip_stream right before the j-th launch of the refinement kernel
+       and event 2j+1 right after it (there are ceil(levels / levels_per_launch) launches), so
+       the caller can read each launch's duration after its own synchronisation.  Nothing is
+       waited on.                                                                               */
     void *const *level_events;
+    /* Refinement levels every row runs back to back inside one kernel launch: 0 = the
+       library's default (all of them in one launch), 1 = one launch per level, n = at most n. */
+    int levels_per_launch;
 } stream_prune_diag;
 
 /* NB = total number of query blocks of the (packed) shape, or -1 on a bad shape. */
@@ -139,6 +143,34 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
                                  const stream_shape *shape,
                                  const int *idx, const int *cnt, int topk_max, float scale,
                                  void *O, float *lse, float *mass,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Algorithm 2 for several values of k over the same Q and K in one call: the tracing driver of
+ * Section 3 estimates the mask again and again while it searches for the smallest k that
+ * preserves the model's output.  K is packed once; a (head, query block) row runs Algorithm 2
+ * for every k of the list in turn inside one kernel, keeping its Q tile on chip and reusing every
+ * block score it has already computed (a block's score does not depend on k), so the values
+ * after the first mostly cost a few selections.
+ *
+ * Result i (i < n_k) is exactly what stream_prune returns for topk = topk_list[i] (every
+ * sequence of a ragged batch uses that same k):
+ *   topk_list  HOST int[n_k], each in [1, topk_max]; n_k <= 32; any order (largest first reuses
+ *              the most)
+ *   idx        int32 [heads, n_k, NB, topk_max]
+ *   cnt        int32 [heads, n_k, NB]
+ *   score      float [heads, n_k, NB, topk_max] or NULL
+ *   diag       as for stream_prune; the trace is [levels, heads, n_k, NB, topk_max, 2] with
+ *              `levels` = stream_prune_levels() of the smallest k; tiles_scored counts the
+ *              block scores actually computed; levels_per_launch is ignored
+ *   workspace  stream_prune_multi_workspace_bytes(shape, n_k, topk_max) bytes, 256-byte aligned
+ * Errors: as stream_prune; STREAM_EUNSUPPORTED when n_k > 32.
+ */
+size_t stream_prune_multi_workspace_bytes(const stream_shape *shape, int n_k, int topk_max);
+
+stream_status stream_prune_multi(const void *Q, const void *K, const stream_shape *shape,
+                                 const int *topk_list, int n_k, int topk_max,
+                                 int *idx, int *cnt, float *score, const stream_prune_diag *diag,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

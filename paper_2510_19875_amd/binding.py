@@ -20,6 +20,7 @@ STREAM_F32, STREAM_BF16 = 0, 1
 
 EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
            "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
+           "stream_prune_multi_workspace_bytes", "stream_prune_multi",
            "stream_select_update", "stream_status_str"]
 
 
@@ -35,7 +36,7 @@ class StreamShape(ctypes.Structure):
 
 class StreamPruneDiag(ctypes.Structure):
     _fields_ = [("trace", ctypes.c_void_p), ("tiles_scored", ctypes.c_void_p),
-                ("level_events", ctypes.POINTER(ctypes.c_void_p))]
+                ("level_events", ctypes.POINTER(ctypes.c_void_p)), ("levels_per_launch", ctypes.c_int)]
 
 
 class StreamError(RuntimeError):
@@ -73,6 +74,11 @@ def load():
     lib.stream_sparse_attn.restype = ctypes.c_int
     lib.stream_sparse_attn.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int, ctypes.c_float,
                                        vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.stream_prune_multi_workspace_bytes.restype = ctypes.c_size_t
+    lib.stream_prune_multi_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.c_int]
+    lib.stream_prune_multi.restype = ctypes.c_int
+    lib.stream_prune_multi.argtypes = [vp, vp, sp, ip, ctypes.c_int, ctypes.c_int, vp, vp, vp,
+                                       ctypes.POINTER(StreamPruneDiag), vp, ctypes.c_size_t, vp]
     lib.stream_select_update.restype = ctypes.c_int
     lib.stream_select_update.argtypes = [vp, vp, vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.stream_status_str.restype = ctypes.c_char_p
@@ -123,7 +129,7 @@ def num_blocks(shape: StreamShape) -> int:
 def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
                  topk, cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
                  want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None,
-                 level_events=None):
+                 level_events=None, levels_per_launch: int = 0):
     """Algorithm 2 for every (head, query block).  Q [H, T, d], K [Hkv, T, d] on the GPU.
 
     topk: int, or one int per sequence.  Returns dict(idx [H, NB, kmax] int32, cnt [H, NB] int32,
@@ -168,15 +174,57 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
         if len(level_events) < 2 * levels:
             raise ValueError("level_events needs 2 events per level")
         diag.level_events = ctypes.cast(level_events, ctypes.POINTER(ctypes.c_void_p))
+    diag.levels_per_launch = int(levels_per_launch)
     rc = lib.stream_prune(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape),
                           kmax if ks is None else 0, k_arr, kmax,
                           idx.data_ptr(), cnt.data_ptr(), score.data_ptr() if score is not None else None,
-                          ctypes.byref(diag) if (want_trace or want_tiles or level_events is not None) else None,
+                          ctypes.byref(diag) if (want_trace or want_tiles or level_events is not None
+                                                 or levels_per_launch) else None,
                           workspace.data_ptr(), workspace.numel(), _stream_ptr())
     if rc != STREAM_OK:
         raise StreamError(rc, "stream_prune")
     return {"idx": idx, "cnt": cnt, "score": score, "trace": trace, "tiles": tiles,
             "levels": levels, "workspace": workspace, "_keep": keep}
+
+
+def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
+                       topk_list: Sequence[int], cu_seqlens: Optional[Sequence[int]] = None,
+                       want_score: bool = False, want_tiles: bool = False, workspace=None, out=None):
+    """Algorithm 2 for several k over the same Q, K in one call.  Returns dict(idx
+    [H, n_k, NB, kmax] int32, cnt [H, n_k, NB] int32, score (optional) fp32, tiles (optional))."""
+    lib = load()
+    if not (Q.is_cuda and K.is_cuda):
+        raise ValueError("Q and K must be device tensors (the library has no CPU path)")
+    H, T, d = Q.shape
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K)
+    ks = [int(x) for x in topk_list]
+    n_k, kmax = len(ks), max(ks)
+    k_arr = (ctypes.c_int * n_k)(*ks)
+    NB = num_blocks(shape)
+    if NB < 0:
+        raise StreamError(STREAM_EINVAL, "stream_num_blocks")
+    dev = Q.device
+    if out is None:
+        idx = torch.empty((H, n_k, NB, kmax), dtype=torch.int32, device=dev)
+        cnt = torch.empty((H, n_k, NB), dtype=torch.int32, device=dev)
+        score = torch.empty((H, n_k, NB, kmax), dtype=torch.float32, device=dev) if want_score else None
+    else:
+        idx, cnt, score = out["idx"], out["cnt"], out.get("score")
+    need = lib.stream_prune_multi_workspace_bytes(ctypes.byref(shape), n_k, kmax)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+    diag = StreamPruneDiag()
+    tiles = None
+    if want_tiles:
+        tiles = torch.zeros((1,), dtype=torch.int64, device=dev)
+        diag.tiles_scored = tiles.data_ptr()
+    rc = lib.stream_prune_multi(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape), k_arr, n_k, kmax,
+                                idx.data_ptr(), cnt.data_ptr(), score.data_ptr() if score is not None else None,
+                                ctypes.byref(diag) if want_tiles else None,
+                                workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_prune_multi")
+    return {"idx": idx, "cnt": cnt, "score": score, "tiles": tiles, "workspace": workspace, "_keep": keep}
 
 
 def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,

@@ -15,20 +15,27 @@ namespace stream {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+constexpr int kMaxSweep = 32;        // values of k in one stream_prune_multi call
+constexpr int kScoreCache = 1024;    // entries of a row's block-score cache (k sweep)
+
 struct PruneParams {
     const char *Q;
     const char *Kp;              // packed K tiles [kv_head][global block][b * d]
     long long q_sh_b, q_st_b;    // byte strides of Q (head, token)
     int H, g, NB, kmax;
-    int level;                   // 1-based refinement level of this launch
+    int level_begin, level_end;  // 1-based refinement levels this launch runs for every row
+    int max_levels;              // levels of the deepest row (length of the trace)
     int *nf, *nl;                // node ranges [H, NB, kmax]
     float *ns;                   // node scores (score of the node's representative block)
     int *ncnt;                   // live nodes per row [H, NB]
     int *idx, *cnt;              // outputs, written by a row's last level
     float *score;                // nullable
     unsigned long long *tiles;   // nullable diagnostic counter
+    int *trace;                  // nullable diagnostic [max_levels, H, NB, kmax, 2]
     WgMap map;
     SeqTable seqs;
+    int n_k;                     // k sweep (MULTI kernels): values of k, outputs [H, n_k, NB, ...]
+    int klist[kMaxSweep];
 };
 
 __device__ __forceinline__ void wave_sync()
@@ -81,7 +88,7 @@ __device__ __forceinline__ floatx16 mfma_frag(const uint4 &a, const uint4 &b, fl
 // Template parameters: element type, head dim, 32-row groups of Q per wavefront (MB), 32-key
 // groups of K per wavefront (NG), wavefronts per row (WPR: 1, or 4 = 2 query halves x 2 key
 // halves for block 128), occupancy hint.
-template <bool BF16, int D, int MB, int NG, int WPR, int OCC>
+template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI>
 __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -91,6 +98,11 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     constexpr int GROUP_BYTES = 32 * D * ES;
     __shared__ int s_rep[4][2 * kMaxTopk];
     __shared__ float s_sc[4][2 * kMaxTopk];
+    __shared__ int s_nf[4][kMaxTopk], s_nl[4][kMaxTopk];   // survivors on their way to the next level
+    __shared__ float s_ns[4][kMaxTopk];
+    // k sweep: block scores this row has computed so far, whatever k they were computed for
+    // (entry = block id << 32 | score bits, direct mapped; a miss only costs a recomputation)
+    __shared__ unsigned long long s_cache[MULTI ? 4 : 1][MULTI ? kScoreCache : 1];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keep it scalar
@@ -103,10 +115,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int h = kvh * p.g + (int)(rk % p.g);
     const int sq = seq_of_block(p.seqs, gb);
     const SeqDesc sd = p.seqs.d[sq];
-    if (p.level > sd.levels) return;
-    const int q = gb - sd.blk0, N = sd.nblk, k = sd.k, L = sd.len;
-    const long long row = (long long)h * p.NB + gb;
-    const bool first = p.level == 1;
+    if (!MULTI && p.level_begin > sd.levels) return;
+    const int q = gb - sd.blk0, N = sd.nblk, L = sd.len;
     const int qh = WPR == 4 ? (wave >> 1) : 0;            // query half / key half of this wavefront
     const int kh = WPR == 4 ? (wave & 1) : 0;
 
@@ -133,11 +143,30 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    if constexpr (MULTI) {
+        for (int i = lane; i < kScoreCache; i += 64) s_cache[wave][i] = ~0ull;
+        wave_sync();
+    }
+    unsigned long long tiles_done = 0;
+    const int n_k = MULTI ? p.n_k : 1;
+    for (int ki = 0; ki < n_k; ++ki) {
+    // this pass's k, its number of levels and its output row
+    int k = sd.k, levels = sd.levels;
+    long long row = (long long)h * p.NB + gb;
+    if constexpr (MULTI) {
+        k = p.klist[ki];
+        const int per = (N + k - 1) / k;                      // max(1, ceil(log2(ceil(N / k)))) levels
+        levels = per <= 2 ? 1 : 32 - __builtin_clz(per - 1);
+        row = ((long long)h * n_k + ki) * p.NB + gb;
+    }
+    const int level_begin = MULTI ? 1 : p.level_begin;
+    const int level_last = MULTI ? levels : (p.level_end < levels ? p.level_end : levels);
+
     // ---- node of this lane (node init line of Alg. 2 at the first level)
     int f = 0, l = -1;
     float sc = -INFINITY;
     bool live = false;
-    if (first) {
+    if (level_begin == 1) {
         if (lane < k) {
             f = (int)(((long long)lane * N) / k);
             l = (int)(((long long)(lane + 1) * N) / k) - 1;
@@ -154,21 +183,6 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         live = lane < c;
         if (!live) { f = 0; l = -1; sc = -INFINITY; }
     }
-    // ---- split at the midpoint; causal validity: a branch is valid iff it is non-empty and
-    //      starts at or before the query block; its representative is its first block.
-    const int m = (f + l + 1) >> 1;
-    const bool v0 = live && m > f && f <= q;              // left child [f, m-1]
-    const bool v1 = live && m <= q;                       // right child [m, l] (never empty)
-    const bool need0 = v0 && first;                       // otherwise the parent's score carries over
-    const bool need1 = v1 && (first || m > f);
-
-    const unsigned long long lt = (1ull << lane) - 1ull;
-    const unsigned long long b0 = __ballot(need0), b1 = __ballot(need1);
-    const int n0 = __popcll(b0), nt = n0 + __popcll(b1);
-    const int pos0 = __popcll(b0 & lt), pos1 = n0 + __popcll(b1 & lt);
-    if (need0) s_rep[wave][pos0] = f;
-    if (need1) s_rep[wave][pos1] = m;
-    wave_sync();
 
     // K tiles of this (kv head, sequence), from this wavefront's key half on
     const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(
@@ -177,127 +191,191 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const unsigned lane_off = lane * 16;
     const bool tail_row = (q == N - 1) && (L % B != 0);
     const int qtok0 = q * B + qh * 32 * MB;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    const long long o = row * p.kmax;
 
-    uint4 kf[NG][FR];
-    if (nt > 0) {
-        const int r0 = __builtin_amdgcn_readfirstlane(s_rep[wave][0]);
-        // same order as the refills in the loop below: waits count loads in issue order
-#pragma unroll
-        for (int fr = 0; fr < FR; ++fr)
-#pragma unroll
-            for (int cb = 0; cb < NG; ++cb) {
-                kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * FR + fr);
-                __builtin_amdgcn_sched_barrier(0);
+    // A row runs its levels level_begin .. level_last back to back: the Q tile stays in
+    // registers and the node list moves from one level to the next through LDS.
+    for (int level = level_begin; level <= level_last; ++level) {
+        const bool first = level == 1;
+        // ---- split at the midpoint; causal validity: a branch is valid iff it is non-empty and
+        //      starts at or before the query block; its representative is its first block.
+        const int m = (f + l + 1) >> 1;
+        const bool v0 = live && m > f && f <= q;              // left child [f, m-1]
+        const bool v1 = live && m <= q;                       // right child [m, l] (never empty)
+        bool need0 = v0 && first;                             // otherwise the parent's score carries over
+        bool need1 = v1 && (first || m > f);
+        float c0 = 0.f, c1 = 0.f;
+        bool hit0 = false, hit1 = false;
+        if constexpr (MULTI) {
+            // a score of the same block computed earlier for this row (another k, another level)
+            if (need0) {
+                const unsigned long long e = s_cache[wave][f & (kScoreCache - 1)];
+                hit0 = (int)(e >> 32) == f;
+                c0 = __builtin_bit_cast(float, (unsigned)e);
             }
-    }
-    for (int t = 0; t < nt; ++t) {
-        const int r = __builtin_amdgcn_readfirstlane(s_rep[wave][t]);
-        const int tn = t + 1 < nt ? t + 1 : t;
-        const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[wave][tn]) * (unsigned)TILE_BYTES;
-        floatx16 acc[MB][NG];
+            if (need1) {
+                const unsigned long long e = s_cache[wave][m & (kScoreCache - 1)];
+                hit1 = (int)(e >> 32) == m;
+                c1 = __builtin_bit_cast(float, (unsigned)e);
+            }
+            need0 = need0 && !hit0;
+            need1 = need1 && !hit1;
+        }
+
+        const unsigned long long b0 = __ballot(need0), b1 = __ballot(need1);
+        const int n0 = __popcll(b0), nt = n0 + __popcll(b1);
+        const int pos0 = __popcll(b0 & lt), pos1 = n0 + __popcll(b1 & lt);
+        if (need0) s_rep[wave][pos0] = f;
+        if (need1) s_rep[wave][pos1] = m;
+        wave_sync();
+
+        uint4 kf[NG][FR];
+        if (nt > 0) {
+            const int r0 = __builtin_amdgcn_readfirstlane(s_rep[wave][0]);
+            // same order as the refills in the loop below: waits count loads in issue order
 #pragma unroll
-        for (int rb = 0; rb < MB; ++rb)
+            for (int fr = 0; fr < FR; ++fr)
 #pragma unroll
-            for (int cb = 0; cb < NG; ++cb)
+                for (int cb = 0; cb < NG; ++cb) {
+                    kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * FR + fr);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
+        for (int t = 0; t < nt; ++t) {
+            const int r = __builtin_amdgcn_readfirstlane(s_rep[wave][t]);
+            const int tn = t + 1 < nt ? t + 1 : t;
+            const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[wave][tn]) * (unsigned)TILE_BYTES;
+            floatx16 acc[MB][NG];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+            for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
-        for (int fr = 0; fr < FR; ++fr) {
+                for (int cb = 0; cb < NG; ++cb)
 #pragma unroll
-            for (int cb = 0; cb < NG; ++cb) {
+                    for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+#pragma unroll
+            for (int fr = 0; fr < FR; ++fr) {
+#pragma unroll
+                for (int cb = 0; cb < NG; ++cb) {
+#pragma unroll
+                    for (int rb = 0; rb < MB; ++rb)
+                        acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
+                    // the fragment is consumed: refill its registers from the next tile right here,
+                    // so that every fragment of the next tile has a whole tile of MFMA time to arrive
+                    // (the scheduling barriers stop the compiler from sinking the loads to the end)
+                    __builtin_amdgcn_sched_barrier(0);
+                    kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * FR + fr);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            float mx = -INFINITY;
+            if (!(r == q || tail_row)) {
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
-                    acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
-                // the fragment is consumed: refill its registers from the next tile right here,
-                // so that every fragment of the next tile has a whole tile of MFMA time to arrive
-                // (the scheduling barriers stop the compiler from sinking the loads to the end)
-                __builtin_amdgcn_sched_barrier(0);
-                kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * FR + fr);
-                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int cb = 0; cb < NG; ++cb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
+            } else {
+                // diagonal block: token-level causal mask; last block of a sequence: padded rows/cols.
+                // 32x32 accumulator layout: lane holds column (lane % 32); element i is row
+                // 8*(i/4) + 4*(lane/32) + (i%4).
+                const int ktok0 = r * B + kh * 32 * NG;
+#pragma unroll
+                for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < NG; ++cb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                            const int tk = ktok0 + cb * 32 + (lane & 31);
+                            if (tq < L && tk <= tq) mx = fmaxf(mx, acc[rb][cb][i]);
+                        }
             }
+            mx = wave_max(mx);
+            if (lane == 0) s_sc[wave][t] = mx;
         }
-        float mx = -INFINITY;
-        if (!(r == q || tail_row)) {
-#pragma unroll
-            for (int rb = 0; rb < MB; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < NG; ++cb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
-        } else {
-            // diagonal block: token-level causal mask; last block of a sequence: padded rows/cols.
-            // 32x32 accumulator layout: lane holds column (lane % 32); element i is row
-            // 8*(i/4) + 4*(lane/32) + (i%4).
-            const int ktok0 = r * B + kh * 32 * NG;
-#pragma unroll
-            for (int rb = 0; rb < MB; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < NG; ++cb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                        const int tk = ktok0 + cb * 32 + (lane & 31);
-                        if (tq < L && tk <= tq) mx = fmaxf(mx, acc[rb][cb][i]);
-                    }
+        tiles_done += (unsigned long long)nt;
+        wave_sync();
+        if constexpr (WPR == 4) __syncthreads();
+
+        auto tile_score = [&](int t) -> float {
+            if constexpr (WPR == 4)
+                return fmaxf(fmaxf(s_sc[0][t], s_sc[1][t]), fmaxf(s_sc[2][t], s_sc[3][t]));
+            else
+                return s_sc[wave][t];
+        };
+        float s0 = -INFINITY, s1 = -INFINITY;
+        if (v0) s0 = need0 ? tile_score(pos0) : (hit0 ? c0 : sc);
+        if (v1) s1 = need1 ? tile_score(pos1) : (hit1 ? c1 : sc);
+        if constexpr (MULTI) {
+            if (need0) s_cache[wave][f & (kScoreCache - 1)] = ((unsigned long long)(unsigned)f << 32) | __builtin_bit_cast(unsigned, s0);
+            if (need1) s_cache[wave][m & (kScoreCache - 1)] = ((unsigned long long)(unsigned)m << 32) | __builtin_bit_cast(unsigned, s1);
         }
-        mx = wave_max(mx);
-        if (lane == 0) s_sc[wave][t] = mx;
-    }
-    wave_sync();
-    if constexpr (WPR == 4) __syncthreads();
+        // the four wavefronts of a row must all have read this level's tile scores before any of
+        // them writes the next level's
+        if constexpr (WPR == 4) __syncthreads();
 
-    auto tile_score = [&](int t) -> float {
-        if constexpr (WPR == 4)
-            return fmaxf(fmaxf(s_sc[0][t], s_sc[1][t]), fmaxf(s_sc[2][t], s_sc[3][t]));
-        else
-            return s_sc[wave][t];
-    };
-    float s0 = -INFINITY, s1 = -INFINITY;
-    if (v0) s0 = need0 ? tile_score(pos0) : sc;
-    if (v1) s1 = need1 ? tile_score(pos1) : sc;
+        // ---- top-k of the 2k branch scores (ties to the lower position): see select_topk_wave
+        const float sel_s[2] = {s0, s1};
+        const bool sel_v[2] = {v0, v1};
+        bool sel_keep[2];
+        select_topk_wave<2>(sel_s, sel_v, k, lane, sel_keep);
+        const bool keep0 = sel_keep[0], keep1 = sel_keep[1];
+        const unsigned long long kb0 = __ballot(keep0), kb1 = __ballot(keep1);
+        const int before = __popcll(kb0 & lt) + __popcll(kb1 & lt);
+        const int p0 = before, p1 = before + (keep0 ? 1 : 0);
+        const int newcnt = __popcll(kb0) + __popcll(kb1);
+        const bool writer = WPR == 1 || wave == 0;
 
-    // ---- top-k of the 2k branch scores (ties to the lower position): see select_topk_wave
-    const float sel_s[2] = {s0, s1};
-    const bool sel_v[2] = {v0, v1};
-    bool sel_keep[2];
-    select_topk_wave<2>(sel_s, sel_v, k, lane, sel_keep);
-    const bool keep0 = sel_keep[0], keep1 = sel_keep[1];
-    const unsigned long long kb0 = __ballot(keep0), kb1 = __ballot(keep1);
-    const int before = __popcll(kb0 & lt) + __popcll(kb1 & lt);
-    const int p0 = before, p1 = before + (keep0 ? 1 : 0);
-    const int newcnt = __popcll(kb0) + __popcll(kb1);
-
-    // ---- update: survivors overwrite the row's node list in positional order
-    if (WPR == 1 || wave == 0) {
-        const long long o = row * p.kmax;
-        if (keep0) { p.nf[o + p0] = f; p.nl[o + p0] = m - 1; p.ns[o + p0] = s0; }
-        if (keep1) { p.nf[o + p1] = m; p.nl[o + p1] = l;     p.ns[o + p1] = s1; }
-        if (lane == 0) p.ncnt[row] = newcnt;
-        if (p.level == sd.levels) {
+        if (p.trace && writer) {
+            int *tr = p.trace + (((long long)(level - 1) * p.H * n_k * p.NB + row) * p.kmax) * 2;
+            if (keep0) { tr[2 * p0] = f; tr[2 * p0 + 1] = m - 1; }
+            if (keep1) { tr[2 * p1] = m; tr[2 * p1 + 1] = l; }
+            if (lane >= newcnt && lane < p.kmax) { tr[2 * lane] = -1; tr[2 * lane + 1] = -1; }
+        }
+        if (level == levels) {
             // every node is now a single block: emit I (ascending), pad, count
-            if (keep0) { p.idx[o + p0] = f; if (p.score) p.score[o + p0] = s0; }
-            if (keep1) { p.idx[o + p1] = m; if (p.score) p.score[o + p1] = s1; }
-            if (lane >= newcnt && lane < p.kmax) {
-                p.idx[o + lane] = -1;
-                if (p.score) p.score[o + lane] = -INFINITY;
+            if (writer) {
+                if (keep0) { p.idx[o + p0] = f; if (p.score) p.score[o + p0] = s0; }
+                if (keep1) { p.idx[o + p1] = m; if (p.score) p.score[o + p1] = s1; }
+                if (lane >= newcnt && lane < p.kmax) {
+                    p.idx[o + lane] = -1;
+                    if (p.score) p.score[o + lane] = -INFINITY;
+                }
+                if (lane == 0) p.cnt[row] = newcnt;
+                // rows that finish before the deepest one: their node list stays as it is
+                if (p.trace)
+                    for (int lv = level + 1; lv <= p.max_levels; ++lv) {
+                        int *tr = p.trace + (((long long)(lv - 1) * p.H * n_k * p.NB + row) * p.kmax) * 2;
+                        if (keep0) { tr[2 * p0] = f; tr[2 * p0 + 1] = m - 1; }
+                        if (keep1) { tr[2 * p1] = m; tr[2 * p1 + 1] = l; }
+                        if (lane >= newcnt && lane < p.kmax) { tr[2 * lane] = -1; tr[2 * lane + 1] = -1; }
+                    }
             }
-            if (lane == 0) p.cnt[row] = newcnt;
+        } else if (level == level_last) {
+            // update: survivors overwrite the row's node list in memory, in positional order,
+            // for the launch that runs the next levels
+            if (writer) {
+                if (keep0) { p.nf[o + p0] = f; p.nl[o + p0] = m - 1; p.ns[o + p0] = s0; }
+                if (keep1) { p.nf[o + p1] = m; p.nl[o + p1] = l;     p.ns[o + p1] = s1; }
+                if (lane == 0) p.ncnt[row] = newcnt;
+            }
+        } else {
+            // update: survivors become the nodes of the next level, node j on lane j
+            if (keep0) { s_nf[wave][p0] = f; s_nl[wave][p0] = m - 1; s_ns[wave][p0] = s0; }
+            if (keep1) { s_nf[wave][p1] = m; s_nl[wave][p1] = l;     s_ns[wave][p1] = s1; }
+            wave_sync();
+            live = lane < newcnt;
+            f = live ? s_nf[wave][lane] : 0;
+            l = live ? s_nl[wave][lane] : -1;
+            sc = live ? s_ns[wave][lane] : -INFINITY;
+            wave_sync();
         }
-        if (p.tiles && lane == 0) atomicAdd(p.tiles, (unsigned long long)nt);
     }
-}
-
-// Copies the node ranges of one level into the caller's trace buffer, -1 in dead slots.
-__global__ void __launch_bounds__(256) trace_kernel(const int *nf, const int *nl, const int *ncnt,
-                                                    int *out, long long rows, int kmax)
-{
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows * kmax) return;
-    const long long row = i / kmax;
-    const int j = (int)(i % kmax);
-    const bool live = j < ncnt[row];
-    out[2 * i] = live ? nf[i] : -1;
-    out[2 * i + 1] = live ? nl[i] : -1;
+    if constexpr (MULTI) wave_sync();     // the last level's cache entries, before the next k reads them
+    }
+    if (p.tiles && (WPR == 1 || wave == 0) && lane == 0) atomicAdd(p.tiles, tiles_done);
 }
 
 struct PruneWorkspace {
@@ -310,6 +388,7 @@ static PruneWorkspace prune_layout(const Problem &pb)
     size_t off = 0;
     const size_t rows = (size_t)pb.H * pb.NB;
     w.kp = off;   off += align_up((size_t)pb.Hkv * pb.NB * pb.b * pb.d * pb.esize, 256);
+    // node lists: used only when a row's levels are split over several launches
     w.nf = off;   off += align_up(rows * pb.kmax * 4, 256);
     w.nl = off;   off += align_up(rows * pb.kmax * 4, 256);
     w.ns = off;   off += align_up(rows * pb.kmax * 4, 256);
@@ -318,27 +397,97 @@ static PruneWorkspace prune_layout(const Problem &pb)
     return w;
 }
 
+// Levels a row runs inside one launch unless the caller asks otherwise (all of them).
+constexpr int kDefaultLevelsPerLaunch = 64;
+
 typedef void (*level_fn)(const PruneParams);
 
-static level_fn pick_level_kernel(const Problem &pb, int &wpr)
+template <bool MULTI>
+static level_fn pick_level_kernel_t(const Problem &pb, int &wpr)
 {
     const bool bf = pb.dtype == STREAM_BF16;
     wpr = pb.b == 128 ? 4 : 1;
     if (pb.b == 32) {
-        if (bf) return pb.d == 128 ? level_kernel<true, 128, 1, 1, 1, 2> : level_kernel<true, 64, 1, 1, 1, 2>;
-        return pb.d == 128 ? level_kernel<false, 128, 1, 1, 1, 2> : level_kernel<false, 64, 1, 1, 1, 2>;
+        if (bf) return pb.d == 128 ? level_kernel<true, 128, 1, 1, 1, 2, MULTI> : level_kernel<true, 64, 1, 1, 1, 2, MULTI>;
+        return pb.d == 128 ? level_kernel<false, 128, 1, 1, 1, 2, MULTI> : level_kernel<false, 64, 1, 1, 1, 2, MULTI>;
     }
     if (pb.b == 64) {
-        if (bf) return pb.d == 128 ? level_kernel<true, 128, 2, 2, 1, 2> : level_kernel<true, 64, 2, 2, 1, 2>;
-        return pb.d == 128 ? level_kernel<false, 128, 2, 2, 1, 1> : level_kernel<false, 64, 2, 2, 1, 2>;
+        if (bf) return pb.d == 128 ? level_kernel<true, 128, 2, 2, 1, 2, MULTI> : level_kernel<true, 64, 2, 2, 1, 2, MULTI>;
+        return pb.d == 128 ? level_kernel<false, 128, 2, 2, 1, 1, MULTI> : level_kernel<false, 64, 2, 2, 1, 2, MULTI>;
     }
-    if (bf) return pb.d == 128 ? level_kernel<true, 128, 2, 2, 4, 2> : level_kernel<true, 64, 2, 2, 4, 2>;
-    return pb.d == 128 ? level_kernel<false, 128, 2, 2, 4, 1> : level_kernel<false, 64, 2, 2, 4, 2>;
+    if (bf) return pb.d == 128 ? level_kernel<true, 128, 2, 2, 4, 2, MULTI> : level_kernel<true, 64, 2, 2, 4, 2, MULTI>;
+    return pb.d == 128 ? level_kernel<false, 128, 2, 2, 4, 1, MULTI> : level_kernel<false, 64, 2, 2, 4, 2, MULTI>;
+}
+
+static level_fn pick_level_kernel(const Problem &pb, bool multi, int &wpr)
+{
+    return multi ? pick_level_kernel_t<true>(pb, wpr) : pick_level_kernel_t<false>(pb, wpr);
 }
 
 }  // namespace stream
 
 using namespace stream;
+
+// Packs K and runs the refinement kernel: once per group of levels, or (topk_list != nullptr)
+// once for a whole sweep over k, every row then running all its levels for every k in turn.
+static stream_status run_prune(const void *Q, const void *K, const stream_shape *shape, const Problem &pb,
+                               const int *topk_list, int n_k, int *idx, int *cnt, float *score,
+                               const stream_prune_diag *diag, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    const bool multi = topk_list != nullptr;
+    const long long q_sh = shape->q_stride_h ? shape->q_stride_h : pb.T * pb.d;
+    const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;
+    const long long k_sh = shape->k_stride_h ? shape->k_stride_h : pb.T * pb.d;
+    const long long k_st = shape->k_stride_t ? shape->k_stride_t : pb.d;
+    if (q_st < pb.d || k_st < pb.d || q_sh < 0 || k_sh < 0) return STREAM_EINVAL;
+    // 16-byte vector loads: base pointers and strides must keep rows 16-byte aligned
+    if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
+    if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
+    const PruneWorkspace w = prune_layout(pb);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return STREAM_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+
+    stream_status rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st);
+    if (rc != STREAM_OK) return rc;
+
+    PruneParams p;
+    p.Q = (const char *)Q;
+    p.Kp = ws + w.kp;
+    p.q_sh_b = q_sh * pb.esize;
+    p.q_st_b = q_st * pb.esize;
+    p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.kmax = pb.kmax;
+    p.nf = (int *)(ws + w.nf); p.nl = (int *)(ws + w.nl);
+    p.ns = (float *)(ws + w.ns); p.ncnt = (int *)(ws + w.ncnt);
+    p.idx = idx; p.cnt = cnt; p.score = score;
+    p.tiles = diag ? diag->tiles_scored : nullptr;
+    p.trace = diag ? diag->trace : nullptr;
+    p.seqs = pb.seqs;
+    p.max_levels = pb.max_levels;
+    p.n_k = multi ? n_k : 1;
+    for (int i = 0; i < kMaxSweep; ++i) p.klist[i] = multi && i < n_k ? topk_list[i] : 0;
+    int wpr = 1;
+    level_fn fn = pick_level_kernel(pb, multi, wpr);
+    const long long rows_per_kv = (long long)pb.NB * pb.g;
+    const long long per_kv = wpr == 1 ? (rows_per_kv + 3) / 4 : rows_per_kv;
+    if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
+    p.map = make_wg_map(pb.Hkv, (int)per_kv);
+    // levels per launch: every row runs that many of its levels back to back inside one kernel
+    // (a sweep always runs whole rows)
+    int per_launch = !multi && diag && diag->levels_per_launch > 0 ? diag->levels_per_launch : kDefaultLevelsPerLaunch;
+    void *const *ev = diag ? diag->level_events : nullptr;
+    int launch = 0;
+    for (int level = 1; level <= pb.max_levels; level += per_launch, ++launch) {
+        p.level_begin = level;
+        p.level_end = level + per_launch - 1 < pb.max_levels ? level + per_launch - 1 : pb.max_levels;
+        if (ev && hipEventRecord((hipEvent_t)ev[2 * launch], st) != hipSuccess) return STREAM_EDEVICE;
+        hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
+        if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+        if (ev && hipEventRecord((hipEvent_t)ev[2 * launch + 1], st) != hipSuccess) return STREAM_EDEVICE;
+    }
+    return STREAM_OK;
+}
 
 extern "C" {
 
@@ -360,56 +509,33 @@ stream_status stream_prune(const void *Q, const void *K, const stream_shape *sha
     Problem pb;
     stream_status rc = make_problem(shape, topk, topk_per_seq, topk_max, &pb);
     if (rc != STREAM_OK) return rc;
-    const long long q_sh = shape->q_stride_h ? shape->q_stride_h : pb.T * pb.d;
-    const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;
-    const long long k_sh = shape->k_stride_h ? shape->k_stride_h : pb.T * pb.d;
-    const long long k_st = shape->k_stride_t ? shape->k_stride_t : pb.d;
-    if (q_st < pb.d || k_st < pb.d || q_sh < 0 || k_sh < 0) return STREAM_EINVAL;
-    // 16-byte vector loads: base pointers and strides must keep rows 16-byte aligned
-    if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
-    if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
-    const PruneWorkspace w = prune_layout(pb);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return STREAM_EWORKSPACE;
-    hipStream_t st = (hipStream_t)hip_stream;
-    char *ws = (char *)workspace;
+    return run_prune(Q, K, shape, pb, nullptr, 0, idx, cnt, score, diag, workspace, workspace_bytes, hip_stream);
+}
 
-    rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st);
-    if (rc != STREAM_OK) return rc;
+size_t stream_prune_multi_workspace_bytes(const stream_shape *shape, int n_k, int topk_max)
+{
+    if (n_k < 1 || n_k > kMaxSweep) return 0;
+    return stream_prune_workspace_bytes(shape, topk_max);
+}
 
-    PruneParams p;
-    p.Q = (const char *)Q;
-    p.Kp = ws + w.kp;
-    p.q_sh_b = q_sh * pb.esize;
-    p.q_st_b = q_st * pb.esize;
-    p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.kmax = pb.kmax;
-    p.nf = (int *)(ws + w.nf); p.nl = (int *)(ws + w.nl);
-    p.ns = (float *)(ws + w.ns); p.ncnt = (int *)(ws + w.ncnt);
-    p.idx = idx; p.cnt = cnt; p.score = score;
-    p.tiles = diag ? diag->tiles_scored : nullptr;
-    p.seqs = pb.seqs;
-    int wpr = 1;
-    level_fn fn = pick_level_kernel(pb, wpr);
-    const long long rows_per_kv = (long long)pb.NB * pb.g;
-    const long long per_kv = wpr == 1 ? (rows_per_kv + 3) / 4 : rows_per_kv;
-    if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
-    p.map = make_wg_map(pb.Hkv, (int)per_kv);
-    const long long rows = (long long)pb.H * pb.NB;
-    for (int level = 1; level <= pb.max_levels; ++level) {
-        p.level = level;
-        void *const *ev = diag ? diag->level_events : nullptr;
-        if (ev && hipEventRecord((hipEvent_t)ev[2 * (level - 1)], st) != hipSuccess) return STREAM_EDEVICE;
-        hipLaunchKernelGGL(fn, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);
-        if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
-        if (ev && hipEventRecord((hipEvent_t)ev[2 * (level - 1) + 1], st) != hipSuccess) return STREAM_EDEVICE;
-        if (diag && diag->trace) {
-            const long long n = rows * pb.kmax;
-            hipLaunchKernelGGL(trace_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                               p.nf, p.nl, p.ncnt, diag->trace + (long long)(level - 1) * n * 2,
-                               rows, pb.kmax);
-            if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
-        }
+stream_status stream_prune_multi(const void *Q, const void *K, const stream_shape *shape,
+                                 const int *topk_list, int n_k, int topk_max,
+                                 int *idx, int *cnt, float *score, const stream_prune_diag *diag,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!Q || !K || !shape || !idx || !cnt || !topk_list) return STREAM_EINVAL;
+    if (topk_max < 1 || n_k < 1) return STREAM_EINVAL;
+    if (n_k > kMaxSweep) return STREAM_EUNSUPPORTED;
+    int kmin = topk_list[0];
+    for (int i = 0; i < n_k; ++i) {
+        if (topk_list[i] < 1 || topk_list[i] > topk_max) return STREAM_EINVAL;
+        if (topk_list[i] < kmin) kmin = topk_list[i];
     }
-    return STREAM_OK;
+    // the smallest k has the deepest rows: it fixes the number of levels (and the trace length)
+    Problem pb;
+    stream_status rc = make_problem(shape, kmin, nullptr, topk_max, &pb);
+    if (rc != STREAM_OK) return rc;
+    return run_prune(Q, K, shape, pb, topk_list, n_k, idx, cnt, score, diag, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

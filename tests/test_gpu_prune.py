@@ -148,3 +148,26 @@ def test_config3_full_size_sampled_rows():
             ties += 1
     print(f"[cfg3] sampled rows={len(rows)} equal={equal} ties={ties} tiles={int(out['tiles'].item())}", flush=True)
     assert ties <= 2
+
+
+@pytest.mark.parametrize("block,seq_lens,k", [(64, (64 * 100 + 7,), 4), (128, (128 * 70 + 1,), 8),
+                                               (32, (3000, 5, 32 * 40), (2, 1, 5))])
+def test_levels_per_launch_does_not_change_the_result(block, seq_lens, k):
+    """All levels of a row inside one launch (the default), one launch per level, or anything
+    between: same lists, scores, per-level trace and evaluation count, bit for bit."""
+    w = wl.scaled(wl.config(2), seq_lens, topk=k, heads=4, kv_heads=2, block=block, needles_per_kv_head=2)
+    dev = torch.device("cuda:0")
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    Qd, Kd = Q.to(dev), K.to(dev)
+    cu = w.cu_seqlens if w.batch > 1 else None
+    topk = list(w.topk) if w.batch > 1 else w.topk[0]
+    outs = []
+    for lpl in (0, 1, 2, 3):
+        r = binding.stream_prune(Qd, Kd, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu, want_score=True,
+                                 want_trace=True, want_tiles=True, levels_per_launch=lpl)
+        torch.cuda.synchronize()
+        outs.append({x: r[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace", "tiles")})
+    assert outs[0]["trace"].shape[0] >= 3
+    for o in outs[1:]:
+        for x in ("idx", "cnt", "score", "trace", "tiles"):
+            np.testing.assert_array_equal(o[x], outs[0][x], err_msg=x)
