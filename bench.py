@@ -224,6 +224,8 @@ def main():
     }
     if not args.no_select:
         result["select_roofline"] = select_standalone(kmax)
+    if not args.no_select:
+        result["mask_diff_roofline"] = mask_diff_standalone(kmax)
     if not args.no_sweep and w.batch == 1:
         result["k_sweep"] = k_sweep(w, layers[0])
     if not args.no_cpu_baseline:
@@ -279,6 +281,45 @@ def k_sweep(w, layer, reps=4):
     return {"topk_list": ks, "sweep_ms": multi_ms, "separate_calls_ms": sep_ms,
             "speedup": sep_ms / multi_ms, "block_scores_sweep": multi_tiles,
             "block_scores_separate_calls": sep_tiles}
+
+
+def mask_diff_standalone(kmax, rows=1 << 21, launches=12):
+    """stream_mask_diff (lists of k against lists of k/2, half of the latter shared) on synthetic
+    lists, against the HBM roofline.  Algorithmic bytes per row: both index lists, the scores and
+    the two counts read; the difference, its weights and its count written."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    dev = "cuda:0"
+    ka, kb, N = kmax, max(1, kmax // 2), 2048
+    g = torch.Generator(device=dev)
+    g.manual_seed(2510_19875 + 1)
+    step = max(1, N // ka)
+    base = torch.arange(ka, device=dev, dtype=torch.int32) * step
+    ia = (base[None, :] + torch.randint(0, step, (rows, ka), device=dev, generator=g, dtype=torch.int32)).contiguous()
+    ib = ia[:, ::2][:, :kb].contiguous().clone()
+    move = (torch.rand(ib.shape, device=dev, generator=g) < 0.5) & (ib % step != 0)
+    ib = torch.where(move, ib - 1, ib).contiguous()
+    ca = torch.full((rows,), ka, dtype=torch.int32, device=dev)
+    cb = torch.full((rows,), ib.shape[1], dtype=torch.int32, device=dev)
+    sa = torch.randn((rows, ka), device=dev, generator=g)
+    r = binding.stream_mask_diff(ia, ca, sa, ib, cb)
+    out = {"idx": r["idx"], "cnt": r["cnt"], "weight": r["weight"]}
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(launches):
+        binding.stream_mask_diff(ia, ca, sa, ib, cb, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / launches
+    bytes_per_row = 4 * ka + 4 * ka + 4 * ib.shape[1] + 8 + 8 * ka + 4
+    gbs = rows * bytes_per_row / (ms * 1e-3) / 1e9
+    return {"kernel": "diff_kernel (stream_mask_diff: sorted-list set difference + weights)",
+            "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": gbs / PEAK_HBM_GBS, "rows": rows, "k_a": ka, "k_b": int(ib.shape[1]),
+            "bytes_per_row": bytes_per_row, "avg_launch_ms": ms, "launches": launches}
 
 
 def select_standalone(kmax, rows=1 << 21, launches=12):

@@ -199,6 +199,30 @@ stream_status stream_select_update(const float *branch_score, int *node_first, i
                                    int *node_count, long long rows, int topk, int topk_max,
                                    void *hip_stream);
 
+/*
+ * Difference of two estimated masks (Section 4.2.2, "Exploring Information Flow": the masks
+ * obtained with k_fail are subtracted from those obtained with k_success to isolate the
+ * connections that enable a behaviour, each weighted by its block score in the k_success run).
+ *
+ * For each of `rows` independent (head, query block) rows: the entries of list a (k_success)
+ * that do not occur in list b (k_fail), in ascending order.
+ *
+ *   idx_a, cnt_a   int32 [rows, kmax_a], [rows]: ascending key-block ids, as written by
+ *                  stream_prune / stream_prune_multi (entries at and after cnt are ignored)
+ *   score_a        float [rows, kmax_a] or NULL: block scores of list a
+ *   idx_b, cnt_b   int32 [rows, kmax_b], [rows]
+ *   idx_out        int32 [rows, kmax_a]: the difference, padded with -1; must not alias an input
+ *   cnt_out        int32 [rows]
+ *   weight_out     float [rows, kmax_a] or NULL: score_a of the kept entries, padded with -inf
+ *                  (needs score_a)
+ *   1 <= kmax_a, kmax_b <= 64; counts outside [0, kmax] are clamped; rows >= 0 (0 is a no-op:
+ *   the pointers are not looked at).
+ * Errors: STREAM_EINVAL, STREAM_EUNSUPPORTED (kmax > 64), STREAM_EDEVICE.  No workspace.
+ */
+stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *score_a, int kmax_a,
+                               const int *idx_b, const int *cnt_b, int kmax_b, long long rows,
+                               int *idx_out, int *cnt_out, float *weight_out, void *hip_stream);
+
 const char *stream_status_str(stream_status s);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ STREAM_F32, STREAM_BF16 = 0, 1
 EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
            "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
            "stream_prune_multi_workspace_bytes", "stream_prune_multi",
-           "stream_select_update", "stream_status_str"]
+           "stream_select_update", "stream_mask_diff", "stream_status_str"]
 
 
 class StreamShape(ctypes.Structure):
@@ -81,6 +81,9 @@ def load():
                                        ctypes.POINTER(StreamPruneDiag), vp, ctypes.c_size_t, vp]
     lib.stream_select_update.restype = ctypes.c_int
     lib.stream_select_update.argtypes = [vp, vp, vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
+    lib.stream_mask_diff.restype = ctypes.c_int
+    lib.stream_mask_diff.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, ctypes.c_longlong,
+                                     vp, vp, vp, vp]
     lib.stream_status_str.restype = ctypes.c_char_p
     lib.stream_status_str.argtypes = [ctypes.c_int]
     _lib = lib
@@ -276,3 +279,40 @@ def stream_select_update(score, node_first, node_last, node_count, topk: int):
                                   node_count.data_ptr(), rows, int(topk), kmax, _stream_ptr())
     if rc != STREAM_OK:
         raise StreamError(rc, "stream_select_update")
+
+
+def stream_mask_diff(idx_a, cnt_a, score_a, idx_b, cnt_b, want_weight: bool = True, out=None):
+    """Entries of the lists a (k_success) absent from the lists b (k_fail), row by row.
+
+    idx_* [..., kmax] int32, cnt_* [...] int32, score_a like idx_a (fp32) or None; leading
+    dimensions are flattened to rows.  Returns dict(idx, cnt, weight) shaped like the a inputs."""
+    lib = load()
+    ts = [idx_a, cnt_a, idx_b, cnt_b] + ([score_a] if score_a is not None else [])
+    for t in ts:
+        if not t.is_cuda:
+            raise ValueError("all arguments must be device tensors (the library has no CPU path)")
+        if not t.is_contiguous():
+            raise ValueError("all arguments must be contiguous")
+    if any(t.dtype != torch.int32 for t in (idx_a, cnt_a, idx_b, cnt_b)) or \
+            (score_a is not None and score_a.dtype != torch.float32):
+        raise ValueError("index/count tensors must be int32, scores float32")
+    ka, kb = idx_a.shape[-1], idx_b.shape[-1]
+    rows = cnt_a.numel()
+    if idx_a.numel() != rows * ka or idx_b.numel() != rows * kb or cnt_b.numel() != rows or \
+            (score_a is not None and score_a.shape != idx_a.shape):
+        raise ValueError("shape mismatch")
+    want_weight = want_weight and score_a is not None
+    if out is None:
+        io = torch.empty_like(idx_a)
+        co = torch.empty_like(cnt_a)
+        wo = torch.empty(idx_a.shape, dtype=torch.float32, device=idx_a.device) if want_weight else None
+    else:
+        io, co, wo = out["idx"], out["cnt"], out.get("weight")
+    rc = lib.stream_mask_diff(idx_a.data_ptr(), cnt_a.data_ptr(),
+                              score_a.data_ptr() if score_a is not None else None, ka,
+                              idx_b.data_ptr(), cnt_b.data_ptr(), kb, rows,
+                              io.data_ptr(), co.data_ptr(), wo.data_ptr() if wo is not None else None,
+                              _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_mask_diff")
+    return {"idx": io, "cnt": co, "weight": wo}

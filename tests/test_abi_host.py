@@ -144,6 +144,26 @@ def test_bad_arguments_of_select_update(lib):
     assert call(rows=0) == B.STREAM_OK                            # nothing to do, nothing launched
 
 
+def test_bad_arguments_of_mask_diff(lib):
+    fake = ctypes.c_void_p(4096)
+    other = ctypes.c_void_p(8192)
+
+    def call(ia=fake, ca=fake, sa=fake, ka=8, ib=fake, cb=fake, kb=4, rows=5, io=other, co=other, wo=other):
+        return lib.stream_mask_diff(ia, ca, sa, ka, ib, cb, kb, rows, io, co, wo, None)
+
+    assert call(ia=None) == B.STREAM_EINVAL
+    assert call(cb=None) == B.STREAM_EINVAL
+    assert call(io=None) == B.STREAM_EINVAL
+    assert call(sa=None) == B.STREAM_EINVAL                 # weights wanted but no scores given
+    assert call(io=fake) == B.STREAM_EINVAL                 # output aliases an input
+    assert call(ka=0) == B.STREAM_EINVAL
+    assert call(rows=-1) == B.STREAM_EINVAL
+    assert call(ka=65) == B.STREAM_EUNSUPPORTED
+    assert call(kb=65) == B.STREAM_EUNSUPPORTED
+    assert call(rows=1 << 40) == B.STREAM_EUNSUPPORTED
+    assert call(rows=0) == B.STREAM_OK
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     Q = torch.zeros(2, 64, 64)
