@@ -52,12 +52,19 @@ int stream_oracle_threads(void)
 #endif
 }
 
+/* Masks C given by a rule instead of a T x T array (Alg. 2 takes any C; these are the ones
+   the models of the paper use: causal layers, sliding-window layers, and no mask = Alg. 1). */
+enum { MASK_CAUSAL = 0, MASK_FULL = 1, MASK_SLIDING = 2 };
+
 typedef struct {
     const float *Q;           /* [T, d]  one query head              */
     const float *K;           /* [T, d]  its key head                */
-    const unsigned char *C;   /* [T, T] attention mask, or NULL = causal (C[t,u] = 1 iff u <= t) */
+    const unsigned char *C;   /* [T, T] attention mask, or NULL = the rule below */
     long T;                   /* real tokens (before padding)        */
     int d, b;                 /* head dim, block size b_q = b_k      */
+    int kind;                 /* MASK_CAUSAL: C[t,u] = 1 iff u <= t; MASK_FULL: all ones;
+                                 MASK_SLIDING: u <= t and t - u < window                  */
+    long window;
 } problem_t;
 
 /* C[t,u] after the preamble's zero padding: rows/cols >= T are 0. */
@@ -65,6 +72,8 @@ static int mask_C(const problem_t *p, long t, long u)
 {
     if (t >= p->T || u >= p->T) return 0;
     if (p->C) return p->C[t * p->T + u] != 0;
+    if (p->kind == MASK_FULL) return 1;
+    if (p->kind == MASK_SLIDING) return u <= t && t - u < p->window;
     return u <= t;
 }
 
@@ -72,7 +81,7 @@ static int mask_C(const problem_t *p, long t, long u)
 static int mask_Cblk(const problem_t *p, long q, long r)
 {
     const int b = p->b;
-    if (!p->C) {
+    if (!p->C && p->kind == MASK_CAUSAL) {
         /* causal: some real key of block r is <= some real query of block q
            iff the block's first key is <= the block's last real query        */
         long first_key = r * b;
@@ -107,7 +116,7 @@ static double block_score(const problem_t *p, long q, long r)
 double stream_oracle_block_score(const float *Q, const float *K, const unsigned char *C,
                                  long T, int d, int b, long q, long r)
 {
-    problem_t p = {Q, K, C, T, d, b};
+    problem_t p = {Q, K, C, T, d, b, MASK_CAUSAL, 0};
     return block_score(&p, q, r);
 }
 
@@ -152,13 +161,16 @@ static int int_cmp(const void *a, const void *b)
  *                  [1] those whose representative differs from the parent node's
  *                  (the evaluations that cannot be inherited), may be NULL
  */
-int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char *C,
-                             long T, int d, int b, int k, int n_levels,
-                             const int *qlist, int nq,
-                             int *idx, int *cnt, double *score, int *trace, long long *evals)
+int stream_oracle_prune_head_rule(const float *Q, const float *K, const unsigned char *C,
+                                  int mask_kind, long window,
+                                  long T, int d, int b, int k, int n_levels,
+                                  const int *qlist, int nq,
+                                  int *idx, int *cnt, double *score, int *trace, long long *evals)
 {
     if (!Q || !K || T <= 0 || d <= 0 || b <= 0 || k <= 0 || nq < 0) return 1;
-    problem_t p = {Q, K, C, T, d, b};
+    if (mask_kind < MASK_CAUSAL || mask_kind > MASK_SLIDING) return 1;
+    if (mask_kind == MASK_SLIDING && window < 1) return 1;
+    problem_t p = {Q, K, C, T, d, b, mask_kind, window};
     /* preamble: pad to l = lcm(b_q, b_k) = b; block views are index arithmetic */
     const long T_p = ((T + b - 1) / b) * b;
     const long N = T_p / b;
@@ -234,9 +246,19 @@ int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char
     return 0;
 }
 
+/* The same with the causal mask (or an explicit C). */
+int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char *C,
+                             long T, int d, int b, int k, int n_levels,
+                             const int *qlist, int nq,
+                             int *idx, int *cnt, double *score, int *trace, long long *evals)
+{
+    return stream_oracle_prune_head_rule(Q, K, C, MASK_CAUSAL, 0, T, d, b, k, n_levels, qlist, nq,
+                                         idx, cnt, score, trace, evals);
+}
+
 /*
  * Eq. (2) with the mask M given by idx/cnt (block ids per query block) and the
- * causal mask inside retained blocks:  for each real query token t of the query
+ * mask C (causal, or the rule named by mask_kind) inside retained blocks:  for each real query token t of the query
  * blocks in qlist,
  *     S~[t,u] = scale * <Q_t, K_u>   for u in retained blocks of block(t), u <= t
  *     P~ = softmax(S~),  O_t = sum_u P~[t,u] V_u,  lse_t = log sum_u exp(S~[t,u])
@@ -244,12 +266,16 @@ int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char
  * idx is [nq, k] (rows aligned with qlist), O is [T, d] and lse [T] (only rows of
  * the listed blocks are written), mass [T] is accumulated into (caller zeroes).
  */
-int stream_oracle_attn_head(const float *Q, const float *K, const float *V,
-                            long T, int d, int b, int k, double scale,
-                            const int *qlist, int nq, const int *idx, const int *cnt,
-                            double *O, double *lse, double *mass)
+int stream_oracle_attn_head_rule(const float *Q, const float *K, const float *V,
+                                 int mask_kind, long window,
+                                 long T, int d, int b, int k, double scale,
+                                 const int *qlist, int nq, const int *idx, const int *cnt,
+                                 double *O, double *lse, double *mass)
 {
     if (!Q || !K || !V || !idx || !cnt || T <= 0) return 1;
+    if (mask_kind < MASK_CAUSAL || mask_kind > MASK_SLIDING) return 1;
+    if (mask_kind == MASK_SLIDING && window < 1) return 1;
+    problem_t p = {Q, K, NULL, T, d, b, mask_kind, window};
 #pragma omp parallel for schedule(dynamic, 1)
     for (int qi = 0; qi < nq; ++qi) {
         const long q = qlist[qi];
@@ -265,7 +291,7 @@ int stream_oracle_attn_head(const float *Q, const float *K, const float *V,
                 const long r = idx[(long)qi * k + j];
                 for (int n = 0; n < b; ++n) {
                     const long u = r * b + n;
-                    if (u >= T || u > t) continue;
+                    if (!mask_C(&p, t, u)) continue;
                     double acc = 0.0;
                     for (int i = 0; i < d; ++i) acc += (double)Q[t * d + i] * (double)K[u * d + i];
                     acc *= scale;
@@ -293,4 +319,13 @@ int stream_oracle_attn_head(const float *Q, const float *K, const float *V,
         free(sc); free(key);
     }
     return 0;
+}
+
+int stream_oracle_attn_head(const float *Q, const float *K, const float *V,
+                            long T, int d, int b, int k, double scale,
+                            const int *qlist, int nq, const int *idx, const int *cnt,
+                            double *O, double *lse, double *mass)
+{
+    return stream_oracle_attn_head_rule(Q, K, V, MASK_CAUSAL, 0, T, d, b, k, scale, qlist, nq, idx, cnt,
+                                        O, lse, mass);
 }

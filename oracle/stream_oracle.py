@@ -55,12 +55,34 @@ def _load():
                                                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ip,
                                                  ctypes.c_int, ip, ip, dp, ip,
                                                  ctypes.POINTER(ctypes.c_longlong)]
+        lib.stream_oracle_prune_head_rule.restype = ctypes.c_int
+        lib.stream_oracle_prune_head_rule.argtypes = [fp, fp, up, ctypes.c_int, ctypes.c_long,
+                                                      ctypes.c_long, ctypes.c_int,
+                                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, ip,
+                                                      ctypes.c_int, ip, ip, dp, ip,
+                                                      ctypes.POINTER(ctypes.c_longlong)]
+        lib.stream_oracle_attn_head_rule.restype = ctypes.c_int
+        lib.stream_oracle_attn_head_rule.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_long,
+                                                     ctypes.c_long, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
+                                                     ctypes.c_int, ip, ip, dp, dp, dp]
         lib.stream_oracle_attn_head.restype = ctypes.c_int
         lib.stream_oracle_attn_head.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
                                                 ctypes.c_int, ip, ip, dp, dp, dp]
         _lib = lib
     return _lib
+
+
+MASKS = {"causal": 0, "full": 1, "sliding": 2}
+
+
+def _mask_code(mask: str, window: int):
+    """Rule-based masks C: "causal" (u <= t), "full" (no mask: Alg. 1), "sliding" (u <= t and
+    t - u < window: sliding-window layers)."""
+    if mask not in MASKS:
+        raise ValueError(f"unknown mask {mask!r}")
+    return MASKS[mask], int(window)
 
 
 def _f32(a) -> np.ndarray:
@@ -94,8 +116,10 @@ def block_score(Qh: np.ndarray, Kh: np.ndarray, block: int, q: int, r: int, C=No
 
 
 def prune_head(Qh, Kh, block: int, topk: int, qblocks: Optional[Sequence[int]] = None,
-               n_levels: int = -1, C=None, want_trace: bool = False):
-    """Algorithm 2 for one head / one sequence.  Returns dict(idx, cnt, score, trace, evals)."""
+               n_levels: int = -1, C=None, want_trace: bool = False, mask: str = "causal",
+               window: int = 0):
+    """Algorithm 2 for one head / one sequence.  Returns dict(idx, cnt, score, trace, evals).
+    The mask C is the explicit [T, T] array if given, else the rule `mask` / `window`."""
     Qh, Kh = _f32(Qh), _f32(Kh)
     T, d = Qh.shape
     N = (T + block - 1) // block
@@ -108,8 +132,9 @@ def prune_head(Qh, Kh, block: int, topk: int, qblocks: Optional[Sequence[int]] =
     trace = np.full((nq, levels, topk, 2), -1, dtype=np.int32) if want_trace else None
     evals = np.zeros(2, dtype=np.int64)
     Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
-    rc = _load().stream_oracle_prune_head(
-        _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Cc, ctypes.c_ubyte), T, d,
+    kind, win = _mask_code(mask, window)
+    rc = _load().stream_oracle_prune_head_rule(
+        _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Cc, ctypes.c_ubyte), kind, win, T, d,
         int(block), int(topk), int(n_levels), _ptr(ql, ctypes.c_int), nq,
         _ptr(idx, ctypes.c_int), _ptr(cnt, ctypes.c_int), _ptr(score, ctypes.c_double),
         _ptr(trace, ctypes.c_int), _ptr(evals, ctypes.c_longlong))
@@ -131,7 +156,7 @@ def block_table(cu_seqlens: Sequence[int], block: int):
 
 def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
           rows: Optional[Sequence[Sequence[int]]] = None, n_levels: int = -1,
-          want_trace: bool = False):
+          want_trace: bool = False, mask: str = "causal", window: int = 0):
     """Stream for every (head, query block), or for the listed rows only.
 
     Q [heads, T, d], K [kv_heads, T, d]; topk is an int or one int per sequence.
@@ -167,7 +192,8 @@ def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
             ql = bloc[rows_arr[sel, 1]].astype(np.int32)
             Qh = Q[h, cu[s]:cu[s + 1]]
             Kh = K[h // g, cu[s]:cu[s + 1]]
-            out = prune_head(Qh, Kh, block, ks[s], ql, n_levels=n_levels, want_trace=want_trace)
+            out = prune_head(Qh, Kh, block, ks[s], ql, n_levels=n_levels, want_trace=want_trace,
+                             mask=mask, window=window)
             idx[sel, :ks[s]] = out["idx"]
             cnt[sel] = out["cnt"]
             score[sel, :ks[s]] = out["score"]
@@ -185,7 +211,7 @@ def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
 
 def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
                 cu_seqlens=None, rows: Optional[Sequence[Sequence[int]]] = None,
-                want_mass: bool = True):
+                want_mass: bool = True, mask: str = "causal", window: int = 0):
     """Eq. (2) over the retained blocks given by idx/cnt.
 
     idx/cnt are [heads, NB, kmax]/[heads, NB] (full) or aligned with `rows`.
@@ -225,9 +251,10 @@ def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale:
             mh = np.zeros((b_ - a,), dtype=np.float64)
             i2 = np.ascontiguousarray(idx2[sel])
             c2 = np.ascontiguousarray(cnt2[sel])
-            rc = lib.stream_oracle_attn_head(
+            kind, win = _mask_code(mask, window)
+            rc = lib.stream_oracle_attn_head_rule(
                 _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Vh, ctypes.c_float),
-                b_ - a, d, int(block), kmax, float(scale), _ptr(ql, ctypes.c_int), len(ql),
+                kind, win, b_ - a, d, int(block), kmax, float(scale), _ptr(ql, ctypes.c_int), len(ql),
                 _ptr(i2, ctypes.c_int), _ptr(c2, ctypes.c_int), _ptr(Oh, ctypes.c_double),
                 _ptr(lh, ctypes.c_double), _ptr(mh if want_mass else None, ctypes.c_double))
             if rc != 0:
