@@ -30,7 +30,9 @@
  *     never straddle sequences: sequence s has N_s = ceil(L_s / block) query
  *     (= key) blocks, the last one possibly partial, and NB = sum_s N_s.
  *     Key-block ids in `idx` are local to their sequence.
- *   - b_q = b_k = block; the mask C is the causal mask.
+ *   - b_q = b_k = block; the mask C is one of the rules of stream_mask (a zero-initialised
+ *     shape means causal).  A key block is valid for a query block when at least one of its
+ *     real keys is visible to one of the block's real queries.
  *   - Every entry point validates its arguments on the host before any launch
  *     and returns a stream_status; nothing is thrown or logged.  Outputs are
  *     fully overwritten on STREAM_OK and untouched on an argument error.
@@ -54,6 +56,15 @@ typedef enum {
 
 typedef enum { STREAM_F32 = 0, STREAM_BF16 = 1 } stream_dtype;
 
+/* The attention mask C (an input of Algorithm 2; the models of the paper use causal layers
+   and, for Gemma 3, sliding-window layers; without a mask Algorithm 2 is Algorithm 1):
+   key u of a sequence is visible to query t of the same sequence iff                       */
+typedef enum {
+    STREAM_MASK_CAUSAL = 0,  /* u <= t                                                       */
+    STREAM_MASK_FULL = 1,    /* always (no mask)                                             */
+    STREAM_MASK_SLIDING = 2  /* u <= t and t - u < window                                    */
+} stream_mask;
+
 typedef struct {
     int heads;       /* query heads H                                                  */
     int kv_heads;    /* key/value heads, divides H                                     */
@@ -67,6 +78,8 @@ typedef struct {
     long long k_stride_h, k_stride_t;
     long long v_stride_h, v_stride_t; /* stream_sparse_attn only                        */
     long long o_stride_h, o_stride_t; /* stream_sparse_attn only                        */
+    int mask;        /* stream_mask: the attention mask C of Algorithm 2 and Eq. (2)   */
+    long long window;/* STREAM_MASK_SLIDING: window length W in tokens, >= 1           */
 } stream_shape;
 
 /* Optional diagnostics of stream_prune (each member may be NULL). */
@@ -110,7 +123,8 @@ size_t stream_prune_workspace_bytes(const stream_shape *shape, int topk_max);
  *   topk_per_seq  HOST int[batch] overriding topk per sequence, or NULL
  *   topk_max      row length of idx/score (>= every k in use, <= 64)
  *   idx           int32 [heads, NB, topk_max]: retained key-block ids, ascending, padded with -1
- *   cnt           int32 [heads, NB]: number of retained blocks = min(k, q+1)
+ *   cnt           int32 [heads, NB]: number of retained blocks = min(k, valid key blocks of the
+ *                 row) (causal: min(k, q+1))
  *   score         float [heads, NB, topk_max] or NULL: block score (max masked dot product,
  *                 Eq. (4), unscaled) of each retained block, padded with -inf
  *   diag          optional diagnostics or NULL

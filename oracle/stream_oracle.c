@@ -120,6 +120,13 @@ double stream_oracle_block_score(const float *Q, const float *K, const unsigned 
     return block_score(&p, q, r);
 }
 
+double stream_oracle_block_score_rule(const float *Q, const float *K, int mask_kind, long window,
+                                      long T, int d, int b, long q, long r)
+{
+    problem_t p = {Q, K, NULL, T, d, b, mask_kind, window};
+    return block_score(&p, q, r);
+}
+
 static long ceil_log2(long n)
 {
     long it = 0, v = 1;

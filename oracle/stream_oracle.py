@@ -106,9 +106,15 @@ def n_it(T: int, block: int) -> int:
     return int(_load().stream_oracle_n_it(int(T), int(block)))
 
 
-def block_score(Qh: np.ndarray, Kh: np.ndarray, block: int, q: int, r: int, C=None) -> float:
+def block_score(Qh: np.ndarray, Kh: np.ndarray, block: int, q: int, r: int, C=None,
+                mask: str = "causal", window: int = 0) -> float:
     """Score of key block r for query block q of one head: masked max of the b x b dot products."""
     Qh, Kh = _f32(Qh), _f32(Kh)
+    if C is None and mask != "causal":
+        kind, win = _mask_code(mask, window)
+        return float(_load().stream_oracle_block_score_rule(
+            _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), kind, win, Qh.shape[0], Qh.shape[1],
+            int(block), int(q), int(r)))
     Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
     return float(_load().stream_oracle_block_score(_ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float),
                                                    _ptr(Cc, ctypes.c_ubyte), Qh.shape[0],

@@ -31,7 +31,8 @@ class StreamShape(ctypes.Structure):
                 ("q_stride_h", ctypes.c_longlong), ("q_stride_t", ctypes.c_longlong),
                 ("k_stride_h", ctypes.c_longlong), ("k_stride_t", ctypes.c_longlong),
                 ("v_stride_h", ctypes.c_longlong), ("v_stride_t", ctypes.c_longlong),
-                ("o_stride_h", ctypes.c_longlong), ("o_stride_t", ctypes.c_longlong)]
+                ("o_stride_h", ctypes.c_longlong), ("o_stride_t", ctypes.c_longlong),
+                ("mask", ctypes.c_int), ("window", ctypes.c_longlong)]
 
 
 class StreamPruneDiag(ctypes.Structure):
@@ -98,12 +99,17 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
+MASKS = {"causal": 0, "full": 1, "sliding": 2}
+
+
 def make_shape(heads, kv_heads, head_dim, block, dtype_code, T, cu_seqlens=None, Q=None, K=None,
-               V=None, O=None):
+               V=None, O=None, mask="causal", window=0):
     """Build a stream_shape; returns (shape, keepalive) - keepalive owns the host cu_seqlens array."""
     s = StreamShape()
     s.heads, s.kv_heads, s.head_dim, s.block, s.dtype = heads, kv_heads, head_dim, block, dtype_code
     s.T = int(T)
+    s.mask = MASKS[mask] if isinstance(mask, str) else int(mask)
+    s.window = int(window)
     keep = None
     if cu_seqlens is not None:
         cu = [int(x) for x in cu_seqlens]
@@ -132,7 +138,7 @@ def num_blocks(shape: StreamShape) -> int:
 def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
                  topk, cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
                  want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None,
-                 level_events=None, levels_per_launch: int = 0):
+                 level_events=None, levels_per_launch: int = 0, mask="causal", window: int = 0):
     """Algorithm 2 for every (head, query block).  Q [H, T, d], K [Hkv, T, d] on the GPU.
 
     topk: int, or one int per sequence.  Returns dict(idx [H, NB, kmax] int32, cnt [H, NB] int32,
@@ -142,7 +148,8 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
     if not (Q.is_cuda and K.is_cuda):
         raise ValueError("Q and K must be device tensors (the library has no CPU path)")
     H, T, d = Q.shape
-    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K)
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
+                             mask=mask, window=window)
     nseq = shape.batch
     if isinstance(topk, int):
         ks, kmax, k_arr = None, int(topk), None
@@ -192,14 +199,16 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
 
 def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
                        topk_list: Sequence[int], cu_seqlens: Optional[Sequence[int]] = None,
-                       want_score: bool = False, want_tiles: bool = False, workspace=None, out=None):
+                       want_score: bool = False, want_tiles: bool = False, workspace=None, out=None,
+                       mask="causal", window: int = 0):
     """Algorithm 2 for several k over the same Q, K in one call.  Returns dict(idx
     [H, n_k, NB, kmax] int32, cnt [H, n_k, NB] int32, score (optional) fp32, tiles (optional))."""
     lib = load()
     if not (Q.is_cuda and K.is_cuda):
         raise ValueError("Q and K must be device tensors (the library has no CPU path)")
     H, T, d = Q.shape
-    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K)
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
+                             mask=mask, window=window)
     ks = [int(x) for x in topk_list]
     n_k, kmax = len(ks), max(ks)
     k_arr = (ctypes.c_int * n_k)(*ks)
@@ -232,7 +241,7 @@ def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: i
 
 def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
                        cu_seqlens=None, want_lse: bool = False, want_mass: bool = False,
-                       workspace=None, out=None):
+                       workspace=None, out=None, mask="causal", window: int = 0):
     """Eq. (2) on the retained blocks.  Returns dict(O [H, T, d], lse [H, T], mass [H, T])."""
     lib = load()
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -240,7 +249,8 @@ def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt,
     H, T, d = Q.shape
     dev = Q.device
     O = torch.empty_like(Q) if out is None else out["O"]
-    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K, V=V, O=O)
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K, V=V, O=O,
+                             mask=mask, window=window)
     kmax = idx.shape[-1]
     if idx.dtype != torch.int32 or cnt.dtype != torch.int32 or not idx.is_contiguous() or not cnt.is_contiguous():
         raise ValueError("idx/cnt must be contiguous int32 device tensors")

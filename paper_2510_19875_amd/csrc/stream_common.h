@@ -88,6 +88,30 @@ __device__ __forceinline__ int seq_of_block(const SeqTable &t, int gb)
     return s;
 }
 
+// Mask rule C (stream_mask) at token and at block level.  Blocks: key block r is valid for
+// query block q when one of its keys is visible to one of q's queries; the valid blocks of a
+// row are the contiguous range [mask_rmin, mask_rmax].
+__host__ __device__ __forceinline__ bool mask_token(int mask, int window, int tq, int tk)
+{
+    if (mask == STREAM_MASK_FULL) return true;
+    if (mask == STREAM_MASK_SLIDING) return tk <= tq && tq - tk < window;
+    return tk <= tq;
+}
+
+__host__ __device__ __forceinline__ int mask_rmin(int mask, int window, int q, int b)
+{
+    if (mask != STREAM_MASK_SLIDING) return 0;
+    // the first query of the block, q*b, sees keys > q*b - window; block r reaches key r*b + b - 1
+    const long long lo = (long long)q * b - window + 1;            // first visible key (may be < 0)
+    if (lo <= 0) return 0;
+    return (int)(lo / b);                                           // block that contains it
+}
+
+__host__ __device__ __forceinline__ int mask_rmax(int mask, int q, int nblk)
+{
+    return mask == STREAM_MASK_FULL ? nblk - 1 : q;
+}
+
 #if defined(__HIPCC__)
 // Packed K/V tiles are read with raw buffer loads: a scalar resource (base + size, so a read
 // past the region returns zeros instead of faulting), a scalar byte offset that selects the tile
@@ -112,6 +136,7 @@ __device__ __forceinline__ uint4 load_frag(__amdgpu_buffer_rsrc_t rs, unsigned l
 // Host-side validated problem description shared by both entry points.
 struct Problem {
     int H, Hkv, g, d, b, dtype, esize, batch, kmax;
+    int mask, window;         // stream_mask rule; window in tokens (sliding window only)
     long long T;
     int NB;
     SeqTable seqs;

@@ -27,12 +27,18 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
     if (s->block != 32 && s->block != 64 && s->block != 128) return STREAM_EUNSUPPORTED;
     if (s->batch > kMaxBatch) return STREAM_EUNSUPPORTED;
     if (s->T > (1LL << 31) - 4096) return STREAM_EUNSUPPORTED;
+    if (s->mask != STREAM_MASK_CAUSAL && s->mask != STREAM_MASK_FULL && s->mask != STREAM_MASK_SLIDING)
+        return STREAM_EINVAL;
+    if (s->mask == STREAM_MASK_SLIDING && s->window < 1) return STREAM_EINVAL;
 
     Problem &p = *out;
     p.H = s->heads; p.Hkv = s->kv_heads; p.g = s->heads / s->kv_heads;
     p.d = s->head_dim; p.b = s->block; p.dtype = s->dtype;
     p.esize = s->dtype == STREAM_BF16 ? 2 : 4;
     p.batch = s->batch; p.T = s->T; p.kmax = topk_max;
+    p.mask = s->mask;
+    // a window that reaches past the longest possible sequence is the causal mask
+    p.window = s->mask == STREAM_MASK_SLIDING ? (int)(s->window < s->T ? s->window : s->T) : 0;
     p.seqs.n = s->batch;
     long long nb = 0, tok = 0;
     int maxlev = 0;

@@ -34,6 +34,7 @@ struct PruneParams {
     int *trace;                  // nullable diagnostic [max_levels, H, NB, kmax, 2]
     WgMap map;
     SeqTable seqs;
+    int mask, window;            // the mask rule C (stream_mask) and its window
     int n_k;                     // k sweep (MULTI kernels): values of k, outputs [H, n_k, NB, ...]
     int klist[kMaxSweep];
 };
@@ -191,6 +192,12 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const unsigned lane_off = lane * 16;
     const bool tail_row = (q == N - 1) && (L % B != 0);
     const int qtok0 = q * B + qh * 32 * MB;
+    // valid key blocks of this row under the mask C: rmin .. rmax (a branch's representative is
+    // its first valid block); blocks the mask cuts through need the token-level test
+    const int rmin = mask_rmin(p.mask, p.window, q, B), rmax = mask_rmax(p.mask, q, N);
+    // blocks <= edge_hi hold a key that lies outside the window of the block's last query
+    const int edge_num = q * B + B - 1 - p.window;
+    const int edge_hi = p.mask == STREAM_MASK_SLIDING && edge_num >= 0 ? edge_num / B : -1;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const long long o = row * p.kmax;
 
@@ -201,22 +208,26 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         // ---- split at the midpoint; causal validity: a branch is valid iff it is non-empty and
         //      starts at or before the query block; its representative is its first block.
         const int m = (f + l + 1) >> 1;
-        const bool v0 = live && m > f && f <= q;              // left child [f, m-1]
-        const bool v1 = live && m <= q;                       // right child [m, l] (never empty)
-        bool need0 = v0 && first;                             // otherwise the parent's score carries over
-        bool need1 = v1 && (first || m > f);
+        const int rep_p = f > rmin ? f : rmin;                // the node's own representative
+        const int rep0 = rep_p;                               // left child [f, m-1]
+        const int rep1 = m > rmin ? m : rmin;                 // right child [m, l] (never empty)
+        const bool v0 = live && m > f && rep0 <= (m - 1 < rmax ? m - 1 : rmax);
+        const bool v1 = live && rep1 <= (l < rmax ? l : rmax);
+        // a child whose representative is the node's own inherits the node's score
+        bool need0 = v0 && first;
+        bool need1 = v1 && (first || rep1 != rep_p);
         float c0 = 0.f, c1 = 0.f;
         bool hit0 = false, hit1 = false;
         if constexpr (MULTI) {
             // a score of the same block computed earlier for this row (another k, another level)
             if (need0) {
-                const unsigned long long e = s_cache[wave][f & (kScoreCache - 1)];
-                hit0 = (int)(e >> 32) == f;
+                const unsigned long long e = s_cache[wave][rep0 & (kScoreCache - 1)];
+                hit0 = (int)(e >> 32) == rep0;
                 c0 = __builtin_bit_cast(float, (unsigned)e);
             }
             if (need1) {
-                const unsigned long long e = s_cache[wave][m & (kScoreCache - 1)];
-                hit1 = (int)(e >> 32) == m;
+                const unsigned long long e = s_cache[wave][rep1 & (kScoreCache - 1)];
+                hit1 = (int)(e >> 32) == rep1;
                 c1 = __builtin_bit_cast(float, (unsigned)e);
             }
             need0 = need0 && !hit0;
@@ -226,8 +237,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         const unsigned long long b0 = __ballot(need0), b1 = __ballot(need1);
         const int n0 = __popcll(b0), nt = n0 + __popcll(b1);
         const int pos0 = __popcll(b0 & lt), pos1 = n0 + __popcll(b1 & lt);
-        if (need0) s_rep[wave][pos0] = f;
-        if (need1) s_rep[wave][pos1] = m;
+        if (need0) s_rep[wave][pos0] = rep0;
+        if (need1) s_rep[wave][pos1] = rep1;
         wave_sync();
 
         uint4 kf[NG][FR];
@@ -269,7 +280,9 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                 }
             }
             float mx = -INFINITY;
-            if (!(r == q || tail_row)) {
+            const bool cut = tail_row || (p.mask != STREAM_MASK_FULL && r == q) || r <= edge_hi ||
+                             (p.mask == STREAM_MASK_FULL && r == N - 1 && L % B != 0);
+            if (!cut) {
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
@@ -277,7 +290,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
             } else {
-                // diagonal block: token-level causal mask; last block of a sequence: padded rows/cols.
+                // a block the mask cuts through (diagonal, window edge) or with padded rows/cols:
+                // token-level test.
                 // 32x32 accumulator layout: lane holds column (lane % 32); element i is row
                 // 8*(i/4) + 4*(lane/32) + (i%4).
                 const int ktok0 = r * B + kh * 32 * NG;
@@ -289,7 +303,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                         for (int i = 0; i < 16; ++i) {
                             const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
                             const int tk = ktok0 + cb * 32 + (lane & 31);
-                            if (tq < L && tk <= tq) mx = fmaxf(mx, acc[rb][cb][i]);
+                            if (tq < L && tk < L && mask_token(p.mask, p.window, tq, tk)) mx = fmaxf(mx, acc[rb][cb][i]);
                         }
             }
             mx = wave_max(mx);
@@ -309,8 +323,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         if (v0) s0 = need0 ? tile_score(pos0) : (hit0 ? c0 : sc);
         if (v1) s1 = need1 ? tile_score(pos1) : (hit1 ? c1 : sc);
         if constexpr (MULTI) {
-            if (need0) s_cache[wave][f & (kScoreCache - 1)] = ((unsigned long long)(unsigned)f << 32) | __builtin_bit_cast(unsigned, s0);
-            if (need1) s_cache[wave][m & (kScoreCache - 1)] = ((unsigned long long)(unsigned)m << 32) | __builtin_bit_cast(unsigned, s1);
+            if (need0) s_cache[wave][rep0 & (kScoreCache - 1)] = ((unsigned long long)(unsigned)rep0 << 32) | __builtin_bit_cast(unsigned, s0);
+            if (need1) s_cache[wave][rep1 & (kScoreCache - 1)] = ((unsigned long long)(unsigned)rep1 << 32) | __builtin_bit_cast(unsigned, s1);
         }
         // the four wavefronts of a row must all have read this level's tile scores before any of
         // them writes the next level's
@@ -337,8 +351,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         if (level == levels) {
             // every node is now a single block: emit I (ascending), pad, count
             if (writer) {
-                if (keep0) { p.idx[o + p0] = f; if (p.score) p.score[o + p0] = s0; }
-                if (keep1) { p.idx[o + p1] = m; if (p.score) p.score[o + p1] = s1; }
+                if (keep0) { p.idx[o + p0] = rep0; if (p.score) p.score[o + p0] = s0; }
+                if (keep1) { p.idx[o + p1] = rep1; if (p.score) p.score[o + p1] = s1; }
                 if (lane >= newcnt && lane < p.kmax) {
                     p.idx[o + lane] = -1;
                     if (p.score) p.score[o + lane] = -INFINITY;
@@ -464,6 +478,7 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     p.tiles = diag ? diag->tiles_scored : nullptr;
     p.trace = diag ? diag->trace : nullptr;
     p.seqs = pb.seqs;
+    p.mask = pb.mask; p.window = pb.window;
     p.max_levels = pb.max_levels;
     p.n_k = multi ? n_k : 1;
     for (int i = 0; i < kMaxSweep; ++i) p.klist[i] = multi && i < n_k ? topk_list[i] : 0;

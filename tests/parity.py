@@ -17,11 +17,23 @@ from oracle import stream_oracle as so
 TIE_RTOL = 1e-3
 
 
-def certify_row(Qh, Kh, block, k, q, trace_row):
+def valid_range(mask, window, q, block, N):
+    """First and last key block with a key visible to a query of block q under the mask rule."""
+    rmax = N - 1 if mask == "full" else q
+    rmin = 0
+    if mask == "sliding":
+        lo = q * block - window + 1           # first key the block's first query sees
+        rmin = max(0, lo // block) if lo > 0 else 0
+    return rmin, rmax
+
+
+def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0):
     """trace_row: int array [levels, k, 2] of (f, l) kept after each GPU level (-1 = dead).
     Returns (ok, reason)."""
     T = Qh.shape[0]
     N = -(-T // block)
+    rmin, rmax = valid_range(mask, window, q, block, N)
+    rep = lambda f: max(f, rmin)              # a branch's representative: its first valid block
     nodes = [((j * N) // k, ((j + 1) * N) // k - 1) for j in range(k)]
     nodes = [(f, l) for (f, l) in nodes if f <= l]
     for lv in range(trace_row.shape[0]):
@@ -29,7 +41,7 @@ def certify_row(Qh, Kh, block, k, q, trace_row):
         for (f, l) in nodes:
             m = (f + l + 1) // 2
             for (cf, cl) in ((f, m - 1), (m, l)):
-                if cf <= cl and cf <= q:
+                if cf <= cl and rep(cf) <= min(cl, rmax):
                     children.append((cf, cl))
         kept = [(int(f), int(l)) for f, l in trace_row[lv] if f >= 0]
         if len(set(kept)) != len(kept) or kept != sorted(kept):
@@ -40,8 +52,8 @@ def certify_row(Qh, Kh, block, k, q, trace_row):
             return False, f"level {lv}: kept {len(kept)} of {len(children)} valid, k={k}"
         dropped = [c for c in children if c not in set(kept)]
         if dropped:
-            s_keep = min(so.block_score(Qh, Kh, block, q, f) for f, _ in kept)
-            s_drop = max(so.block_score(Qh, Kh, block, q, f) for f, _ in dropped)
+            s_keep = min(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window) for f, _ in kept)
+            s_drop = max(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window) for f, _ in dropped)
             if s_keep < s_drop - TIE_RTOL * max(abs(s_drop), abs(s_keep)):
                 return False, f"level {lv}: dropped {s_drop} > kept {s_keep}"
         nodes = kept
@@ -50,7 +62,8 @@ def certify_row(Qh, Kh, block, k, q, trace_row):
     return True, ""
 
 
-def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None, rows=None):
+def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None, rows=None,
+                  mask="causal", window=0):
     """gpu: dict of numpy arrays idx [H,NB,kmax], cnt [H,NB], optional score, trace
     [levels,H,NB,kmax,2].  ref: output of so.prune(...) for the same rows (or all).
     Q, K: numpy float32 (exact input values).  Returns dict with counts; raises on failure."""
@@ -75,9 +88,11 @@ def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None,
         s, q = int(bseq[gb]), int(bloc[gb])
         k = ks[s]
         gi, gc = gpu["idx"][h, gb], int(gpu["cnt"][h, gb])
-        assert gc == int(rcnt[i]) == min(k, q + 1), (h, gb, gc, int(rcnt[i]))
+        Ns = -(-(cu[s + 1] - cu[s]) // block)
+        rmin, rmax = valid_range(mask, window, q, block, Ns)
+        assert gc == int(rcnt[i]) == min(k, rmax - rmin + 1), (h, gb, gc, int(rcnt[i]))
         assert np.all(gi[gc:] == -1), (h, gb)
-        assert np.all(np.diff(gi[:gc]) > 0) and (gc == 0 or (gi[0] >= 0 and gi[gc - 1] <= q)), (h, gb)
+        assert np.all(np.diff(gi[:gc]) > 0) and (gc == 0 or (gi[0] >= rmin and gi[gc - 1] <= rmax)), (h, gb)
         Qh = Q[h, cu[s]:cu[s + 1]]
         Kh = K[h // g, cu[s]:cu[s + 1]]
         if np.array_equal(gi, ridx[i]):
@@ -92,7 +107,7 @@ def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None,
             tr = gpu["trace"][:, h, gb, :k, :]
             n_eff = max(1, math.ceil(math.log2(math.ceil((-(-Qh.shape[0] // block)) / k))))
             tr = tr[:n_eff]
-            ok, why = certify_row(Qh, Kh, block, k, q, tr)
+            ok, why = certify_row(Qh, Kh, block, k, q, tr, mask=mask, window=window)
             assert ok, f"row (h={h}, block={gb}): {why}; gpu={gi[:gc]} oracle={ridx[i][:gc]}"
             assert list(tr[-1][:gc, 0]) == list(gi[:gc])
             ties += 1
