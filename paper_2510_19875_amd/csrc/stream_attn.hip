@@ -92,6 +92,7 @@ struct AttnParams {
     long long T;
     int H, g, NB, kmax;
     float scale_log2e;           // scale * log2(e): softmax runs in base 2
+    int mask, window;            // the mask rule C (stream_mask) and its window
     WgMap map;
     SeqTable seqs;
 };
@@ -204,11 +205,11 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     n_blk = n_blk < 0 ? 0 : (n_blk > p.kmax ? p.kmax : n_blk);   // never read past the row's list
     const int *my_idx = p.idx + row * p.kmax;
 
-    // key sub-tiles to visit: all of every listed block, except that sub-tiles of the diagonal
-    // block lying entirely after this wavefront's queries are dropped (lists are ascending, so the
-    // diagonal block, if present, is the last one)
+    // key sub-tiles to visit: all of every listed block, except that under a causal rule the
+    // sub-tiles of the diagonal block lying entirely after this wavefront's queries are dropped
+    // (lists are ascending, so the diagonal block, if present, is the last one)
     int n_tiles = n_blk * KSUB;
-    if (n_blk > 0) {
+    if (n_blk > 0 && p.mask != STREAM_MASK_FULL) {
         const int last_r = my_idx[n_blk - 1];
         if (last_r * B + (KSUB - 1) * KT > qtok0 + QT - 1) {
             int vis = (qtok0 + QT - 1 - last_r * B) / KT + 1;
@@ -251,6 +252,13 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         const int ts = __builtin_amdgcn_readfirstlane(t);
         const int r = __builtin_amdgcn_readlane(my_blk, ts / KSUB);
         return r * B + (ts % KSUB) * KT;
+    };
+    // does the mask C (or the end of the sequence) cut through the sub-tile that starts at key k0?
+    auto needs_mask = [&](int k0) -> bool {
+        bool m = k0 + KT > L;
+        if (p.mask != STREAM_MASK_FULL) m = m || (k0 + KT - 1 > qtok0);                       // keys after a query
+        if (p.mask == STREAM_MASK_SLIDING) m = m || (k0 <= qtok0 + QT - 1 - p.window);         // keys before a window
+        return m;
     };
 
     if constexpr (PASS == 1) {
@@ -301,17 +309,152 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // that refill each V / K fragment right after its last use, and between the MFMA groups
     // the softmax of S(t) cut into small chunks.  S is double buffered by parity.
     // Iteration 0 multiplies a zero P, the last one computes an S nobody reads: one loop body
-    // serves all iterations.  Masked sub-tiles (diagonal block, sequence tail) follow in the
-    // plain loop below.
-    int n_fast = 0;
+    // serves all iterations.  Sub-tiles the mask cuts (diagonal block, sequence tail, edge of a
+    // sliding window) go through the plain order, before and after.
+    // Lists are ascending, so the sub-tiles the mask cuts are a prefix (keys before the window
+    // of a sliding mask) and a suffix (diagonal block, end of the sequence): [tb, t_end) is the
+    // unmasked middle, n_fast its length.
+    int tb = 0, t_end = 0;
     if constexpr (PIPE) {
-        n_fast = n_tiles;
-        while (n_fast > 0) {
-            const int k0 = tile_ktok0(n_fast - 1);
-            if ((k0 + KT - 1 > qtok0) || (k0 + KT > L)) --n_fast; else break;
-        }
-        n_fast = __builtin_amdgcn_readfirstlane(n_fast);
+        t_end = n_tiles;
+        while (t_end > 0 && needs_mask(tile_ktok0(t_end - 1))) --t_end;
+        if (p.mask == STREAM_MASK_SLIDING)
+            while (tb < t_end && needs_mask(tile_ktok0(tb))) ++tb;
+        tb = __builtin_amdgcn_readfirstlane(tb);
+        t_end = __builtin_amdgcn_readfirstlane(t_end > tb ? t_end : tb);
     }
+    const int n_fast = t_end - tb;
+
+    // One sub-tile in the plain order: loads, S, mask, softmax update, PV.
+    auto serial_tile = [&](const int t) {
+        const unsigned off = tile_off(t);
+        const int ktok0 = tile_ktok0(t);
+        const unsigned knext = tile_off(t + 1 < n_tiles ? t + 1 : t);
+        uint4 vreg[NK][NDB * NVF];
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int j = 0; j < NDB * NVF; ++j)
+                vreg[rb][j] = load_frag(vrs, lane_off, off, rb * NDB * NVF + j);
+        __builtin_amdgcn_sched_barrier(0);
+
+        floatx16 acc_s[NK][NQ];
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_s[rb][cq][i] = 0.f;
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb) {
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq)
+                    acc_s[rb][cq] = mfma16<BF16>(kreg[rb][fr], qf[cq][fr], acc_s[rb][cq]);
+                __builtin_amdgcn_sched_barrier(0);
+                kreg[rb][fr] = load_frag(krs, lane_off, knext, rb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        // mask (raw scores): the rule C inside the tile, padded keys
+        if (needs_mask(ktok0)) {
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int tk = ktok0 + rb * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
+                        const int tq = qtok0 + cq * 32 + col;
+                        // (a select, not a conditional store: `if (!visible) acc_s[..][i] = -inf` on a
+                        // vector element was dropped by this compiler inside the lambda)
+                        const bool visible = (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                        acc_s[rb][cq][i] = visible ? acc_s[rb][cq][i] : -INFINITY;
+                    }
+        }
+        // running softmax per query column, in base 2: logit = raw * c2
+        float alpha[NQ];
+        bool grew = false;
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[rb][cq][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
+            // the reference exponent follows the running maximum lazily: it moves only when the
+            // maximum has grown by more than 2^8, so probabilities stay <= 256 (harmless in fp32
+            // and bf16) and the output accumulators are rescaled a handful of times per row
+            const float m_new = mx > m_run[cq] + 8.f ? mx : m_run[cq];
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            grew = grew || (m_new > m_run[cq] && m_run[cq] != -INFINITY);
+            alpha[cq] = __builtin_amdgcn_exp2f(m_run[cq] - m_use);
+            m_run[cq] = m_new;
+            float sum = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pr = __builtin_amdgcn_exp2f(fmaf(acc_s[rb][cq][i], c2, -m_use));
+                    acc_s[rb][cq][i] = pr;
+                    sum += pr;
+                }
+            l_run[cq] = l_run[cq] * alpha[cq] + sum;   // per-lane partial; halves are added at the end
+        }
+        // rescale the output accumulators only when some column's maximum moved
+        if (__any(grew)) {
+#pragma unroll
+            for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        // The accumulators live in the accumulation registers, where the MFMAs
+                        // update them; scale them there (read, multiply, write back) so that this
+                        // rare path does not drag all 128 of them through the vector registers
+                        // on every iteration.
+                        float t = acc_o[db][cq][i], tmp;
+                        asm volatile("v_accvgpr_read_b32 %1, %0\n\t"
+                                     "v_mul_f32 %1, %1, %2\n\t"
+                                     "v_accvgpr_write_b32 %0, %1"
+                                     : "+a"(t), "=&v"(tmp)
+                                     : "v"(alpha[cq]));
+                        acc_o[db][cq][i] = t;
+                    }
+            asm volatile("s_nop 7");
+        }
+        // O^T += V^T P^T
+#pragma unroll
+        for (int rb = 0; rb < NK; ++rb)
+#pragma unroll
+            for (int vf = 0; vf < NVF; ++vf) {
+                uint4 pf[NQ];
+#pragma unroll
+                for (int cq = 0; cq < NQ; ++cq) {
+                    if constexpr (BF16) {
+                        const int o = vf * 8;
+                        pf[cq] = to_bf16_frag(acc_s[rb][cq][o + 0], acc_s[rb][cq][o + 1],
+                                              acc_s[rb][cq][o + 2], acc_s[rb][cq][o + 3],
+                                              acc_s[rb][cq][o + 4], acc_s[rb][cq][o + 5],
+                                              acc_s[rb][cq][o + 6], acc_s[rb][cq][o + 7]);
+                    } else {
+                        const int o = vf * 4;
+                        pf[cq].x = f2u(acc_s[rb][cq][o + 0]);
+                        pf[cq].y = f2u(acc_s[rb][cq][o + 1]);
+                        pf[cq].z = f2u(acc_s[rb][cq][o + 2]);
+                        pf[cq].w = f2u(acc_s[rb][cq][o + 3]);
+                    }
+                }
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                    for (int cq = 0; cq < NQ; ++cq)
+                        acc_o[db][cq] = mfma16<BF16>(vreg[rb][db * NVF + vf], pf[cq], acc_o[db][cq]);
+            }
+    };
+    for (int t = 0; t < tb; ++t) serial_tile(t);
+
     if constexpr (PIPE) {
     if (n_fast > 0) {
         constexpr int GPV = NVF * NDB;          // MFMA groups of the PV product
@@ -327,8 +470,9 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         //                            kb(sb) holds K(t+1), refilled with K(t+3).
         uint4 vr[2][GPV];
         uint4 k1r[FR];                          // parity 1 of the K buffer; parity 0 is kreg[0]
+        // the pipeline counts its sub-tiles from 0; list position = tb + that
         auto clampk = [&](int x) {              // K tile to prefetch: never past the first masked tile
-            x = x < n_fast ? x : n_fast;
+            x = tb + (x < n_fast ? x : n_fast);
             return x < n_tiles ? x : n_tiles - 1;
         };
 #pragma unroll
@@ -356,7 +500,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 kreg[0][fr] = load_frag(krs, lane_off, k1, fr);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            const unsigned off0 = tile_off(0);
+            const unsigned off0 = tile_off(tb);
 #pragma unroll
             for (int g = 0; g < GPV; ++g) {
                 const int vf = g / NDB, db = g % NDB;
@@ -372,7 +516,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         }
         auto iter = [&](const int t, auto SBc) {
             constexpr int sb = decltype(SBc)::value, ob = sb ^ 1;
-            const unsigned voff = tile_off(t + 1 < n_fast ? t + 1 : n_fast - 1);
+            const unsigned voff = tile_off(tb + (t + 1 < n_fast ? t + 1 : n_fast - 1));
             const unsigned knext = tile_off(clampk(t + 3));
             float sv[NQ][16], mx[NQ], mxo[NQ], m_use[NQ], alpha[NQ], sum[NQ];
             bool grew = false;
@@ -505,131 +649,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         }
     }
     }
-    for (int t = n_fast; t < n_tiles; ++t) {
-        const unsigned off = tile_off(t);
-        const int ktok0 = tile_ktok0(t);
-        const unsigned knext = tile_off(t + 1 < n_tiles ? t + 1 : t);
-        uint4 vreg[NK][NDB * NVF];
-#pragma unroll
-        for (int rb = 0; rb < NK; ++rb)
-#pragma unroll
-            for (int j = 0; j < NDB * NVF; ++j)
-                vreg[rb][j] = load_frag(vrs, lane_off, off, rb * NDB * NVF + j);
-        __builtin_amdgcn_sched_barrier(0);
-
-        floatx16 acc_s[NK][NQ];
-#pragma unroll
-        for (int rb = 0; rb < NK; ++rb)
-#pragma unroll
-            for (int cq = 0; cq < NQ; ++cq)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc_s[rb][cq][i] = 0.f;
-#pragma unroll
-        for (int fr = 0; fr < FR; ++fr)
-#pragma unroll
-            for (int rb = 0; rb < NK; ++rb) {
-#pragma unroll
-                for (int cq = 0; cq < NQ; ++cq)
-                    acc_s[rb][cq] = mfma16<BF16>(kreg[rb][fr], qf[cq][fr], acc_s[rb][cq]);
-                __builtin_amdgcn_sched_barrier(0);
-                kreg[rb][fr] = load_frag(krs, lane_off, knext, rb * FR + fr);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        // mask (raw scores): causal inside the tile, padded keys
-        const bool need_mask = (ktok0 + KT - 1 > qtok0) || (ktok0 + KT > L);
-        if (need_mask) {
-#pragma unroll
-            for (int rb = 0; rb < NK; ++rb)
-#pragma unroll
-                for (int cq = 0; cq < NQ; ++cq)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int tk = ktok0 + rb * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
-                        const int tq = qtok0 + cq * 32 + col;
-                        if (tk > tq || tk >= L) acc_s[rb][cq][i] = -INFINITY;
-                    }
-        }
-        // running softmax per query column, in base 2: logit = raw * c2
-        float alpha[NQ];
-        bool grew = false;
-#pragma unroll
-        for (int cq = 0; cq < NQ; ++cq) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int rb = 0; rb < NK; ++rb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[rb][cq][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
-            // the reference exponent follows the running maximum lazily: it moves only when the
-            // maximum has grown by more than 2^8, so probabilities stay <= 256 (harmless in fp32
-            // and bf16) and the output accumulators are rescaled a handful of times per row
-            const float m_new = mx > m_run[cq] + 8.f ? mx : m_run[cq];
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            grew = grew || (m_new > m_run[cq] && m_run[cq] != -INFINITY);
-            alpha[cq] = __builtin_amdgcn_exp2f(m_run[cq] - m_use);
-            m_run[cq] = m_new;
-            float sum = 0.f;
-#pragma unroll
-            for (int rb = 0; rb < NK; ++rb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float pr = __builtin_amdgcn_exp2f(fmaf(acc_s[rb][cq][i], c2, -m_use));
-                    acc_s[rb][cq][i] = pr;
-                    sum += pr;
-                }
-            l_run[cq] = l_run[cq] * alpha[cq] + sum;   // per-lane partial; halves are added at the end
-        }
-        // rescale the output accumulators only when some column's maximum moved
-        if (__any(grew)) {
-#pragma unroll
-            for (int cq = 0; cq < NQ; ++cq)
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        // The accumulators live in the accumulation registers, where the MFMAs
-                        // update them; scale them there (read, multiply, write back) so that this
-                        // rare path does not drag all 128 of them through the vector registers
-                        // on every iteration.
-                        float t = acc_o[db][cq][i], tmp;
-                        asm volatile("v_accvgpr_read_b32 %1, %0\n\t"
-                                     "v_mul_f32 %1, %1, %2\n\t"
-                                     "v_accvgpr_write_b32 %0, %1"
-                                     : "+a"(t), "=&v"(tmp)
-                                     : "v"(alpha[cq]));
-                        acc_o[db][cq][i] = t;
-                    }
-            asm volatile("s_nop 7");
-        }
-        // O^T += V^T P^T
-#pragma unroll
-        for (int rb = 0; rb < NK; ++rb)
-#pragma unroll
-            for (int vf = 0; vf < NVF; ++vf) {
-                uint4 pf[NQ];
-#pragma unroll
-                for (int cq = 0; cq < NQ; ++cq) {
-                    if constexpr (BF16) {
-                        const int o = vf * 8;
-                        pf[cq] = to_bf16_frag(acc_s[rb][cq][o + 0], acc_s[rb][cq][o + 1],
-                                              acc_s[rb][cq][o + 2], acc_s[rb][cq][o + 3],
-                                              acc_s[rb][cq][o + 4], acc_s[rb][cq][o + 5],
-                                              acc_s[rb][cq][o + 6], acc_s[rb][cq][o + 7]);
-                    } else {
-                        const int o = vf * 4;
-                        pf[cq].x = f2u(acc_s[rb][cq][o + 0]);
-                        pf[cq].y = f2u(acc_s[rb][cq][o + 1]);
-                        pf[cq].z = f2u(acc_s[rb][cq][o + 2]);
-                        pf[cq].w = f2u(acc_s[rb][cq][o + 3]);
-                    }
-                }
-#pragma unroll
-                for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                    for (int cq = 0; cq < NQ; ++cq)
-                        acc_o[db][cq] = mfma16<BF16>(vreg[rb][db * NVF + vf], pf[cq], acc_o[db][cq]);
-            }
-    }
+    for (int t = t_end; t < n_tiles; ++t) serial_tile(t);
 
     // ------------------------------------------------------------------ normalise, store O, lse
     float lse2[NQ];   // log2-domain log-sum-exp of each query column
@@ -711,7 +731,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 kreg[ck][fr] = load_frag(krs, lane_off, knext, ck * FR + fr);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        const bool need_mask = (ktok0 + KT - 1 > qtok0) || (ktok0 + KT > L) || (qtok0 + QT > L);
+        const bool need_mask = needs_mask(ktok0) || (qtok0 + QT > L);
 #pragma unroll
         for (int ck = 0; ck < NK; ++ck) {
             const int tk = ktok0 + ck * 32 + col;
@@ -729,7 +749,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                     for (int i = 0; i < 16; ++i) {
                         const int tq = qtok0 + rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
                         const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
-                        colsum += (tq < L && tk <= tq) ? e : 0.f;
+                        colsum += ((tq < L) & mask_token(p.mask, p.window, tq, tk)) ? e : 0.f;
                     }
             }
             colsum += __shfl_xor(colsum, 32);
@@ -855,6 +875,7 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
     p.idx = idx; p.cnt = cnt; p.lse = lse; p.mass = mass;
     p.T = pb.T; p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.kmax = topk_max;
     p.scale_log2e = scale * 1.4426950408889634f;
+    p.mask = pb.mask; p.window = pb.window;
     p.seqs = pb.seqs;
     p.lse2 = mass ? (float *)(ws + w.lse2) : nullptr;
     for (int pass = 1; pass <= (mass ? 2 : 1); ++pass) {

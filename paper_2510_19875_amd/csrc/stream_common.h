@@ -93,9 +93,10 @@ __device__ __forceinline__ int seq_of_block(const SeqTable &t, int gb)
 // row are the contiguous range [mask_rmin, mask_rmax].
 __host__ __device__ __forceinline__ bool mask_token(int mask, int window, int tq, int tk)
 {
-    if (mask == STREAM_MASK_FULL) return true;
-    if (mask == STREAM_MASK_SLIDING) return tk <= tq && tq - tk < window;
-    return tk <= tq;
+    // branch-free on purpose (| and & on bools): this sits in per-element code of the kernels
+    const bool causal_ok = tk <= tq;
+    const bool window_ok = (mask != STREAM_MASK_SLIDING) | (tq - tk < window);
+    return (mask == STREAM_MASK_FULL) | (causal_ok & window_ok);
 }
 
 __host__ __device__ __forceinline__ int mask_rmin(int mask, int window, int q, int b)

@@ -303,7 +303,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                         for (int i = 0; i < 16; ++i) {
                             const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
                             const int tk = ktok0 + cb * 32 + (lane & 31);
-                            if (tq < L && tk < L && mask_token(p.mask, p.window, tq, tk)) mx = fmaxf(mx, acc[rb][cb][i]);
+                            const bool visible = (tq < L) & (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                            mx = visible ? fmaxf(mx, acc[rb][cb][i]) : mx;
                         }
             }
             mx = wave_max(mx);

@@ -68,3 +68,45 @@ def test_prune_sliding_ragged_batch_and_sweep():
         torch.cuda.synchronize()
         np.testing.assert_array_equal(m["idx"][:, i, :, :k].cpu().numpy(), one["idx"].cpu().numpy())
         np.testing.assert_array_equal(m["score"][:, i, :, :k].cpu().numpy(), one["score"].cpu().numpy())
+
+
+def attn_case(w, mask, window):
+    print(f"[mask-attn] {mask} W={window} {w.name} b={w.block} k={w.topk}", flush=True)
+    Q, K, V, _ = wl.make_inputs(w)
+    cu = w.cu_seqlens if w.batch > 1 else None
+    topk = list(w.topk) if w.batch > 1 else w.topk[0]
+    Qf, Kf, Vf = Q.float().numpy(), K.float().numpy(), V.float().numpy()
+    ref_p = so.prune(Qf, Kf, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu, mask=mask, window=window)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    # the oracle's lists feed the GPU attention, so near-ties of the prune cannot leak in here
+    out = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), w.heads, w.kv_heads, w.block,
+                                     torch.from_numpy(ref_p["idx"]).to(DEV), torch.from_numpy(ref_p["cnt"]).to(DEV),
+                                     scale, cu_seqlens=cu, want_lse=True, want_mass=True, mask=mask, window=window)
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Qf, Kf, Vf, w.heads, w.kv_heads, w.block, ref_p["idx"], ref_p["cnt"], scale,
+                         cu_seqlens=cu, mask=mask, window=window)
+    err = np.abs(out["O"].float().cpu().numpy() - ref["O"]).max()
+    lerr = np.abs(out["lse"].cpu().numpy() - ref["lse"]).max()
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    merr = (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max()
+    print(f"[mask-attn] max|dO|={err:.3e} max|dlse|={lerr:.3e} mass rel err={merr:.3e}", flush=True)
+    assert err <= TOL[w.dtype] and lerr <= 1e-3 and merr <= 1e-3
+    np.testing.assert_allclose(mass.sum(axis=1), w.T, rtol=1e-4)   # every real row of P sums to 1
+
+
+@pytest.mark.parametrize("mask,window", [("sliding", 64), ("sliding", 200), ("sliding", 1), ("sliding", 777),
+                                          ("full", 0)])
+@pytest.mark.parametrize("block,dtype,T,k,d", [(64, "bf16", 64 * 40 + 9, 4, 128), (32, "f32", 32 * 50 + 3, 6, 64),
+                                                (128, "bf16", 128 * 30 + 77, 3, 128), (64, "bf16", 64 * 20, 5, 64),
+                                                (64, "f32", 64 * 12 + 1, 3, 128)])
+def test_attention_under_mask_rules(mask, window, block, dtype, T, k, d):
+    w = wl.scaled(wl.config(2), (T,), topk=k, heads=4, kv_heads=2, block=block, dtype=dtype, head_dim=d,
+                  needles_per_kv_head=2)
+    attn_case(w, mask, window)
+
+
+def test_attention_sliding_ragged_batch():
+    w = wl.scaled(wl.config(5), (700, 1300, 64, 33, 2049), topk=(2, 3, 1, 4, 2), heads=14, kv_heads=2,
+                  anchors_per_seq=3)
+    attn_case(w, "sliding", 300)
+    attn_case(w, "full", 0)
