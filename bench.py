@@ -228,6 +228,7 @@ def main():
         result["mask_diff_roofline"] = mask_diff_standalone(kmax)
     if not args.no_sweep and w.batch == 1:
         result["k_sweep"] = k_sweep(w, layers[0])
+        result["mask_rules"] = mask_rules(w, layers[0], scale)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale)
     print(json.dumps(result))
@@ -281,6 +282,45 @@ def k_sweep(w, layer, reps=4):
     return {"topk_list": ks, "sweep_ms": multi_ms, "separate_calls_ms": sep_ms,
             "speedup": sep_ms / multi_ms, "block_scores_sweep": multi_tiles,
             "block_scores_separate_calls": sep_tiles}
+
+
+def mask_rules(w, layer, scale, reps=3):
+    """The same step under the other mask rules C: a sliding window of 4096 tokens (a local
+    layer) and no mask at all (Alg. 1), next to the causal mask; milliseconds per call."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, V = layer
+    out = {}
+    for name, mask, window in (("causal", "causal", 0), ("sliding_4096", "sliding", 4096), ("full", "full", 0)):
+        st = {}
+
+        def prune():
+            r = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, w.topk[0], workspace=st.get("wp"),
+                                     out=st.get("op"), mask=mask, window=window)
+            st["wp"], st["op"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}
+
+        def attn():
+            r = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, w.block, st["op"]["idx"], st["op"]["cnt"],
+                                           scale, want_lse=True, want_mass=True, workspace=st.get("wa"),
+                                           out=st.get("oa"), mask=mask, window=window)
+            st["wa"], st["oa"] = r["workspace"], {"O": r["O"], "lse": r["lse"], "mass": r["mass"]}
+
+        res = {}
+        for key, fn in (("prune_ms", prune), ("attn_ms", attn)):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res[key] = e0.elapsed_time(e1) / reps
+        res["retained_blocks"] = int(st["op"]["cnt"].sum().item())
+        out[name] = res
+    return out
 
 
 def mask_diff_standalone(kmax, rows=1 << 21, launches=12):

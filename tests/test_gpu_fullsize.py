@@ -13,7 +13,7 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
-def check_full(w, heads_sampled, n_rows, seed, check_sink=True):
+def check_full(w, heads_sampled, n_rows, seed, check_sink=True, mask="causal", window=0):
     dev = torch.device("cuda:0")
     print(f"[full] {w.name}: generating inputs", flush=True)
     Q, K, V, meta = wl.make_inputs(w, device=dev)
@@ -24,11 +24,11 @@ def check_full(w, heads_sampled, n_rows, seed, check_sink=True):
     base = torch.cuda.memory_allocated()
     print("[full] prune", flush=True)
     out = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu,
-                               want_score=True, want_trace=True)
+                               want_score=True, want_trace=True, mask=mask, window=window)
     scale = 1.0 / math.sqrt(w.head_dim)
     print("[full] attention", flush=True)
     att = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, w.block, out["idx"], out["cnt"], scale,
-                                     cu_seqlens=cu, want_lse=True, want_mass=True)
+                                     cu_seqlens=cu, want_lse=True, want_mass=True, mask=mask, window=window)
     torch.cuda.synchronize()
     extra = torch.cuda.max_memory_allocated() - base
     # O(T) memory: everything beyond the inputs is outputs + workspaces, linear in T (no T x T term)
@@ -42,11 +42,18 @@ def check_full(w, heads_sampled, n_rows, seed, check_sink=True):
     qloc = torch.from_numpy(bloc).to(dev)
     kseq = torch.tensor([w.topk[s] for s in bseq], device=dev)
     cnt = out["cnt"]
-    assert torch.equal(cnt, torch.minimum(kseq, qloc + 1).to(torch.int32)[None, :].expand_as(cnt))
+    # valid key blocks of every row under the mask rule: rmin .. rmax
+    nseq_blocks = torch.tensor([w.blocks_per_seq[s] for s in bseq], device=dev)
+    rmax = nseq_blocks - 1 if mask == "full" else qloc
+    rmin = torch.zeros_like(qloc)
+    if mask == "sliding":
+        lo = qloc * w.block - window + 1
+        rmin = torch.where(lo > 0, torch.div(lo, w.block, rounding_mode="floor"), torch.zeros_like(lo))
+    assert torch.equal(cnt, torch.minimum(kseq, rmax - rmin + 1).to(torch.int32)[None, :].expand_as(cnt))
     idx = out["idx"]
     slot = torch.arange(kmax, device=dev)[None, None, :]
     live = slot < cnt[:, :, None]
-    assert bool(((idx >= 0) & (idx <= qloc[None, :, None]))[live].all()) and bool((idx[~live] == -1).all())
+    assert bool(((idx >= rmin[None, :, None]) & (idx <= rmax[None, :, None]))[live].all()) and bool((idx[~live] == -1).all())
     assert bool((idx[:, :, 1:] > idx[:, :, :-1])[live[:, :, 1:]].all())
     if check_sink:
         assert bool((idx[:, :, 0] == 0).all())
@@ -75,20 +82,21 @@ def check_full(w, heads_sampled, n_rows, seed, check_sink=True):
                           V[h // g, a:e].float().cpu().numpy())
         Qh, Kh, Vh = cache[key]
         k = w.topk[s]
-        r = so.prune_head(Qh, Kh, w.block, k, qblocks=[q])
+        r = so.prune_head(Qh, Kh, w.block, k, qblocks=[q], mask=mask, window=window)
         c = int(r["cnt"][0])
         if np.array_equal(r["idx"][0], idx_c[h, gb, :k]):
             equal += 1
             np.testing.assert_allclose(score_c[h, gb, :c], r["score"][0, :c], rtol=1e-4)
         else:
             n_eff = max(1, math.ceil(math.log2(math.ceil(-(-(e - a) // w.block) / k))))
-            ok, why = parity.certify_row(Qh, Kh, w.block, k, q, trace_c[:n_eff, h, gb, :k])
+            ok, why = parity.certify_row(Qh, Kh, w.block, k, q, trace_c[:n_eff, h, gb, :k], mask=mask, window=window)
             assert ok, (h, gb, why)
             ties += 1
         # attention of that row with the GPU's own list (checked above) against Eq. (2) in fp64
         gi = np.ascontiguousarray(idx_c[h, gb][None, :])
         gc = np.ascontiguousarray(cnt_c[h, gb][None])
-        ra = so.sparse_attn(Qh[None], Kh[None], Vh[None], 1, 1, w.block, gi, gc, scale, rows=[(0, q)])
+        ra = so.sparse_attn(Qh[None], Kh[None], Vh[None], 1, 1, w.block, gi, gc, scale, rows=[(0, q)],
+                            mask=mask, window=window)
         t0, t1 = q * w.block, min((q + 1) * w.block, e - a)
         O_g = att["O"][h, a + t0:a + t1].float().cpu().numpy()
         l_g = att["lse"][h, a + t0:a + t1].cpu().numpy()
@@ -103,6 +111,13 @@ def check_full(w, heads_sampled, n_rows, seed, check_sink=True):
 
 def test_config3_attention_and_prune_sampled():
     check_full(wl.config(3), heads_sampled=[2, 17, 30], n_rows=36, seed=11)
+
+
+def test_config3_sliding_window_sampled():
+    """The headline shape under a sliding window of 4096 tokens (65 valid key blocks per row,
+    32 kept): the local layers of the Gemma 3 models the paper traces."""
+    check_full(wl.config(3), heads_sampled=[4, 21], n_rows=24, seed=14, check_sink=False,
+               mask="sliding", window=4096)
 
 
 def test_config4_one_million_tokens_sampled():
