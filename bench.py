@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-select", action="store_true", help="skip the standalone select-kernel measurement")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k-sweep (stream_prune_multi) measurement")
+    ap.add_argument("--dense-reference", action="store_true",
+                    help="also time PyTorch's dense causal attention on the same tensors (context only)")
     ap.add_argument("--levels-per-launch", type=int, default=0,
                     help="refinement levels per kernel launch (0 = library default: all in one)")
     ap.add_argument("--cpu-rows", type=int, default=1536)
@@ -229,9 +231,32 @@ def main():
     if not args.no_sweep and w.batch == 1:
         result["k_sweep"] = k_sweep(w, layers[0])
         result["mask_rules"] = mask_rules(w, layers[0], scale)
+    if args.dense_reference and w.batch == 1:
+        result["dense_reference"] = dense_reference(w, layers[0])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale)
     print(json.dumps(result))
+
+
+def dense_reference(w, layer):
+    """Context only: the dense causal attention the method replaces, as PyTorch's fused
+    scaled_dot_product_attention computes it on the same Q, K, V (one call, after a warm-up)."""
+    import torch
+
+    Q, K, V = layer
+    g = w.heads // w.kv_heads
+    q, k, v = Q[None], K[None].repeat_interleave(g, 1), V[None].repeat_interleave(g, 1)
+    torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    flop = 4.0 * w.head_dim * w.heads * (float(w.T) * (w.T + 1) / 2)
+    return {"what": "torch scaled_dot_product_attention(is_causal=True), K/V repeated per query head",
+            "ms": ms, "tflops": flop / (ms * 1e-3) / 1e12}
 
 
 def k_sweep(w, layer, reps=4):
