@@ -231,6 +231,7 @@ def main():
     if not args.no_sweep and w.batch == 1:
         result["k_sweep"] = k_sweep(w, layers[0])
         result["mask_rules"] = mask_rules(w, layers[0], scale)
+        result["variable_k"] = variable_k(w, layers[0])
     if args.dense_reference and w.batch == 1:
         result["dense_reference"] = dense_reference(w, layers[0])
     if not args.no_cpu_baseline:
@@ -346,6 +347,34 @@ def mask_rules(w, layer, scale, reps=3):
         res["retained_blocks"] = int(st["op"]["cnt"].sum().item())
         out[name] = res
     return out
+
+
+def variable_k(w, layer, reps=3):
+    """stream_prune_variable: every row keeps 1/64 of its valid key blocks (k from 1 at the top
+    of the pattern to the headline k at the bottom), next to the constant-k call."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, _ = layer
+    kmax = w.topk[0]
+    st = {}
+
+    def run():
+        r = binding.stream_prune_variable(Q, K, w.heads, w.kv_heads, w.block, 1, 64, 1, kmax,
+                                          workspace=st.get("ws"), out=st.get("out"), want_tiles=True)
+        st["ws"], st["out"], st["tiles"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}, r["tiles"]
+
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return {"rule": f"k(row) = clamp(ceil(valid/64), 1, {kmax})", "prune_ms": e0.elapsed_time(e1) / reps,
+            "block_scores": int(st["tiles"].item()), "retained_blocks": int(st["out"]["cnt"].sum().item())}
 
 
 def mask_diff_standalone(kmax, rows=1 << 21, launches=12):

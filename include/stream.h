@@ -188,6 +188,26 @@ stream_status stream_prune_multi(const void *Q, const void *K, const stream_shap
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Algorithm 2 with a sparsity constant that varies per query block.  Section 4.2.1 (Discussion)
+ * and Section 6 (4) observe that under a causal mask a constant k prunes the rows at the bottom
+ * of the pattern harder than those at the top, and name a variable k as the remedy without
+ * defining one; this entry point keeps a fixed share of each row's valid key blocks:
+ *
+ *     k(row) = min(topk_max, max(topk_min, ceil(valid(row) * keep_num / keep_den)))
+ *
+ * where valid(row) is the number of key blocks the mask C leaves to the row (q + 1 for the
+ * causal mask).  Every row then runs Algorithm 2 as printed with its own k (and its own number
+ * of levels).  Outputs as stream_prune: idx/score rows have topk_max entries, cnt = min(k(row),
+ * valid(row)).  1 <= keep_num <= keep_den, 1 <= topk_min <= topk_max <= 64.  Workspace:
+ * stream_prune_workspace_bytes(shape, topk_max).  diag->trace has stream_prune_levels(shape,
+ * topk_min, NULL) levels.
+ */
+stream_status stream_prune_variable(const void *Q, const void *K, const stream_shape *shape,
+                                    int keep_num, int keep_den, int topk_min, int topk_max,
+                                    int *idx, int *cnt, float *score, const stream_prune_diag *diag,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The "top-k indices" and "update" lines of Algorithm 2 (Appendix C) as a pass of their own.
  * stream_prune performs this step inside its scoring kernels; this entry point applies it to
  * branch scores that already sit in memory.

@@ -215,6 +215,60 @@ def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
             "evals": evals, "rows": rows_arr, "blk_off": blk_off}
 
 
+def variable_k(valid: int, keep_num: int, keep_den: int, topk_min: int, topk_max: int) -> int:
+    """Sparsity constant of a row that keeps a fixed share of its valid key blocks.  The paper
+    names a variable k as the remedy for the harder pruning of the bottom rows of a causal
+    pattern (Section 4.2.1, Discussion; Section 6 (4)) without defining one; this is the rule the
+    library implements: ceil(valid * keep_num / keep_den), clamped to [topk_min, topk_max]."""
+    k = -((-valid * keep_num) // keep_den)
+    return min(topk_max, max(topk_min, k))
+
+
+def valid_blocks(q: int, N: int, block: int, mask: str = "causal", window: int = 0) -> int:
+    """Number of key blocks the mask rule leaves to query block q (they are contiguous)."""
+    if mask == "full":
+        return N
+    rmin = 0
+    if mask == "sliding":
+        lo = q * block - window + 1
+        rmin = lo // block if lo > 0 else 0
+    return q - rmin + 1
+
+
+def prune_variable(Q, K, heads: int, kv_heads: int, block: int, keep_num: int, keep_den: int,
+                   topk_min: int, topk_max: int, cu_seqlens=None,
+                   rows: Optional[Sequence[Sequence[int]]] = None, mask: str = "causal", window: int = 0):
+    """Algorithm 2 run row by row with k(row) = variable_k(valid(row), ...).  Output arrays as
+    prune(): [heads, NB, topk_max] (full) or [len(rows), topk_max]; also "k" per row."""
+    Q, K = _f32(Q), _f32(K)
+    H, T, d = Q.shape
+    g = heads // kv_heads
+    cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
+    bseq, bloc = block_table(cu, block)
+    NB = len(bseq)
+    full = rows is None
+    rows_arr = (np.asarray([(h, gb) for h in range(H) for gb in range(NB)], dtype=np.int64) if full
+                else np.asarray(rows, dtype=np.int64).reshape(-1, 2))
+    R = len(rows_arr)
+    idx = np.full((R, topk_max), -1, dtype=np.int32)
+    cnt = np.zeros((R,), dtype=np.int32)
+    score = np.full((R, topk_max), -np.inf, dtype=np.float64)
+    ks = np.zeros((R,), dtype=np.int32)
+    for i, (h, gb) in enumerate(rows_arr):
+        s, q = int(bseq[gb]), int(bloc[gb])
+        L = cu[s + 1] - cu[s]
+        N = -(-L // block)
+        k = variable_k(valid_blocks(q, N, block, mask, window), keep_num, keep_den, topk_min, topk_max)
+        out = prune_head(Q[h, cu[s]:cu[s + 1]], K[h // g, cu[s]:cu[s + 1]], block, k, [q], mask=mask, window=window)
+        idx[i, :k] = out["idx"][0]
+        cnt[i] = out["cnt"][0]
+        score[i, :k] = out["score"][0]
+        ks[i] = k
+    if full:
+        idx, cnt, score, ks = idx.reshape(H, NB, topk_max), cnt.reshape(H, NB), score.reshape(H, NB, topk_max), ks.reshape(H, NB)
+    return {"idx": idx, "cnt": cnt, "score": score, "k": ks, "rows": rows_arr}
+
+
 def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
                 cu_seqlens=None, rows: Optional[Sequence[Sequence[int]]] = None,
                 want_mass: bool = True, mask: str = "causal", window: int = 0):

@@ -20,7 +20,7 @@ STREAM_F32, STREAM_BF16 = 0, 1
 
 EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
            "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
-           "stream_prune_multi_workspace_bytes", "stream_prune_multi",
+           "stream_prune_multi_workspace_bytes", "stream_prune_multi", "stream_prune_variable",
            "stream_select_update", "stream_mask_diff", "stream_status_str"]
 
 
@@ -80,6 +80,9 @@ def load():
     lib.stream_prune_multi.restype = ctypes.c_int
     lib.stream_prune_multi.argtypes = [vp, vp, sp, ip, ctypes.c_int, ctypes.c_int, vp, vp, vp,
                                        ctypes.POINTER(StreamPruneDiag), vp, ctypes.c_size_t, vp]
+    lib.stream_prune_variable.restype = ctypes.c_int
+    lib.stream_prune_variable.argtypes = [vp, vp, sp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                          vp, vp, vp, ctypes.POINTER(StreamPruneDiag), vp, ctypes.c_size_t, vp]
     lib.stream_select_update.restype = ctypes.c_int
     lib.stream_select_update.argtypes = [vp, vp, vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.stream_mask_diff.restype = ctypes.c_int
@@ -237,6 +240,53 @@ def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: i
     if rc != STREAM_OK:
         raise StreamError(rc, "stream_prune_multi")
     return {"idx": idx, "cnt": cnt, "score": score, "tiles": tiles, "workspace": workspace, "_keep": keep}
+
+
+def stream_prune_variable(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
+                          keep_num: int, keep_den: int, topk_min: int, topk_max: int,
+                          cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
+                          want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None,
+                          mask="causal", window: int = 0):
+    """Algorithm 2 with k(row) = clamp(ceil(valid(row) * keep_num / keep_den), topk_min, topk_max).
+    Returns dict(idx [H, NB, topk_max], cnt [H, NB], score, trace, tiles)."""
+    lib = load()
+    if not (Q.is_cuda and K.is_cuda):
+        raise ValueError("Q and K must be device tensors (the library has no CPU path)")
+    H, T, d = Q.shape
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
+                             mask=mask, window=window)
+    NB = num_blocks(shape)
+    if NB < 0:
+        raise StreamError(STREAM_EINVAL, "stream_num_blocks")
+    dev = Q.device
+    kmax = int(topk_max)
+    if out is None:
+        idx = torch.empty((H, NB, kmax), dtype=torch.int32, device=dev)
+        cnt = torch.empty((H, NB), dtype=torch.int32, device=dev)
+        score = torch.empty((H, NB, kmax), dtype=torch.float32, device=dev) if want_score else None
+    else:
+        idx, cnt, score = out["idx"], out["cnt"], out.get("score")
+    need = lib.stream_prune_workspace_bytes(ctypes.byref(shape), kmax)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+    diag = StreamPruneDiag()
+    trace = tiles = None
+    levels = lib.stream_prune_levels(ctypes.byref(shape), int(topk_min), None)
+    if want_trace:
+        trace = torch.empty((max(levels, 0), H, NB, kmax, 2), dtype=torch.int32, device=dev)
+        diag.trace = trace.data_ptr()
+    if want_tiles:
+        tiles = torch.zeros((1,), dtype=torch.int64, device=dev)
+        diag.tiles_scored = tiles.data_ptr()
+    rc = lib.stream_prune_variable(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape), int(keep_num), int(keep_den),
+                                   int(topk_min), kmax, idx.data_ptr(), cnt.data_ptr(),
+                                   score.data_ptr() if score is not None else None,
+                                   ctypes.byref(diag) if (want_trace or want_tiles) else None,
+                                   workspace.data_ptr(), workspace.numel(), _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_prune_variable")
+    return {"idx": idx, "cnt": cnt, "score": score, "trace": trace, "tiles": tiles, "levels": levels,
+            "workspace": workspace, "_keep": keep}
 
 
 def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,

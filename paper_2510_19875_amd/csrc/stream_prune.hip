@@ -35,9 +35,27 @@ struct PruneParams {
     WgMap map;
     SeqTable seqs;
     int mask, window;            // the mask rule C (stream_mask) and its window
+    int vk_num, vk_den, vk_min;  // variable k (vk_den > 0): k(row) = clamp(ceil(valid * num / den), min, kmax)
     int n_k;                     // k sweep (MULTI kernels): values of k, outputs [H, n_k, NB, ...]
     int klist[kMaxSweep];
 };
+
+// max(1, ceil(log2(ceil(N / k)))): the levels after which every node is a single block
+__host__ __device__ __forceinline__ int levels_for(int N, int k)
+{
+    const int per = (N + k - 1) / k;
+    int lv = 0;
+    for (long long v = 1; v < per; v <<= 1) ++lv;
+    return lv < 1 ? 1 : lv;
+}
+
+// k of a row under the variable-k rule: a fixed share of the row's valid key blocks
+__host__ __device__ __forceinline__ int variable_k(int valid, int num, int den, int kmin, int kmax)
+{
+    long long k = ((long long)valid * num + den - 1) / den;
+    k = k < kmin ? kmin : k;
+    return (int)(k > kmax ? kmax : k);
+}
 
 __device__ __forceinline__ void wave_sync()
 {
@@ -116,8 +134,14 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int h = kvh * p.g + (int)(rk % p.g);
     const int sq = seq_of_block(p.seqs, gb);
     const SeqDesc sd = p.seqs.d[sq];
-    if (!MULTI && p.level_begin > sd.levels) return;
     const int q = gb - sd.blk0, N = sd.nblk, L = sd.len;
+    int row_k = sd.k, row_levels = sd.levels;
+    if (!MULTI && p.vk_den > 0) {
+        const int valid = mask_rmax(p.mask, q, N) - mask_rmin(p.mask, p.window, q, B) + 1;
+        row_k = variable_k(valid, p.vk_num, p.vk_den, p.vk_min, p.kmax);
+        row_levels = levels_for(N, row_k);
+    }
+    if (!MULTI && p.level_begin > row_levels) return;
     const int qh = WPR == 4 ? (wave >> 1) : 0;            // query half / key half of this wavefront
     const int kh = WPR == 4 ? (wave & 1) : 0;
 
@@ -152,12 +176,11 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int n_k = MULTI ? p.n_k : 1;
     for (int ki = 0; ki < n_k; ++ki) {
     // this pass's k, its number of levels and its output row
-    int k = sd.k, levels = sd.levels;
+    int k = row_k, levels = row_levels;
     long long row = (long long)h * p.NB + gb;
     if constexpr (MULTI) {
         k = p.klist[ki];
-        const int per = (N + k - 1) / k;                      // max(1, ceil(log2(ceil(N / k)))) levels
-        levels = per <= 2 ? 1 : 32 - __builtin_clz(per - 1);
+        levels = levels_for(N, k);
         row = ((long long)h * n_k + ki) * p.NB + gb;
     }
     const int level_begin = MULTI ? 1 : p.level_begin;
@@ -445,8 +468,10 @@ using namespace stream;
 
 // Packs K and runs the refinement kernel: once per group of levels, or (topk_list != nullptr)
 // once for a whole sweep over k, every row then running all its levels for every k in turn.
+struct VariableK { int num, den, kmin; };   // den == 0: off
+
 static stream_status run_prune(const void *Q, const void *K, const stream_shape *shape, const Problem &pb,
-                               const int *topk_list, int n_k, int *idx, int *cnt, float *score,
+                               const int *topk_list, int n_k, VariableK vk, int *idx, int *cnt, float *score,
                                const stream_prune_diag *diag, void *workspace, size_t workspace_bytes,
                                void *hip_stream)
 {
@@ -481,6 +506,7 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     p.seqs = pb.seqs;
     p.mask = pb.mask; p.window = pb.window;
     p.max_levels = pb.max_levels;
+    p.vk_num = vk.num; p.vk_den = vk.den; p.vk_min = vk.kmin;
     p.n_k = multi ? n_k : 1;
     for (int i = 0; i < kMaxSweep; ++i) p.klist[i] = multi && i < n_k ? topk_list[i] : 0;
     int wpr = 1;
@@ -525,7 +551,8 @@ stream_status stream_prune(const void *Q, const void *K, const stream_shape *sha
     Problem pb;
     stream_status rc = make_problem(shape, topk, topk_per_seq, topk_max, &pb);
     if (rc != STREAM_OK) return rc;
-    return run_prune(Q, K, shape, pb, nullptr, 0, idx, cnt, score, diag, workspace, workspace_bytes, hip_stream);
+    return run_prune(Q, K, shape, pb, nullptr, 0, VariableK{0, 0, 0}, idx, cnt, score, diag, workspace,
+                     workspace_bytes, hip_stream);
 }
 
 size_t stream_prune_multi_workspace_bytes(const stream_shape *shape, int n_k, int topk_max)
@@ -551,7 +578,24 @@ stream_status stream_prune_multi(const void *Q, const void *K, const stream_shap
     Problem pb;
     stream_status rc = make_problem(shape, kmin, nullptr, topk_max, &pb);
     if (rc != STREAM_OK) return rc;
-    return run_prune(Q, K, shape, pb, topk_list, n_k, idx, cnt, score, diag, workspace, workspace_bytes, hip_stream);
+    return run_prune(Q, K, shape, pb, topk_list, n_k, VariableK{0, 0, 0}, idx, cnt, score, diag, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+stream_status stream_prune_variable(const void *Q, const void *K, const stream_shape *shape,
+                                    int keep_num, int keep_den, int topk_min, int topk_max,
+                                    int *idx, int *cnt, float *score, const stream_prune_diag *diag,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!Q || !K || !shape || !idx || !cnt) return STREAM_EINVAL;
+    if (keep_num < 1 || keep_den < 1 || keep_num > keep_den) return STREAM_EINVAL;
+    if (topk_min < 1 || topk_max < topk_min) return STREAM_EINVAL;
+    // the rows with the smallest k are the deepest: they fix the number of levels
+    Problem pb;
+    stream_status rc = make_problem(shape, topk_min, nullptr, topk_max, &pb);
+    if (rc != STREAM_OK) return rc;
+    return run_prune(Q, K, shape, pb, nullptr, 0, VariableK{keep_num, keep_den, topk_min}, idx, cnt, score,
+                     diag, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"
