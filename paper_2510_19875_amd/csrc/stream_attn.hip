@@ -743,6 +743,9 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                     for (int i = 0; i < 16; ++i)
                         colsum += __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
             } else {
+                // (the empty asm keeps this a real branch: merged into the path above, the mask
+                // arithmetic would run on every sub-tile)
+                asm volatile("" ::: "memory");
 #pragma unroll
                 for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
