@@ -149,6 +149,14 @@ __device__ __forceinline__ void qk_mfma_bf16(floatx16 &c, const uint4 &a, const 
         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(av), "a"(bv));
 }
 
+// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1)).
+__device__ __forceinline__ float dot2_ones(unsigned pair, float acc)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair),
+                                           __builtin_bit_cast(bf16x2_t, 0x3f803f80u), acc, false);
+}
+
 // Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
 template <int I> struct IntC { static constexpr int value = I; };
 template <int I, int N, class F>
@@ -263,15 +271,11 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 
     if constexpr (PASS == 1) {
     floatx16 acc_o[NDB][NQ];
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int cq = 0; cq < NQ; ++cq)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc_o[db][cq][i] = 0.f;
     float m_run[NQ], l_run[NQ];
-#pragma unroll
-    for (int cq = 0; cq < NQ; ++cq) { m_run[cq] = -INFINITY; l_run[cq] = 0.f; }
+    // bf16: the PV product uses the probabilities rounded to bf16, so O is normalised by the sum
+    // of those same rounded values (lr_run): a row dominated by one key then gets that key's V
+    // exactly, whatever the rounding of its probability.  lse uses the unrounded sum (l_run).
+    float lr_run[NQ];
     const float c2 = p.scale_log2e;
     // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
     constexpr bool PIPE = NK == 1 && (BF16 || D == 64);
@@ -291,23 +295,12 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     }
 
     uint4 kreg[NK][FR];
-    if (n_tiles > 0) {
-        const unsigned off0 = tile_off(0);
-        // same order as the refills inside the loop: waits count loads in issue order
-#pragma unroll
-        for (int fr = 0; fr < FR; ++fr)
-#pragma unroll
-            for (int rb = 0; rb < NK; ++rb) {
-                kreg[rb][fr] = load_frag(krs, lane_off, off0, rb * FR + fr);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-    }
     // ------------------------------------------------------------------ pass 1: O and lse
     // Leading sub-tiles that need no mask run in a software pipeline that keeps the matrix
     // pipe busy while the vector ALUs do the softmax: iteration t issues, as one interleaved
     // stream,  O^T += V(t-1)^T P(t-1)^T  and  S(t+1)^T = K(t+1) Q^T  (MFMA groups), the loads
     // that refill each V / K fragment right after its last use, and between the MFMA groups
-    // the softmax of S(t) cut into small chunks.  S is double buffered by parity.
+    // the exponentials and conversions of S(t) cut into small chunks.  S is double buffered by parity.
     // Iteration 0 multiplies a zero P, the last one computes an S nobody reads: one loop body
     // serves all iterations.  Sub-tiles the mask cuts (diagonal block, sequence tail, edge of a
     // sliding window) go through the plain order, before and after.
@@ -320,7 +313,10 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         while (t_end > 0 && needs_mask(tile_ktok0(t_end - 1))) --t_end;
         if (p.mask == STREAM_MASK_SLIDING)
             while (tb < t_end && needs_mask(tile_ktok0(tb))) ++tb;
-        tb = __builtin_amdgcn_readfirstlane(tb);
+        // the pipelined loop keeps the softmax reference fixed (see below): the sub-tile before
+        // it always goes through the plain order, which sets the reference
+        tb = tb < 1 ? 1 : tb;
+        tb = __builtin_amdgcn_readfirstlane(tb < n_tiles ? tb : n_tiles);
         t_end = __builtin_amdgcn_readfirstlane(t_end > tb ? t_end : tb);
     }
     const int n_fast = t_end - tb;
@@ -401,6 +397,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                     sum += pr;
                 }
             l_run[cq] = l_run[cq] * alpha[cq] + sum;   // per-lane partial; halves are added at the end
+            if constexpr (BF16) lr_run[cq] *= alpha[cq];
         }
         // rescale the output accumulators only when some column's maximum moved
         if (__any(grew)) {
@@ -438,6 +435,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                                               acc_s[rb][cq][o + 2], acc_s[rb][cq][o + 3],
                                               acc_s[rb][cq][o + 4], acc_s[rb][cq][o + 5],
                                               acc_s[rb][cq][o + 6], acc_s[rb][cq][o + 7]);
+                        lr_run[cq] = dot2_ones(pf[cq].w, dot2_ones(pf[cq].z, dot2_ones(pf[cq].y, dot2_ones(pf[cq].x, lr_run[cq]))));
                     } else {
                         const int o = vf * 4;
                         pf[cq].x = f2u(acc_s[rb][cq][o + 0]);
@@ -453,15 +451,56 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         acc_o[db][cq] = mfma16<BF16>(vreg[rb][db * NVF + vf], pf[cq], acc_o[db][cq]);
             }
     };
-    for (int t = 0; t < tb; ++t) serial_tile(t);
+    // The pipelined loop does not follow the running maximum: it keeps the reference exponent
+    // the plain order has set so far (probabilities are then 2^(s - m_ref), any magnitude fp32
+    // and bf16 represent; the final normalisation makes the choice of reference immaterial).
+    // That saves the maximum, the reference update and the accumulator rescale of every
+    // pipelined sub-tile.  It cannot be wrong silently: a probability beyond 2^127 or a row sum
+    // that vanished shows as a non-finite or zero normaliser / output, and then the row is
+    // computed again entirely in the plain order (`safe`), which tracks the maximum.
+    float lse2[NQ];   // log2-domain log-sum-exp of each query column
+    float inv[NQ];
+    bool safe = !PIPE;
+    for (;;) {
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc_o[db][cq][i] = 0.f;
+#pragma unroll
+    for (int cq = 0; cq < NQ; ++cq) { m_run[cq] = -INFINITY; l_run[cq] = 0.f; lr_run[cq] = 0.f; }
+    if (n_tiles > 0) {
+        const unsigned off0 = tile_off(0);
+        // same order as the refills inside the loops: waits count loads in issue order
+#pragma unroll
+        for (int fr = 0; fr < FR; ++fr)
+#pragma unroll
+            for (int rb = 0; rb < NK; ++rb) {
+                kreg[rb][fr] = load_frag(krs, lane_off, off0, rb * FR + fr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
+    const int t_plain = safe ? n_tiles : tb;      // plain order up to here ...
+    const int t_resume = safe ? n_tiles : t_end;  // ... and again from here
+    for (int t = 0; t < t_plain; ++t) serial_tile(t);
 
     if constexpr (PIPE) {
-    if (n_fast > 0) {
+    if (!safe && n_fast > 0) {
         constexpr int GPV = NVF * NDB;          // MFMA groups of the PV product
         constexpr int G = GPV + FR;             // + groups of the QK product
-        constexpr int C = 7 * NQ;               // softmax chunks
-        // P has one buffer: every PV group must be issued before the first chunk that writes P
-        static_assert(GPV * C / G <= 2 * NQ + 4, "P would be overwritten while PV still reads it");
+        constexpr int C = 5 * NQ;               // softmax chunks: per column 4 x four exponentials, 1 convert
+        // P has one buffer: the first chunk that writes P (index 4) must not run before the
+        // MFMAs of the last PV group (chunks of group g follow the group's MFMAs)
+        static_assert((GPV - 1) * C / G <= 4, "P would be overwritten while PV still reads it");
+        float m_fix[NQ];                        // the reference exponent, fixed for the loop
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq) {
+            // a column that has seen no key yet takes 0: from here on that is its reference, also
+            // for the plain order that follows (sums and accumulators are relative to m_run)
+            m_fix[cq] = m_run[cq] == -INFINITY ? 0.f : m_run[cq];
+            m_run[cq] = m_fix[cq];
+        }
         floatx16 S[2][NQ];
         uint4 Pf[NVF][NQ];
         // V and K fragments are double buffered by parity as well: what iteration t loads is
@@ -518,37 +557,19 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
             constexpr int sb = decltype(SBc)::value, ob = sb ^ 1;
             const unsigned voff = tile_off(tb + (t + 1 < n_fast ? t + 1 : n_fast - 1));
             const unsigned knext = tile_off(clampk(t + 3));
-            float sv[NQ][16], mx[NQ], mxo[NQ], m_use[NQ], alpha[NQ], sum[NQ];
-            bool grew = false;
+            float sv[NQ][16], sum[NQ];
             auto chunk = [&](auto Cc) {
                 constexpr int c = decltype(Cc)::value;
-                // order: max(0..NQ-1), ref(0..NQ-1), then per column: 4 exp quarters + convert
-                if constexpr (c < NQ) {
-                    constexpr int cq = c;
-                    float m = -INFINITY;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) { sv[cq][i] = S[sb][cq][i]; m = fmaxf(m, sv[cq][i]); }
-                    mx[cq] = m;
-                    mxo[cq] = __shfl_xor(m, 32);
-                } else if constexpr (c < 2 * NQ) {
-                    constexpr int cq = c - NQ;
-                    const float m = fmaxf(mx[cq], mxo[cq]) * c2;
-                    const float m_new = m > m_run[cq] + 8.f ? m : m_run[cq];
-                    m_use[cq] = m_new == -INFINITY ? 0.f : m_new;
-                    grew = grew | ((m_new > m_run[cq]) & (m_run[cq] != -INFINITY));
-                    alpha[cq] = __builtin_amdgcn_exp2f(m_run[cq] - m_use[cq]);
-                    m_run[cq] = m_new;
-                    sum[cq] = 0.f;
-                } else {
-                    constexpr int cq = (c - 2 * NQ) / 5, part = (c - 2 * NQ) % 5;
+                {
+                    constexpr int cq = c / 5, part = c % 5;
+                    if constexpr (part == 0) sum[cq] = 0.f;
                     if constexpr (part < 4) {
 #pragma unroll
                         for (int i = part * 4; i < part * 4 + 4; ++i) {
-                            sv[cq][i] = __builtin_amdgcn_exp2f(fmaf(sv[cq][i], c2, -m_use[cq]));
+                            sv[cq][i] = __builtin_amdgcn_exp2f(fmaf(S[sb][cq][i], c2, -m_fix[cq]));
                             sum[cq] += sv[cq][i];
-                            // keeps the chunk where it is written: its results are first used
-                            // after the branch below, and the compiler would otherwise sink
-                            // the arithmetic there, out of the shadow of the MFMAs
+                            // keeps the chunk where it is written (in the shadow of this
+                            // group's MFMAs): its results are first used much later
                             asm volatile("" : "+v"(sv[cq][i]));
                         }
                         asm volatile("" : "+v"(sum[cq]));
@@ -567,9 +588,13 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                             }
                             asm volatile("" : "+v"(Pf[vf][cq].x), "+v"(Pf[vf][cq].y),
                                              "+v"(Pf[vf][cq].z), "+v"(Pf[vf][cq].w));
+                            if constexpr (BF16)
+                                lr_run[cq] = dot2_ones(Pf[vf][cq].w, dot2_ones(Pf[vf][cq].z,
+                                             dot2_ones(Pf[vf][cq].y, dot2_ones(Pf[vf][cq].x, lr_run[cq]))));
                         }
-                        l_run[cq] = l_run[cq] * alpha[cq] + sum[cq];
+                        l_run[cq] += sum[cq];
                         asm volatile("" : "+v"(l_run[cq]));
+                        if constexpr (BF16) asm volatile("" : "+v"(lr_run[cq]));
                     }
                 }
             };
@@ -607,23 +632,6 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 __builtin_amdgcn_sched_barrier(0);
             };
             static_for<0, G>(group);
-            if (__any(grew)) {
-#pragma unroll
-                for (int cq = 0; cq < NQ; ++cq)
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            float a = acc_o[db][cq][i], tmp;
-                            asm volatile("v_accvgpr_read_b32 %1, %0\n\t"
-                                         "v_mul_f32 %1, %1, %2\n\t"
-                                         "v_accvgpr_write_b32 %0, %1"
-                                         : "+a"(a), "=&v"(tmp)
-                                         : "v"(alpha[cq]));
-                            acc_o[db][cq][i] = a;
-                        }
-                asm volatile("s_nop 7");
-            }
         };
         auto drain = [&](auto SBc) {   // O^T += V(n_fast-1)^T P(n_fast-1)^T
             constexpr int sb = decltype(SBc)::value;
@@ -649,15 +657,31 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         }
     }
     }
-    for (int t = t_end; t < n_tiles; ++t) serial_tile(t);
+    for (int t = t_resume; t < n_tiles; ++t) serial_tile(t);
 
-    // ------------------------------------------------------------------ normalise, store O, lse
-    float lse2[NQ];   // log2-domain log-sum-exp of each query column
+    // normalisers; in the first attempt also the check that nothing overflowed or vanished
+    bool bad = false;
 #pragma unroll
     for (int cq = 0; cq < NQ; ++cq) {
         const float l_tot = l_run[cq] + __shfl_xor(l_run[cq], 32);
-        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        const float lr_tot = BF16 ? lr_run[cq] + __shfl_xor(lr_run[cq], 32) : l_tot;
+        inv[cq] = lr_tot > 0.f ? 1.f / lr_tot : 0.f;
         lse2[cq] = l_tot > 0.f ? m_run[cq] + log2f(l_tot) : -INFINITY;
+        if (!safe) {
+            bad = bad | !(l_tot > 1e-30f) | !(l_tot < 3e38f) | !(lr_tot > 1e-30f) | !(lr_tot < 3e38f);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) bad = bad | !(fabsf(acc_o[db][cq][i]) < 3e38f);
+        }
+    }
+    if (safe || !__any(bad)) break;
+    safe = true;
+    }
+
+    // ------------------------------------------------------------------ store O, lse
+#pragma unroll
+    for (int cq = 0; cq < NQ; ++cq) {
         const int tok = qtok0 + cq * 32 + col;
         if (tok < L) {
             char *dst = p.O + (long long)h * p.o_sh_b + (sd.tok0 + tok) * p.o_st_b;
@@ -668,8 +692,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
                     const int feat = db * 32 + i4 * 8 + gh * 4;
-                    const float a = acc_o[db][cq][i4 * 4 + 0] * inv, b = acc_o[db][cq][i4 * 4 + 1] * inv;
-                    const float c = acc_o[db][cq][i4 * 4 + 2] * inv, d = acc_o[db][cq][i4 * 4 + 3] * inv;
+                    const float a = acc_o[db][cq][i4 * 4 + 0] * inv[cq], b = acc_o[db][cq][i4 * 4 + 1] * inv[cq];
+                    const float c = acc_o[db][cq][i4 * 4 + 2] * inv[cq], d = acc_o[db][cq][i4 * 4 + 3] * inv[cq];
                     if constexpr (BF16) {
                         uint2 v;
                         v.x = pack_bf16x2(a, b);

@@ -93,3 +93,40 @@ def test_full_mask_equals_torch_causal_attention_on_gpu():
         Q.double()[None], K.double().repeat_interleave(2, 0)[None], V.double().repeat_interleave(2, 0)[None],
         is_causal=True)[0]
     assert (a["O"].double().cpu() - ref).abs().max() <= 2e-2
+
+
+@pytest.mark.parametrize("kind", ["overflow", "vanish"])
+def test_fixed_reference_falls_back_to_the_tracked_order(kind):
+    """The pipelined loop keeps the softmax reference of the sub-tile before it.  Scores that
+    then jump by hundreds of octaves (overflow), or a row whose first visible keys sit hundreds
+    of octaves above everything else seen later under a zero reference (vanish), must come out
+    right: the kernel notices the non-finite / vanished sums and recomputes the row while
+    tracking the maximum."""
+    dev = torch.device("cuda:0")
+    H, T, d, b = 2, 64 * 8 + 5, 128, 64
+    g = torch.Generator().manual_seed(5)
+    V = torch.randn((H, T, d), generator=g).to(torch.bfloat16)
+    Q = torch.full((H, T, d), 4.0).to(torch.bfloat16)
+    K = torch.full((H, T, d), 4.0).to(torch.bfloat16)
+    if kind == "overflow":
+        K[:, :32] = 0.0          # first sub-tile: score 0; every later key: 2048 * scale * log2(e) = 261 octaves
+    else:
+        K[:, 32:] = -4.0         # first sub-tile: +261 octaves; later keys: -261
+        K[:, :32] = 0.0
+        Q[:, :] = 4.0
+    mask, window = ("causal", 0) if kind == "overflow" else ("sliding", 100)
+    Qf, Kf, Vf = Q.float().numpy(), K.float().numpy(), V.float().numpy()
+    N = -(-T // b)
+    ref_p = so.prune(Qf, Kf, H, H, b, N, mask=mask, window=window)
+    scale = 1.0 / math.sqrt(d)
+    out = binding.stream_sparse_attn(Q.to(dev), K.to(dev), V.to(dev), H, H, b, torch.from_numpy(ref_p["idx"]).to(dev),
+                                     torch.from_numpy(ref_p["cnt"]).to(dev), scale, want_lse=True, want_mass=True,
+                                     mask=mask, window=window)
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Qf, Kf, Vf, H, H, b, ref_p["idx"], ref_p["cnt"], scale, mask=mask, window=window)
+    O = out["O"].float().cpu().numpy()
+    assert np.isfinite(O).all() and np.isfinite(out["lse"].cpu().numpy()).all()
+    assert np.abs(O - ref["O"]).max() <= TOL["bf16"]
+    np.testing.assert_allclose(out["lse"].cpu().numpy(), ref["lse"], rtol=1e-5, atol=1e-3)
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    assert (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max() <= 1e-3
