@@ -170,11 +170,13 @@ __device__ __forceinline__ void static_for(F &f)
 
 // NQ: 32-query groups per wavefront, NK: 32-key groups per key sub-tile, B: block size.
 //
-// Software pipeline of pass 1, per key sub-tile t (the K fragments of t are already in registers):
-//   issue the V fragment loads of t  ->  S^T = K Q^T, refilling each K fragment's registers with
-//   sub-tile t+1 as soon as its last MFMA is issued  ->  softmax update  ->  O^T += V^T P^T.
-// Loads return in issue order, so V(t) is complete before K(t+1) and each wait is a count of
-// younger loads still allowed in flight.
+// Pass 1 handles a key sub-tile in one of two ways.  Plain order (sub-tiles the mask cuts, the
+// sub-tile that sets the softmax reference, the fallback): the K fragments of t are already in
+// registers; issue the V fragment loads of t -> S^T = K Q^T, refilling each K fragment's
+// registers with sub-tile t+1 as soon as its last MFMA is issued -> running-maximum softmax
+// update -> O^T += V^T P^T.  Pipelined order (the unmasked middle of the list): see the comment
+// at the loop.  Loads return in issue order, so each wait is a count of younger loads still
+// allowed in flight.
 // PASS 1: outputs O, lse (and the base-2 normalisers for pass 2).  PASS 2: received mass, a
 // separate launch with two wavefronts per SIMD so that one's exponentials overlap the other's MFMAs.
 template <bool BF16, int D, int NQ, int NK, int B, int PASS, int OCC>
