@@ -1,7 +1,8 @@
 // stream_mask_diff: per (head, query block) row, the key blocks retained with k_success and
 // not retained with k_fail (Section 4.2.2, "Exploring Information Flow"), with the block scores
 // of the k_success run as weights.  Both lists are ascending, so membership is a binary search;
-// a lane holds one entry of each list and the search reads the other list across lanes.
+// a lane holds one entry of each list and the search reads the other list across lanes.  Lists of
+// at most 32 entries take half a wavefront each.
 #include "stream_common.h"
 
 #include <math.h>
@@ -25,62 +26,72 @@ struct DiffRow {
     float s;
 };
 
-__device__ __forceinline__ DiffRow diff_load(const DiffParams &p, long long row, int lane)
+// RPW rows per wavefront step: 1 (a row on 64 lanes) or, when both lists have at most 32 entries,
+// 2 (a row on each half of the wavefront).
+template <int RPW>
+__device__ __forceinline__ DiffRow diff_load(const DiffParams &p, long long row, int l)
 {
     DiffRow r;
     r.ca = 0; r.cb = 0; r.a = -1; r.b = -1; r.s = -INFINITY;
     if (row < p.rows) {
         r.ca = p.ca[row];
         r.cb = p.cb[row];
-        if (lane < p.ka) {
-            r.a = p.ia[row * p.ka + lane];
-            if (p.sa) r.s = p.sa[row * p.ka + lane];
+        if (l < p.ka) {
+            r.a = p.ia[row * p.ka + l];
+            if (p.sa) r.s = p.sa[row * p.ka + l];
         }
-        if (lane < p.kb) r.b = p.ib[row * p.kb + lane];
+        if (l < p.kb) r.b = p.ib[row * p.kb + l];
     }
     return r;
 }
 
+template <int RPW>
 __global__ void __launch_bounds__(256) diff_kernel(const DiffParams p)
 {
+    constexpr int LPR = 64 / RPW;                      // lanes per row
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const long long stride = (long long)gridDim.x * 4;
-    long long row = (long long)blockIdx.x * 4 + wave;
-    DiffRow nx = diff_load(p, row, lane);
-    for (int i = 0; i < kDiffRowsPerWave && row < p.rows; ++i, row += stride) {
+    const int sub = lane / LPR, l = lane % LPR;        // which row of the step, which entry
+    const long long stride = (long long)gridDim.x * 4 * RPW;
+    long long row = ((long long)blockIdx.x * 4 + wave) * RPW + sub;
+    DiffRow nx = diff_load<RPW>(p, row, l);
+    for (int i = 0; i < kDiffRowsPerWave; ++i, row += stride) {
+        if (row - sub >= p.rows) break;                // wave-uniform: the step's first row
         const DiffRow cur = nx;
-        nx = diff_load(p, row + stride, lane);      // next row's loads fly while this one is searched
-        int ca = __builtin_amdgcn_readfirstlane(cur.ca), cb = __builtin_amdgcn_readfirstlane(cur.cb);
+        nx = diff_load<RPW>(p, row + stride, l);       // next rows' loads fly while these are searched
+        int ca = cur.ca, cb = cur.cb;
         ca = ca < 0 ? 0 : (ca > p.ka ? p.ka : ca);
         cb = cb < 0 ? 0 : (cb > p.kb ? p.kb : cb);
         // lower bound of this lane's a in b[0 .. cb): first position whose entry is >= a
         int lo = 0, hi = cb;
 #pragma unroll
-        for (int step = 0; step < 7; ++step) {       // 2^7 > 64 entries
+        for (int step = 0; step < (RPW == 1 ? 7 : 6); ++step) {   // 2^7 > 64, 2^6 > 32 entries
             const int mid = (lo + hi) >> 1;
-            const int bm = __shfl(cur.b, mid & 63);
+            const int bm = __shfl(cur.b, sub * LPR + (mid & (LPR - 1)));
             const bool go = lo < hi && bm < cur.a;
             const bool stay = lo < hi && !(bm < cur.a);
             lo = go ? mid + 1 : lo;
             hi = stay ? mid : hi;
         }
-        const int bl = __shfl(cur.b, lo & 63);
+        const int bl = __shfl(cur.b, sub * LPR + (lo & (LPR - 1)));
         const bool in_b = lo < cb && bl == cur.a;
-        const bool keep = lane < ca && !in_b;
-        const unsigned long long kb = __ballot(keep);
-        const int pos = __popcll(kb & ((1ull << lane) - 1ull));
+        const bool keep = row < p.rows && l < ca && !in_b;
+        const unsigned long long kb_all = __ballot(keep);
+        const unsigned long long kb = RPW == 1 ? kb_all : ((kb_all >> (sub * LPR)) & 0xffffffffull);
+        const int pos = __popcll(kb & ((1ull << l) - 1ull));
         const int n = __popcll(kb);
-        const long long o = row * p.ka;
-        if (keep) {
-            p.io[o + pos] = cur.a;
-            if (p.wo) p.wo[o + pos] = cur.s;
+        if (row < p.rows) {
+            const long long o = row * p.ka;
+            if (keep) {
+                p.io[o + pos] = cur.a;
+                if (p.wo) p.wo[o + pos] = cur.s;
+            }
+            if (l >= n && l < p.ka) {
+                p.io[o + l] = -1;
+                if (p.wo) p.wo[o + l] = -INFINITY;
+            }
+            if (l == 0) p.co[row] = n;
         }
-        if (lane >= n && lane < p.ka) {
-            p.io[o + lane] = -1;
-            if (p.wo) p.wo[o + lane] = -INFINITY;
-        }
-        if (lane == 0) p.co[row] = n;
     }
 }
 
@@ -94,7 +105,9 @@ extern "C" stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, co
 {
     if (rows < 0 || kmax_a < 1 || kmax_b < 1) return STREAM_EINVAL;
     if (kmax_a > kMaxTopk || kmax_b > kMaxTopk) return STREAM_EUNSUPPORTED;
-    const long long grid = (rows + 4 * kDiffRowsPerWave - 1) / (4 * kDiffRowsPerWave);
+    const int rpw = (kmax_a <= 32 && kmax_b <= 32) ? 2 : 1;
+    const long long per_wg = 4LL * kDiffRowsPerWave * rpw;
+    const long long grid = (rows + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
     if (rows == 0) return STREAM_OK;                 // empty tensors may have no address
     if (!idx_a || !cnt_a || !idx_b || !cnt_b || !idx_out || !cnt_out) return STREAM_EINVAL;
@@ -105,6 +118,6 @@ extern "C" stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, co
     p.ia = idx_a; p.ca = cnt_a; p.sa = score_a; p.ib = idx_b; p.cb = cnt_b;
     p.io = idx_out; p.co = cnt_out; p.wo = weight_out;
     p.rows = rows; p.ka = kmax_a; p.kb = kmax_b;
-    hipLaunchKernelGGL(diff_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
+    hipLaunchKernelGGL(rpw == 2 ? diff_kernel<2> : diff_kernel<1>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
     return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
 }
