@@ -1,11 +1,15 @@
 // stream_prune: Algorithm 2 ("Stream", Appendix C) on gfx950.
 //
-// One kernel launch per refinement level.  A wavefront owns one (query head, query block) row
-// (four wavefronts share a row when block = 128): it holds the row's Q tile in registers as
-// MFMA operand fragments, gathers the packed K tiles of the branches that need a new score,
-// reduces each 32x32 accumulator set to the masked maximum (score line of Alg. 2 / Eq. (4)),
-// ranks the 2k branch scores across its lanes, and writes the surviving nodes back in place in
-// positional order.  The node lists [heads, NB, k] are the only state: O(T) memory.
+// A wavefront owns one (query head, query block) row (four wavefronts share a row when
+// block = 128) and runs the row's refinement levels back to back, all of them in one launch by
+// default: it holds the row's Q tile in registers as MFMA operand fragments and, per level,
+// gathers the packed K tiles of the branches that need a new score, reduces each 32x32
+// accumulator set to the masked maximum (score line of Alg. 2 / Eq. (4)), selects the k best of
+// the 2k branch scores across its lanes and hands the surviving nodes, in positional order, to
+// the next level through LDS (through the node lists [heads, NB, k] in the workspace when the
+// caller splits a row's levels over several launches): O(T) memory either way.
+// Variants of the same kernel: a sweep over several k with a per-row cache of block scores
+// (stream_prune_multi) and a sparsity constant per row (stream_prune_variable).
 #include "stream_select.h"
 
 #include <math.h>
@@ -106,7 +110,7 @@ __device__ __forceinline__ floatx16 mfma_frag(const uint4 &a, const uint4 &b, fl
 
 // Template parameters: element type, head dim, 32-row groups of Q per wavefront (MB), 32-key
 // groups of K per wavefront (NG), wavefronts per row (WPR: 1, or 4 = 2 query halves x 2 key
-// halves for block 128), occupancy hint.
+// halves for block 128), occupancy hint, k sweep with the block-score cache (MULTI).
 template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI>
 __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
