@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per level-kernel launch (mean of the 6 levels) at the headline workload, from the
+# HBM-side bytes per level-kernel launch at the headline workload, from the
 # rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/cfg3_pmc_counters.txt, per
 # launch of the level kernel in its default form (all levels of a row in one launch):
 # FETCH_SIZE 4.576e6 x 2.0 (the factor a plain 268 MB copy shows for this counter) + WRITE_SIZE
@@ -167,7 +167,7 @@ def main():
     tok_heads = float(T) * H
     value = tok_heads / (ms_per_step * 1e-3)
 
-    Q_BYTES = float(H) * T * d * layers[0][0].element_size()      # Q tile of every row, once per level
+    Q_BYTES = float(H) * T * d * layers[0][0].element_size()      # Q tile of every row, once per launch
     K_BYTES = float(Hkv) * T * d * layers[0][0].element_size()    # distinct K tiles: 1/64 .. 1/2 of K by level
     retained = float(out_p["cnt"].sum().item())
     attn_flop = retained * 6.0 * b * b * d                        # QK^T + PV + the QK^T of the mass pass
