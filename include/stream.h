@@ -257,6 +257,40 @@ stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *
                                const int *idx_b, const int *cnt_b, int kmax_b, long long rows,
                                int *idx_out, int *cnt_out, float *weight_out, void *hip_stream);
 
+/*
+ * Receiver-head statistics (Section 4.1, "Thought Anchors"): the section looks for heads whose
+ * attention concentrates on a few parts of the context by averaging the head's DENSE attention
+ * probabilities over b_q x b_k spans (the "block mean" pattern of its attention-patterns figure)
+ * and measuring the maximum vertical kurtosis of these block means.  The dense pattern is never
+ * stored: O(T^2 d) time, O(T) memory besides the optional block_mean output.
+ *
+ *   P = softmax over the visible keys of scale * Q K^T (mask C of `shape`), per head/sequence
+ *   M[i, j] = sum of P over (queries of block i) x (keys of block j) / (real queries of i *
+ *             real keys of j), where key block j is valid for query block i, else 0
+ *   column j = the values M[i, j] over the query blocks i that j is valid for ("vertical"):
+ *             col_mean[j] their mean, col_kurt[j] their excess kurtosis m4 / m2^2 - 3 (biased
+ *             central moments; 0 with fewer than 4 values or no spread)
+ *
+ *   scale       as stream_sparse_attn (> 0, finite)
+ *   block_mean  float [heads, NB, NB] (query block, key block; global block ids) or NULL;
+ *               zero outside the valid blocks and across sequences of a packed batch
+ *   col_mean    float [heads, NB]
+ *   col_kurt    float [heads, NB]
+ *   head_stats  float [heads, batch, 2]: [0] the maximum of col_kurt over the sequence's columns
+ *               with at least 4 values (0 if there is none), [1] the excess kurtosis of
+ *               col_mean over the sequence's columns (0 for fewer than 4 columns)
+ *   workspace   stream_receiver_stats_workspace_bytes(shape) bytes (packed Q and K, one float
+ *               per padded token and head), 256-byte aligned
+ * The moments are accumulated in fp64 from the fp32 block means.  Errors: as stream_prune;
+ * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and block 128.
+ */
+size_t stream_receiver_stats_workspace_bytes(const stream_shape *shape);
+
+stream_status stream_receiver_stats(const void *Q, const void *K, const stream_shape *shape, float scale,
+                                    float *block_mean, float *col_mean, float *col_kurt,
+                                    float *head_stats, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream);
+
 const char *stream_status_str(stream_status s);
 
 #ifdef __cplusplus

@@ -21,7 +21,8 @@ STREAM_F32, STREAM_BF16 = 0, 1
 EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
            "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
            "stream_prune_multi_workspace_bytes", "stream_prune_multi", "stream_prune_variable",
-           "stream_select_update", "stream_mask_diff", "stream_status_str"]
+           "stream_select_update", "stream_mask_diff", "stream_receiver_stats_workspace_bytes",
+           "stream_receiver_stats", "stream_status_str"]
 
 
 class StreamShape(ctypes.Structure):
@@ -88,6 +89,10 @@ def load():
     lib.stream_mask_diff.restype = ctypes.c_int
     lib.stream_mask_diff.argtypes = [vp, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, ctypes.c_longlong,
                                      vp, vp, vp, vp]
+    lib.stream_receiver_stats_workspace_bytes.restype = ctypes.c_size_t
+    lib.stream_receiver_stats_workspace_bytes.argtypes = [sp]
+    lib.stream_receiver_stats.restype = ctypes.c_int
+    lib.stream_receiver_stats.argtypes = [vp, vp, sp, ctypes.c_float, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.stream_status_str.restype = ctypes.c_char_p
     lib.stream_status_str.argtypes = [ctypes.c_int]
     _lib = lib
@@ -376,3 +381,41 @@ def stream_mask_diff(idx_a, cnt_a, score_a, idx_b, cnt_b, want_weight: bool = Tr
     if rc != STREAM_OK:
         raise StreamError(rc, "stream_mask_diff")
     return {"idx": io, "cnt": co, "weight": wo}
+
+
+def stream_receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: float, cu_seqlens=None,
+                          want_block_mean: bool = False, workspace=None, out=None, mask="causal",
+                          window: int = 0):
+    """Block means of the dense attention pattern and their vertical kurtosis (Section 4.1).
+
+    Returns dict(block_mean [H, NB, NB] or None, col_mean [H, NB], col_kurt [H, NB],
+    head [H, batch, 2] = (max column kurtosis, kurtosis of the column means))."""
+    lib = load()
+    if not (Q.is_cuda and K.is_cuda):
+        raise ValueError("Q, K must be device tensors (the library has no CPU path)")
+    H, T, d = Q.shape
+    dev = Q.device
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
+                             mask=mask, window=window)
+    NB = lib.stream_num_blocks(ctypes.byref(shape))
+    if NB < 0:
+        raise StreamError(1, "stream_num_blocks")
+    batch = shape.batch
+    if out is None:
+        bm = torch.empty((H, NB, NB), dtype=torch.float32, device=dev) if want_block_mean else None
+        cm = torch.empty((H, NB), dtype=torch.float32, device=dev)
+        ck = torch.empty((H, NB), dtype=torch.float32, device=dev)
+        hs = torch.empty((H, batch, 2), dtype=torch.float32, device=dev)
+    else:
+        bm, cm, ck, hs = out.get("block_mean"), out["col_mean"], out["col_kurt"], out["head"]
+    need = lib.stream_receiver_stats_workspace_bytes(ctypes.byref(shape))
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=dev)
+    rc = lib.stream_receiver_stats(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape), float(scale),
+                                   bm.data_ptr() if bm is not None else None, cm.data_ptr(),
+                                   ck.data_ptr(), hs.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel(), _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_receiver_stats")
+    return {"block_mean": bm, "col_mean": cm, "col_kurt": ck, "head": hs, "workspace": workspace,
+            "_keep": keep}

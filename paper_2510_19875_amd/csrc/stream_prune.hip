@@ -10,14 +10,12 @@
 // caller splits a row's levels over several launches): O(T) memory either way.
 // Variants of the same kernel: a sweep over several k with a per-row cache of block scores
 // (stream_prune_multi) and a sparsity constant per row (stream_prune_variable).
+#include "stream_mfma.h"
 #include "stream_select.h"
 
 #include <math.h>
 
 namespace stream {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kMaxSweep = 32;        // values of k in one stream_prune_multi call
 constexpr int kScoreCache = 1024;    // entries of a row's block-score cache (k sweep)
@@ -59,53 +57,6 @@ __host__ __device__ __forceinline__ int variable_k(int valid, int num, int den, 
     long long k = ((long long)valid * num + den - 1) / den;
     k = k < kmin ? kmin : k;
     return (int)(k > kmax ? kmax : k);
-}
-
-__device__ __forceinline__ void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
-                                                                 0xf, 0xf, false));
-}
-
-// Maximum over the 64 lanes, returned in every lane.
-__device__ __forceinline__ float wave_max(float v)
-{
-    v = fmaxf(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
-    v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror: every lane of a 16-lane row holds the row max
-    const int iv = __builtin_bit_cast(int, v);
-    const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
-    const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
-    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
-    const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
-    return fmaxf(fmaxf(a, b), fmaxf(c, d));
-}
-
-// One operand fragment (16 bytes per lane) times another, accumulated into a 32x32 tile.
-template <bool BF16>
-__device__ __forceinline__ floatx16 mfma_frag(const uint4 &a, const uint4 &b, floatx16 c)
-{
-    if constexpr (BF16) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    } else {
-        // fp32: the fragment's 8 contraction indices are split 4 + 4 between the lane halves;
-        // step j multiplies component j of both operands (32x32x2 MFMA, 2 indices per step).
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.y), __builtin_bit_cast(float, b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.z), __builtin_bit_cast(float, b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a.w), __builtin_bit_cast(float, b.w), c, 0, 0, 0);
-        return c;
-    }
 }
 
 // Template parameters: element type, head dim, 32-row groups of Q per wavefront (MB), 32-key

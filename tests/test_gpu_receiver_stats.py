@@ -1,0 +1,144 @@
+"""stream_receiver_stats against oracle/receiver_stats.py through the C ABI.
+
+Tolerances.  A block mean is a sum of exp2(x - lse) terms whose arguments carry an absolute
+error of a few fp32 ulps of |x| <= ~64 (log2 units): relative error ~1e-5 whatever the size of
+the entry, so block means and column means are held to 2e-4 relative.  The kurtosis of a column
+amplifies the relative error of its entries by about mean/std of the column (and by the value
+itself), so against the oracle it is held to 5e-3 * (1 + |kurt|) * max(1, mean/std); the
+library's own arithmetic (fp64 one-pass moments of the fp32 block means) is checked tightly by
+recomputing the statistics in fp64 from the block means the library returned."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import receiver_stats as rs
+from paper_2510_19875_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+RTOL_M = 2e-4
+
+
+def run(Q, K, H, Hkv, b, scale, cu=None, mask="causal", window=0, want_block_mean=True):
+    r = binding.stream_receiver_stats(Q.to(DEV), K.to(DEV), H, Hkv, b, scale, cu_seqlens=cu,
+                                      want_block_mean=want_block_mean, mask=mask, window=window)
+    torch.cuda.synchronize()
+    return {k: (v.cpu().numpy() if isinstance(v, torch.Tensor) and k != "workspace" else v)
+            for k, v in r.items()}
+
+
+def seq_blocks(cu, T, b):
+    cu = [0, T] if cu is None else list(cu)
+    nblk = [-(-(cu[s + 1] - cu[s]) // b) for s in range(len(cu) - 1)]
+    blk0 = np.concatenate([[0], np.cumsum(nblk)]).astype(int)
+    return cu, nblk, blk0
+
+
+def check(w, mask="causal", window=0, scale=None):
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    H, Hkv, b, d = w.heads, w.kv_heads, w.block, w.head_dim
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    cu = list(w.cu_seqlens) if len(w.seq_lens) > 1 else None
+    got = run(Q, K, H, Hkv, b, scale, cu, mask, window)
+    Qn, Kn = Q.to(torch.float64).numpy(), K.to(torch.float64).numpy()
+    want = rs.receiver_stats(Qn, Kn, H, Hkv, b, scale, cu_seqlens=cu, mask=mask, window=window)
+
+    bm = got["block_mean"].astype(np.float64)
+    np.testing.assert_allclose(bm, want["block_mean"], rtol=RTOL_M, atol=1e-30)
+    assert ((want["block_mean"] == 0) <= (bm == 0)).all()          # nothing where the mask hides
+    np.testing.assert_allclose(got["col_mean"], want["col_mean"], rtol=RTOL_M, atol=1e-30)
+
+    # statistics recomputed in fp64 from the library's own block means
+    cu_l, nblk, blk0 = seq_blocks(cu, w.T, b)
+    worst = 0.0
+    for h in range(H):
+        for s in range(len(nblk)):
+            lo, hi = blk0[s], blk0[s + 1]
+            L = cu_l[s + 1] - cu_l[s]
+            _, Cblk = rs.block_means(np.zeros((L, L)), b, mask, window)
+            mean, kurt, n = rs.column_stats(bm[h, lo:hi, lo:hi], Cblk)
+            np.testing.assert_allclose(got["col_mean"][h, lo:hi], mean, rtol=1e-6, atol=1e-37)
+            np.testing.assert_allclose(got["col_kurt"][h, lo:hi], kurt, rtol=1e-4, atol=1e-4)
+            mx, vk = rs.head_stats(got["col_mean"][h, lo:hi].astype(np.float64), got["col_kurt"][h, lo:hi].astype(np.float64), n)
+            np.testing.assert_allclose(got["head"][h, s], [mx, vk], rtol=1e-5, atol=1e-5)
+            # against the oracle, conditioning-aware
+            for j in range(hi - lo):
+                vals = want["block_mean"][h, lo:hi, lo + j][Cblk[:, j]]
+                if vals.size < 4:
+                    assert got["col_kurt"][h, lo + j] == 0.0
+                    continue
+                cond = max(1.0, abs(vals.mean()) / max(vals.std(), 1e-300))
+                tol = 5e-3 * (1 + abs(want["col_kurt"][h, lo + j])) * cond
+                err = abs(got["col_kurt"][h, lo + j] - want["col_kurt"][h, lo + j])
+                worst = max(worst, err / tol)
+                assert err <= tol, (h, s, j, got["col_kurt"][h, lo + j], want["col_kurt"][h, lo + j], cond)
+            wm, wv = want["head"][h, s]
+            assert abs(got["head"][h, s, 0] - wm) <= 5e-3 * (1 + abs(wm)) * 10
+            assert abs(got["head"][h, s, 1] - wv) <= 5e-3 * (1 + abs(wv)) * 10
+    print(f"[stats] {w.name} b={b} {mask}/{window}: worst kurt err/tol {worst:.3f}", flush=True)
+    return got, want
+
+
+CASES = [
+    # (dtype cfg, seq_lens, heads, kv_heads, block, mask, window)
+    (2, (1000,), 4, 2, 64, "causal", 0),            # several tiles + ragged tail, GQA
+    (2, (1000,), 2, 2, 32, "causal", 0),
+    (2, (1100,), 2, 1, 128, "causal", 0),           # ragged tail shorter than half a block
+    (2, (1000,), 2, 1, 64, "sliding", 200),
+    (2, (1000,), 2, 1, 128, "sliding", 77),
+    (2, (1000,), 2, 1, 32, "sliding", 1),
+    (2, (700,), 2, 1, 64, "full", 0),
+    (2, (600,), 2, 1, 128, "full", 0),
+    (1, (777,), 2, 2, 64, "causal", 0),             # fp32, d = 64
+    (1, (500,), 2, 2, 128, "sliding", 100),
+    (1, (500,), 2, 2, 32, "full", 0),
+    (5, (300, 64, 1, 517), 7, 1, 64, "causal", 0),  # packed ragged batch, g = 7, a 1-token sequence
+    (5, (300, 129), 7, 1, 128, "sliding", 130),
+]
+
+
+@pytest.mark.parametrize("cfg,lens,H,Hkv,b,mask,window", CASES)
+def test_against_oracle(cfg, lens, H, Hkv, b, mask, window):
+    kw = {"needles_per_kv_head": 2} if cfg != 5 else {}
+    w = wl.scaled(wl.config(cfg), lens, topk=4, heads=H, kv_heads=Hkv, block=b, **kw)
+    check(w, mask, window)
+
+
+def test_without_block_mean_output_and_repeat_call():
+    w = wl.scaled(wl.config(2), (900,), topk=4, heads=4, kv_heads=2, needles_per_kv_head=2)
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    a = run(Q, K, 4, 2, 64, 0.1, want_block_mean=True)
+    b = run(Q, K, 4, 2, 64, 0.1, want_block_mean=False)
+    assert b["block_mean"] is None
+    for k in ("col_mean", "col_kurt", "head"):
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_planted_receiver_head_is_ranked_first():
+    """Head 1 gets a key block that all later queries attend to: it has the largest statistics."""
+    g = torch.Generator().manual_seed(5)
+    H, T, d, b = 4, 2048, 128, 64
+    Q = torch.randn((H, T, d), generator=g)
+    K = torch.randn((H, T, d), generator=g)
+    u = torch.randn(d, generator=g); u /= u.norm()
+    Q[1] += 3.0 * u
+    K[1, 5 * b:6 * b] = 8.0 * u
+    Q, K = Q.to(torch.bfloat16), K.to(torch.bfloat16)
+    got = run(Q, K, H, H, b, 1.0 / math.sqrt(d), want_block_mean=False)
+    assert int(np.argmax(got["col_mean"][1][1:])) + 1 == 5
+    assert int(np.argmax(got["head"][:, 0, 1])) == 1
+
+
+def test_bad_arguments():
+    w = wl.scaled(wl.config(2), (256,), topk=4, heads=2, kv_heads=1, needles_per_kv_head=1)
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    Qd, Kd = Q.to(DEV), K.to(DEV)
+    with pytest.raises(binding.StreamError):
+        binding.stream_receiver_stats(Qd, Kd, 2, 1, 64, 0.0)
+    with pytest.raises(binding.StreamError):
+        binding.stream_receiver_stats(Qd, Kd, 2, 1, 64, 0.1, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    with pytest.raises(binding.StreamError) as e:
+        binding.stream_receiver_stats(Qd.float(), Kd.float(), 2, 1, 128, 0.1)     # fp32, d = 128, b = 128
+    assert e.value.code == 2
