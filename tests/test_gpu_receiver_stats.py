@@ -142,3 +142,43 @@ def test_bad_arguments():
     with pytest.raises(binding.StreamError) as e:
         binding.stream_receiver_stats(Qd.float(), Kd.float(), 2, 1, 128, 0.1)     # fp32, d = 128, b = 128
     assert e.value.code == 2
+
+
+def test_config3_full_size_sampled():
+    """T = 131072, 32/8 heads, d = 128, bf16, b = 64: sampled block means against the oracle
+    (each from the rows of its query block alone), and properties over whole heads: every
+    query's probabilities sum to 1 (so sum_j M[i,j] * n_k(j) = 1 for every query block), and
+    the column statistics are those of the returned block means."""
+    w = wl.config(3)
+    dev = torch.device(DEV)
+    print(f"[stats-full] {w.name}: generating inputs", flush=True)
+    Q, K, _, _ = wl.make_inputs(w, device=dev, with_v=False)
+    H, Hkv, b, d, T = w.heads, w.kv_heads, w.block, w.head_dim, w.T
+    g = H // Hkv
+    scale = 1.0 / math.sqrt(d)
+    print("[stats-full] stream_receiver_stats", flush=True)
+    r = binding.stream_receiver_stats(Q, K, H, Hkv, b, scale, want_block_mean=True)
+    torch.cuda.synchronize()
+    N = T // b
+    bm = r["block_mean"]
+    assert tuple(bm.shape) == (H, N, N)
+    rowsum = (bm.double().sum(dim=2) * b).cpu().numpy()
+    np.testing.assert_allclose(rowsum, 1.0, rtol=2e-4)
+    assert bool((torch.triu(bm[0], 1) == 0).all()) and bool((bm >= 0).all())
+    rng = np.random.default_rng(3)
+    for h in (0, 13, 31):
+        print(f"[stats-full] head {h}", flush=True)
+        Mh = bm[h].cpu().numpy().astype(np.float64)
+        Cblk = np.tril(np.ones((N, N), bool))
+        mean, kurt, n = rs.column_stats(Mh, Cblk)
+        np.testing.assert_allclose(r["col_mean"][h].cpu().numpy(), mean, rtol=1e-6)
+        np.testing.assert_allclose(r["col_kurt"][h].cpu().numpy(), kurt, rtol=1e-4, atol=1e-4)
+        mx, vk = rs.head_stats(mean, kurt, n)
+        np.testing.assert_allclose(r["head"][h, 0].cpu().numpy(), [mx, vk], rtol=1e-4, atol=1e-4)
+        Qh = Q[h].cpu().to(torch.float64).numpy()
+        Kh = K[h // g].cpu().to(torch.float64).numpy()
+        pairs = [(0, 0), (N - 1, 0), (N - 1, N - 1), (N - 1, N - 2), (N // 2, 1)]
+        pairs += [(int(i), int(rng.integers(0, i + 1))) for i in rng.integers(1, N, size=8)]
+        for (i, j) in pairs:
+            want = rs.block_mean_entry(Qh, Kh, b, scale, i, j)
+            assert Mh[i, j] == pytest.approx(want, rel=RTOL_M, abs=1e-30), (h, i, j)
