@@ -232,6 +232,7 @@ def main():
         result["k_sweep"] = k_sweep(w, layers[0])
         result["mask_rules"] = mask_rules(w, layers[0], scale)
         result["variable_k"] = variable_k(w, layers[0])
+        result["receiver_stats"] = receiver_stats(w, layers[0], scale)
     if args.dense_reference and w.batch == 1:
         result["dense_reference"] = dense_reference(w, layers[0])
     if not args.no_cpu_baseline:
@@ -375,6 +376,38 @@ def variable_k(w, layer, reps=3):
     torch.cuda.synchronize()
     return {"rule": f"k(row) = clamp(ceil(valid/64), 1, {kmax})", "prune_ms": e0.elapsed_time(e1) / reps,
             "block_scores": int(st["tiles"].item()), "retained_blocks": int(st["out"]["cnt"].sum().item())}
+
+
+def receiver_stats(w, layer, scale, reps=2):
+    """stream_receiver_stats on the same Q, K: two dense passes of b x b x d tile products over the
+    causal half of the pattern (row log-sum-exp, then block means and column moments)."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, _ = layer
+    st = {}
+
+    def run():
+        r = binding.stream_receiver_stats(Q, K, w.heads, w.kv_heads, w.block, scale,
+                                          workspace=st.get("ws"), out=st.get("out"))
+        st["ws"] = r["workspace"]
+        st["out"] = {k: r[k] for k in ("col_mean", "col_kurt", "head")}
+
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    N = w.blocks_per_seq[0]
+    flop = 2.0 * w.heads * (N * (N + 1) / 2) * 2.0 * w.block * w.block * w.head_dim
+    return {"ms": ms, "tflops": flop / (ms * 1e-3) / 1e12, "bound": "mfma",
+            "frac_of_mfma_peak": flop / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+            "max_column_kurtosis_head0": float(st["out"]["head"][0, 0, 0].item())}
 
 
 def mask_diff_standalone(kmax, rows=1 << 21, launches=12):
