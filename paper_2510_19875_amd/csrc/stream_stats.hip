@@ -8,8 +8,8 @@
 //            log-sum-exp of every row of the pattern;
 //   columns  a wavefront owns one key block, keeps its K fragments in registers, streams the
 //            query tiles that can see it, turns scores into probabilities with the rows'
-//            log-sum-exp, reduces each b x b span to its mean and feeds the means, in fp64, to a
-//            one-pass update of the column's central moments (Pebay's formulas for M2, M3, M4).
+//            log-sum-exp, reduces each b x b span to its mean and adds the means' powers, in fp64
+//            and shifted by the column's first value, to the column's four power sums.
 // A third, tiny kernel reduces the column statistics to the two numbers per (head, sequence).
 #include "stream_mfma.h"
 
@@ -133,13 +133,15 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
         // 8*(i/4) + 4*(lane/32) + (i%4)
 #pragma unroll
         for (int qs = 0; qs < NS; ++qs) {
+            // m[] is kept on the raw products (c > 0, so the maximum commutes with the scaling):
+            // per element one max, one fused multiply-add, one exp2, one add
             float x[2][16];
             float tmax = -INFINITY;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    float v = acc[kb][qs][i] * p.c;
+                    float v = acc[kb][qs][i];
                     if (cut) {
                         const int tq = tq0 + qs * 32 + (lane & 31);
                         const int tk = tk0 + kb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
@@ -151,12 +153,13 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
                 }
             const float m_new = fmaxf(m[qs], tmax);
             const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float mc = m_ref * p.c;
             float sum = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(x[kb][i] - m_ref);
-            l[qs] = l[qs] * __builtin_amdgcn_exp2f(m[qs] - m_ref) + sum;
+                for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(x[kb][i], p.c, -mc));
+            l[qs] = l[qs] * __builtin_amdgcn_exp2f((m[qs] - m_ref) * p.c) + sum;
             m[qs] = m_new;
         }
     }
@@ -166,9 +169,10 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
         const float m2 = __shfl_xor(m[qs], 32), l2 = __shfl_xor(l[qs], 32);
         const float mm = fmaxf(m[qs], m2);
         const float m_ref = mm == -INFINITY ? 0.f : mm;
-        const float lt = l[qs] * __builtin_amdgcn_exp2f(m[qs] - m_ref) + l2 * __builtin_amdgcn_exp2f(m2 - m_ref);
+        const float lt = l[qs] * __builtin_amdgcn_exp2f((m[qs] - m_ref) * p.c) +
+                         l2 * __builtin_amdgcn_exp2f((m2 - m_ref) * p.c);
         const int tq = tq0 + qs * 32 + (lane & 31);
-        if (lane < 32) out[qs * 32 + lane] = tq < L ? m_ref + log2f(lt) : 0.f;
+        if (lane < 32) out[qs * 32 + lane] = tq < L ? m_ref * p.c + log2f(lt) : 0.f;
     }
 }
 
@@ -217,8 +221,10 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
     const int nk = L - tk0 < B ? L - tk0 : B;       // real keys of the block
     float *bm = p.block_mean ? p.block_mean + ((long long)h * p.NB + sd.blk0) * p.NB + gbj : nullptr;
 
-    // running moments of the column (one-pass updates, fp64)
-    double cn = 0.0, mean = 0.0, M2 = 0.0, M3 = 0.0, M4 = 0.0;
+    // power sums of the column's means, in fp64, shifted by the column's first value (the
+    // diagonal block) so that the central moments formed from them at the end lose nothing that
+    // matters: four short independent chains per span instead of a long dependent update
+    double x0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0, s4 = 0.0;
 
     uint4 qf[NS][FR];
     float lq[NS];
@@ -291,22 +297,22 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
             psum = 0.f;
             if (bm && lane == 0) bm[(long long)i_blk * p.NB] = mval;
             const double x = (double)mval;
-            const double n1 = cn;
-            cn += 1.0;
-            const double delta = x - mean;
-            const double dn = delta / cn;
-            const double dn2 = dn * dn;
-            const double t1 = delta * dn * n1;
-            mean += dn;
-            M4 += t1 * dn2 * (cn * cn - 3.0 * cn + 3.0) + 6.0 * dn2 * M2 - 4.0 * dn * M3;
-            M3 += t1 * dn * (cn - 2.0) - 3.0 * dn * M2;
-            M2 += t1;
+            if (t + 1 == TPB) x0 = x;
+            const double y = x - x0, y2 = y * y;
+            s1 += y;
+            s2 += y2;
+            s3 = fma(y2, y, s3);
+            s4 = fma(y2, y2, s4);
         }
     }
     if (lane == 0) {
         const long long o = (long long)h * p.NB + gbj;
-        p.col_mean[o] = (float)mean;
-        p.col_kurt[o] = (cn >= 4.0 && M2 > 0.0) ? (float)(cn * M4 / (M2 * M2) - 3.0) : 0.f;
+        const double cn = (double)(imax - imin + 1);
+        const double mu = s1 / cn;                                  // mean of the shifted values
+        const double m2 = s2 / cn - mu * mu;
+        const double m4 = s4 / cn - 4.0 * mu * (s3 / cn) + 6.0 * mu * mu * (s2 / cn) - 3.0 * mu * mu * mu * mu;
+        p.col_mean[o] = (float)(x0 + mu);
+        p.col_kurt[o] = (cn >= 4.0 && m2 > 0.0) ? (float)(m4 / (m2 * m2) - 3.0) : 0.f;
     }
 }
 
