@@ -164,8 +164,34 @@ def test_bad_arguments_of_mask_diff(lib):
     assert call(rows=0) == B.STREAM_OK
 
 
+def test_bad_arguments_of_receiver_stats(lib):
+    s = shape()
+    fake = ctypes.c_void_p(4096)
+    ws = ctypes.c_void_p(256 * 16)
+    need = lib.stream_receiver_stats_workspace_bytes(ctypes.byref(s))
+    assert need > 0
+
+    def call(Q=fake, K=fake, sh=s, scale=0.125, cm=fake, ck=fake, hs=fake, wsp=ws, wsz=need):
+        return lib.stream_receiver_stats(Q, K, ctypes.byref(sh), scale, None, cm, ck, hs, wsp, wsz, None)
+
+    assert call(Q=None) == B.STREAM_EINVAL
+    assert call(K=None) == B.STREAM_EINVAL
+    assert call(cm=None) == B.STREAM_EINVAL
+    assert call(ck=None) == B.STREAM_EINVAL
+    assert call(hs=None) == B.STREAM_EINVAL
+    assert call(scale=0.0) == B.STREAM_EINVAL
+    assert call(scale=float("inf")) == B.STREAM_EINVAL
+    assert call(Q=ctypes.c_void_p(4100)) == B.STREAM_EINVAL          # 16-byte loads
+    assert call(wsz=need - 1) == B.STREAM_EWORKSPACE
+    assert call(wsp=None) == B.STREAM_EWORKSPACE
+    assert call(sh=shape(dtype=B.STREAM_F32, head_dim=128, block=128)) == B.STREAM_EUNSUPPORTED
+    assert lib.stream_receiver_stats_workspace_bytes(ctypes.byref(shape(block=48))) == 0
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     Q = torch.zeros(2, 64, 64)
     with pytest.raises(ValueError):
         B.stream_prune(Q, Q, 2, 2, 64, 1)
+    with pytest.raises(ValueError):
+        B.stream_receiver_stats(Q, Q, 2, 2, 64, 0.125)
