@@ -24,28 +24,32 @@ def causal_mask(T: int) -> np.ndarray:
     return np.tril(np.ones((T, T), dtype=np.uint8))
 
 
-def block_score_table(Qh: np.ndarray, Kh: np.ndarray, block: int, C: np.ndarray | None = None):
+def block_score_table(Qh: np.ndarray, Kh: np.ndarray, block: int, C: np.ndarray | None = None,
+                      block_k: int | None = None):
+    """A [T_p / b_q, T_p / b_k] and C^blk of the same shape (block = b_q, block_k = b_k,
+    default the same; T_p = T rounded up to a multiple of lcm(b_q, b_k))."""
     Qh = np.asarray(Qh, dtype=np.float64)
     Kh = np.asarray(Kh, dtype=np.float64)
     T = Qh.shape[0]
+    bk = block if block_k is None else block_k
     C = causal_mask(T) if C is None else np.asarray(C)
-    N = -(-T // block)
-    Tp = N * block
+    ell = math.lcm(block, bk)
+    Tp = -(-T // ell) * ell
     S = np.full((Tp, Tp), -np.inf)
     S[:T, :T] = np.where(C != 0, Qh @ Kh.T, -np.inf)
     Cp = np.zeros((Tp, Tp), dtype=np.uint8)
     Cp[:T, :T] = C != 0
-    A = S.reshape(N, block, N, block).max(axis=(1, 3))
-    Cblk = Cp.reshape(N, block, N, block).max(axis=(1, 3))
+    A = S.reshape(Tp // block, block, Tp // bk, bk).max(axis=(1, 3))
+    Cblk = Cp.reshape(Tp // block, block, Tp // bk, bk).max(axis=(1, 3))
     return A, Cblk
 
 
 def stream_from_table(A: np.ndarray, Cblk: np.ndarray, k: int, n_levels: int | None = None):
     """Alg. 2 with every block score read from the dense table.  Returns list of index lists."""
-    N = A.shape[0]
+    N = A.shape[1]                       # the nodes range over the key blocks
     n_it = (0 if N <= 1 else math.ceil(math.log2(N))) if n_levels is None else n_levels
     out = []
-    for q in range(N):
+    for q in range(A.shape[0]):
         nodes = [((j * N) // k, ((j + 1) * N) // k - 1) for j in range(k)]
         for _ in range(n_it):
             branches = []
@@ -90,13 +94,14 @@ def dense_attention(Qh, Kh, Vh, token_mask: np.ndarray, scale: float):
     return P @ Vh, (mx + np.log(Z))[:, 0], P.sum(axis=0)
 
 
-def mask_from_blocks(idx_lists, T: int, block: int) -> np.ndarray:
+def mask_from_blocks(idx_lists, T: int, block: int, block_k: int | None = None) -> np.ndarray:
     """Token-level mask M * C from per-query-block key-block lists (causal inside blocks)."""
+    bk = block if block_k is None else block_k
     M = np.zeros((T, T), dtype=np.uint8)
     for q, lst in enumerate(idx_lists):
-        t0, t1 = q * block, min((q + 1) * block, T)
+        t0, t1 = min(q * block, T), min((q + 1) * block, T)
         for r in lst:
             if r < 0:
                 continue
-            M[t0:t1, r * block:min((r + 1) * block, T)] = 1
+            M[t0:t1, r * bk:min((r + 1) * bk, T)] = 1
     return M * causal_mask(T)

@@ -61,7 +61,7 @@ typedef struct {
     const float *K;           /* [T, d]  its key head                */
     const unsigned char *C;   /* [T, T] attention mask, or NULL = the rule below */
     long T;                   /* real tokens (before padding)        */
-    int d, b;                 /* head dim, block size b_q = b_k      */
+    int d, bq, bk;            /* head dim, query block size b_q, key block size b_k */
     int kind;                 /* MASK_CAUSAL: C[t,u] = 1 iff u <= t; MASK_FULL: all ones;
                                  MASK_SLIDING: u <= t and t - u < window                  */
     long window;
@@ -80,29 +80,29 @@ static int mask_C(const problem_t *p, long t, long u)
 /* C^blk[q,r] = max_{m,n} C[q,m,r,n]. */
 static int mask_Cblk(const problem_t *p, long q, long r)
 {
-    const int b = p->b;
+    const int bq = p->bq, bk = p->bk;
     if (!p->C && p->kind == MASK_CAUSAL) {
         /* causal: some real key of block r is <= some real query of block q
            iff the block's first key is <= the block's last real query        */
-        long first_key = r * b;
-        long last_query = ((q + 1) * (long)b < p->T ? (q + 1) * (long)b : p->T) - 1;
-        return first_key < p->T && q * (long)b < p->T && first_key <= last_query;
+        long first_key = r * bk;
+        long last_query = ((q + 1) * (long)bq < p->T ? (q + 1) * (long)bq : p->T) - 1;
+        return first_key < p->T && q * (long)bq < p->T && first_key <= last_query;
     }
-    for (int m = 0; m < b; ++m)
-        for (int n = 0; n < b; ++n)
-            if (mask_C(p, q * b + m, r * b + n)) return 1;
+    for (int m = 0; m < bq; ++m)
+        for (int n = 0; n < bk; ++n)
+            if (mask_C(p, q * bq + m, r * bk + n)) return 1;
     return 0;
 }
 
 /* s = max over (m,n) with C = 1 of <Q[q,m,:], K[r,n,:]>   (score line of Alg. 2; Eq. (4)) */
 static double block_score(const problem_t *p, long q, long r)
 {
-    const int b = p->b, d = p->d;
+    const int bq = p->bq, bk = p->bk, d = p->d;
     double s = -INFINITY;
-    for (int m = 0; m < b; ++m) {
-        long t = q * b + m;
-        for (int n = 0; n < b; ++n) {
-            long u = r * b + n;
+    for (int m = 0; m < bq; ++m) {
+        long t = q * bq + m;
+        for (int n = 0; n < bk; ++n) {
+            long u = r * bk + n;
             if (!mask_C(p, t, u)) continue;
             const float *qv = p->Q + t * d, *kv = p->K + u * d;
             double acc = 0.0;
@@ -116,15 +116,33 @@ static double block_score(const problem_t *p, long q, long r)
 double stream_oracle_block_score(const float *Q, const float *K, const unsigned char *C,
                                  long T, int d, int b, long q, long r)
 {
-    problem_t p = {Q, K, C, T, d, b, MASK_CAUSAL, 0};
+    problem_t p = {Q, K, C, T, d, b, b, MASK_CAUSAL, 0};
     return block_score(&p, q, r);
 }
 
 double stream_oracle_block_score_rule(const float *Q, const float *K, int mask_kind, long window,
                                       long T, int d, int b, long q, long r)
 {
-    problem_t p = {Q, K, NULL, T, d, b, mask_kind, window};
+    problem_t p = {Q, K, NULL, T, d, b, b, mask_kind, window};
     return block_score(&p, q, r);
+}
+
+/* The same for b_q x b_k blocks (q counts query blocks of b_q tokens, r key blocks of b_k). */
+double stream_oracle_block_score_rect(const float *Q, const float *K, const unsigned char *C,
+                                      int mask_kind, long window,
+                                      long T, int d, int bq, int bk, long q, long r)
+{
+    problem_t p = {Q, K, C, T, d, bq, bk, mask_kind, window};
+    return block_score(&p, q, r);
+}
+
+static long gcd_l(long a, long b) { while (b) { long t = a % b; a = b; b = t; } return a; }
+
+/* T_p of the preamble of Alg. 2: T rounded up to a multiple of lcm(b_q, b_k). */
+long stream_oracle_padded_len(long T, int bq, int bk)
+{
+    const long l = (long)bq / gcd_l(bq, bk) * bk;
+    return (T + l - 1) / l * l;
 }
 
 static long ceil_log2(long n)
@@ -168,19 +186,20 @@ static int int_cmp(const void *a, const void *b)
  *                  [1] those whose representative differs from the parent node's
  *                  (the evaluations that cannot be inherited), may be NULL
  */
-int stream_oracle_prune_head_rule(const float *Q, const float *K, const unsigned char *C,
+int stream_oracle_prune_head_rect(const float *Q, const float *K, const unsigned char *C,
                                   int mask_kind, long window,
-                                  long T, int d, int b, int k, int n_levels,
+                                  long T, int d, int bq, int bk, int k, int n_levels,
                                   const int *qlist, int nq,
                                   int *idx, int *cnt, double *score, int *trace, long long *evals)
 {
-    if (!Q || !K || T <= 0 || d <= 0 || b <= 0 || k <= 0 || nq < 0) return 1;
+    if (!Q || !K || T <= 0 || d <= 0 || bq <= 0 || bk <= 0 || k <= 0 || nq < 0) return 1;
     if (mask_kind < MASK_CAUSAL || mask_kind > MASK_SLIDING) return 1;
     if (mask_kind == MASK_SLIDING && window < 1) return 1;
-    problem_t p = {Q, K, C, T, d, b, mask_kind, window};
-    /* preamble: pad to l = lcm(b_q, b_k) = b; block views are index arithmetic */
-    const long T_p = ((T + b - 1) / b) * b;
-    const long N = T_p / b;
+    problem_t p = {Q, K, C, T, d, bq, bk, mask_kind, window};
+    /* preamble: pad to a multiple of l = lcm(b_q, b_k); block views are index arithmetic;
+       the nodes range over the T_p / b_k key blocks */
+    const long T_p = stream_oracle_padded_len(T, bq, bk);
+    const long N = T_p / bk;
     const long n_it = n_levels < 0 ? ceil_log2(N) : n_levels;
     long long ev_all = 0, ev_new = 0;
 
@@ -253,6 +272,17 @@ int stream_oracle_prune_head_rule(const float *Q, const float *K, const unsigned
     return 0;
 }
 
+/* b_q = b_k = b. */
+int stream_oracle_prune_head_rule(const float *Q, const float *K, const unsigned char *C,
+                                  int mask_kind, long window,
+                                  long T, int d, int b, int k, int n_levels,
+                                  const int *qlist, int nq,
+                                  int *idx, int *cnt, double *score, int *trace, long long *evals)
+{
+    return stream_oracle_prune_head_rect(Q, K, C, mask_kind, window, T, d, b, b, k, n_levels, qlist, nq,
+                                         idx, cnt, score, trace, evals);
+}
+
 /* The same with the causal mask (or an explicit C). */
 int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char *C,
                              long T, int d, int b, int k, int n_levels,
@@ -273,31 +303,31 @@ int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char
  * idx is [nq, k] (rows aligned with qlist), O is [T, d] and lse [T] (only rows of
  * the listed blocks are written), mass [T] is accumulated into (caller zeroes).
  */
-int stream_oracle_attn_head_rule(const float *Q, const float *K, const float *V,
+int stream_oracle_attn_head_rect(const float *Q, const float *K, const float *V,
                                  int mask_kind, long window,
-                                 long T, int d, int b, int k, double scale,
+                                 long T, int d, int bq, int bk, int k, double scale,
                                  const int *qlist, int nq, const int *idx, const int *cnt,
                                  double *O, double *lse, double *mass)
 {
     if (!Q || !K || !V || !idx || !cnt || T <= 0) return 1;
     if (mask_kind < MASK_CAUSAL || mask_kind > MASK_SLIDING) return 1;
     if (mask_kind == MASK_SLIDING && window < 1) return 1;
-    problem_t p = {Q, K, NULL, T, d, b, mask_kind, window};
+    problem_t p = {Q, K, NULL, T, d, bq, bk, mask_kind, window};
 #pragma omp parallel for schedule(dynamic, 1)
     for (int qi = 0; qi < nq; ++qi) {
         const long q = qlist[qi];
         const int c = cnt[qi];
-        double *sc = (double *)malloc(sizeof(double) * (size_t)(c > 0 ? c : 1) * b);
-        long *key = (long *)malloc(sizeof(long) * (size_t)(c > 0 ? c : 1) * b);
-        for (int m = 0; m < b; ++m) {
-            const long t = q * b + m;
+        double *sc = (double *)malloc(sizeof(double) * (size_t)(c > 0 ? c : 1) * bk);
+        long *key = (long *)malloc(sizeof(long) * (size_t)(c > 0 ? c : 1) * bk);
+        for (int m = 0; m < bq; ++m) {
+            const long t = q * bq + m;
             if (t >= T) break;
             long nk = 0;
             double mx = -INFINITY;
             for (int j = 0; j < c; ++j) {
                 const long r = idx[(long)qi * k + j];
-                for (int n = 0; n < b; ++n) {
-                    const long u = r * b + n;
+                for (int n = 0; n < bk; ++n) {
+                    const long u = r * bk + n;
                     if (!mask_C(&p, t, u)) continue;
                     double acc = 0.0;
                     for (int i = 0; i < d; ++i) acc += (double)Q[t * d + i] * (double)K[u * d + i];
@@ -326,6 +356,16 @@ int stream_oracle_attn_head_rule(const float *Q, const float *K, const float *V,
         free(sc); free(key);
     }
     return 0;
+}
+
+int stream_oracle_attn_head_rule(const float *Q, const float *K, const float *V,
+                                 int mask_kind, long window,
+                                 long T, int d, int b, int k, double scale,
+                                 const int *qlist, int nq, const int *idx, const int *cnt,
+                                 double *O, double *lse, double *mass)
+{
+    return stream_oracle_attn_head_rect(Q, K, V, mask_kind, window, T, d, b, b, k, scale, qlist, nq, idx,
+                                        cnt, O, lse, mass);
 }
 
 int stream_oracle_attn_head(const float *Q, const float *K, const float *V,

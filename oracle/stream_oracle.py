@@ -48,6 +48,9 @@ def _load():
         lib.stream_oracle_block_score.restype = ctypes.c_double
         lib.stream_oracle_block_score.argtypes = [fp, fp, up, ctypes.c_long, ctypes.c_int,
                                                   ctypes.c_int, ctypes.c_long, ctypes.c_long]
+        lib.stream_oracle_block_score_rule.restype = ctypes.c_double
+        lib.stream_oracle_block_score_rule.argtypes = [fp, fp, ctypes.c_int, ctypes.c_long, ctypes.c_long,
+                                                       ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_long]
         lib.stream_oracle_n_it.restype = ctypes.c_long
         lib.stream_oracle_n_it.argtypes = [ctypes.c_long, ctypes.c_int]
         lib.stream_oracle_prune_head.restype = ctypes.c_int
@@ -66,6 +69,23 @@ def _load():
                                                      ctypes.c_long, ctypes.c_int,
                                                      ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
                                                      ctypes.c_int, ip, ip, dp, dp, dp]
+        lib.stream_oracle_prune_head_rect.restype = ctypes.c_int
+        lib.stream_oracle_prune_head_rect.argtypes = [fp, fp, up, ctypes.c_int, ctypes.c_long,
+                                                      ctypes.c_long, ctypes.c_int, ctypes.c_int,
+                                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, ip,
+                                                      ctypes.c_int, ip, ip, dp, ip,
+                                                      ctypes.POINTER(ctypes.c_longlong)]
+        lib.stream_oracle_attn_head_rect.restype = ctypes.c_int
+        lib.stream_oracle_attn_head_rect.argtypes = [fp, fp, fp, ctypes.c_int, ctypes.c_long,
+                                                     ctypes.c_long, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
+                                                     ctypes.c_int, ip, ip, dp, dp, dp]
+        lib.stream_oracle_block_score_rect.restype = ctypes.c_double
+        lib.stream_oracle_block_score_rect.argtypes = [fp, fp, up, ctypes.c_int, ctypes.c_long,
+                                                       ctypes.c_long, ctypes.c_int, ctypes.c_int,
+                                                       ctypes.c_int, ctypes.c_long, ctypes.c_long]
+        lib.stream_oracle_padded_len.restype = ctypes.c_long
+        lib.stream_oracle_padded_len.argtypes = [ctypes.c_long, ctypes.c_int, ctypes.c_int]
         lib.stream_oracle_attn_head.restype = ctypes.c_int
         lib.stream_oracle_attn_head.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
@@ -101,15 +121,29 @@ def threads() -> int:
     return int(lib.stream_oracle_threads())
 
 
-def n_it(T: int, block: int) -> int:
+def padded_len(T: int, block: int, block_k: Optional[int] = None) -> int:
+    """T_p of the preamble of Alg. 2: T rounded up to a multiple of lcm(b_q, b_k)."""
+    return int(_load().stream_oracle_padded_len(int(T), int(block), int(block_k or block)))
+
+
+def n_it(T: int, block: int, block_k: Optional[int] = None) -> int:
     """n_it = ceil(log2(T_p / b_k)) (iteration count line of Alg. 2)."""
-    return int(_load().stream_oracle_n_it(int(T), int(block)))
+    if block_k is None or block_k == block:
+        return int(_load().stream_oracle_n_it(int(T), int(block)))
+    return int(_load().stream_oracle_n_it(padded_len(T, block, block_k), int(block_k)))
 
 
 def block_score(Qh: np.ndarray, Kh: np.ndarray, block: int, q: int, r: int, C=None,
-                mask: str = "causal", window: int = 0) -> float:
-    """Score of key block r for query block q of one head: masked max of the b x b dot products."""
+                mask: str = "causal", window: int = 0, block_k: Optional[int] = None) -> float:
+    """Score of key block r for query block q of one head: masked max of the b_q x b_k dot
+    products (block = b_q; block_k = b_k, default the same)."""
     Qh, Kh = _f32(Qh), _f32(Kh)
+    if block_k is not None and block_k != block:
+        kind, win = _mask_code(mask, window)
+        Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
+        return float(_load().stream_oracle_block_score_rect(
+            _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Cc, ctypes.c_ubyte), kind, win,
+            Qh.shape[0], Qh.shape[1], int(block), int(block_k), int(q), int(r)))
     if C is None and mask != "causal":
         kind, win = _mask_code(mask, window)
         return float(_load().stream_oracle_block_score_rule(
@@ -123,25 +157,27 @@ def block_score(Qh: np.ndarray, Kh: np.ndarray, block: int, q: int, r: int, C=No
 
 def prune_head(Qh, Kh, block: int, topk: int, qblocks: Optional[Sequence[int]] = None,
                n_levels: int = -1, C=None, want_trace: bool = False, mask: str = "causal",
-               window: int = 0):
+               window: int = 0, block_k: Optional[int] = None):
     """Algorithm 2 for one head / one sequence.  Returns dict(idx, cnt, score, trace, evals).
-    The mask C is the explicit [T, T] array if given, else the rule `mask` / `window`."""
+    The mask C is the explicit [T, T] array if given, else the rule `mask` / `window`.
+    block = b_q, block_k = b_k (default the same); there are T_p / b_q query blocks."""
     Qh, Kh = _f32(Qh), _f32(Kh)
     T, d = Qh.shape
-    N = (T + block - 1) // block
+    bk = int(block_k or block)
+    N = padded_len(T, block, bk) // block
     ql = np.arange(N, dtype=np.int32) if qblocks is None else np.ascontiguousarray(qblocks, dtype=np.int32)
     nq = len(ql)
     idx = np.full((nq, topk), -1, dtype=np.int32)
     cnt = np.zeros((nq,), dtype=np.int32)
     score = np.full((nq, topk), -np.inf, dtype=np.float64)
-    levels = n_it(T, block) if n_levels < 0 else n_levels
+    levels = n_it(T, block, bk) if n_levels < 0 else n_levels
     trace = np.full((nq, levels, topk, 2), -1, dtype=np.int32) if want_trace else None
     evals = np.zeros(2, dtype=np.int64)
     Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
     kind, win = _mask_code(mask, window)
-    rc = _load().stream_oracle_prune_head_rule(
+    rc = _load().stream_oracle_prune_head_rect(
         _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Cc, ctypes.c_ubyte), kind, win, T, d,
-        int(block), int(topk), int(n_levels), _ptr(ql, ctypes.c_int), nq,
+        int(block), bk, int(topk), int(n_levels), _ptr(ql, ctypes.c_int), nq,
         _ptr(idx, ctypes.c_int), _ptr(cnt, ctypes.c_int), _ptr(score, ctypes.c_double),
         _ptr(trace, ctypes.c_int), _ptr(evals, ctypes.c_longlong))
     if rc != 0:
@@ -149,12 +185,13 @@ def prune_head(Qh, Kh, block: int, topk: int, qblocks: Optional[Sequence[int]] =
     return {"idx": idx, "cnt": cnt, "score": score, "trace": trace, "evals": evals}
 
 
-def block_table(cu_seqlens: Sequence[int], block: int):
-    """(sequence id, local block id) of every global query block of a packed batch."""
+def block_table(cu_seqlens: Sequence[int], block: int, block_k: Optional[int] = None):
+    """(sequence id, local block id) of every global query block of a packed batch (T_p / b_q
+    query blocks per sequence, T_p the sequence's padded length)."""
     seq, loc = [], []
     for s in range(len(cu_seqlens) - 1):
         L = cu_seqlens[s + 1] - cu_seqlens[s]
-        nb = (L + block - 1) // block
+        nb = (L + block - 1) // block if not block_k or block_k == block else padded_len(L, block, block_k) // block
         seq += [s] * nb
         loc += list(range(nb))
     return np.asarray(seq, dtype=np.int64), np.asarray(loc, dtype=np.int64)
@@ -162,7 +199,8 @@ def block_table(cu_seqlens: Sequence[int], block: int):
 
 def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
           rows: Optional[Sequence[Sequence[int]]] = None, n_levels: int = -1,
-          want_trace: bool = False, mask: str = "causal", window: int = 0):
+          want_trace: bool = False, mask: str = "causal", window: int = 0,
+          block_k: Optional[int] = None):
     """Stream for every (head, query block), or for the listed rows only.
 
     Q [heads, T, d], K [kv_heads, T, d]; topk is an int or one int per sequence.
@@ -176,7 +214,7 @@ def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
     nseq = len(cu) - 1
     ks = [int(topk)] * nseq if np.isscalar(topk) else [int(x) for x in topk]
     kmax = max(ks)
-    bseq, bloc = block_table(cu, block)
+    bseq, bloc = block_table(cu, block, block_k)
     NB = len(bseq)
     blk_off = np.concatenate([[0], np.cumsum(np.bincount(bseq, minlength=nseq))])
     if rows is None:
@@ -199,7 +237,7 @@ def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
             Qh = Q[h, cu[s]:cu[s + 1]]
             Kh = K[h // g, cu[s]:cu[s + 1]]
             out = prune_head(Qh, Kh, block, ks[s], ql, n_levels=n_levels, want_trace=want_trace,
-                             mask=mask, window=window)
+                             mask=mask, window=window, block_k=block_k)
             idx[sel, :ks[s]] = out["idx"]
             cnt[sel] = out["cnt"]
             score[sel, :ks[s]] = out["score"]
@@ -271,8 +309,10 @@ def prune_variable(Q, K, heads: int, kv_heads: int, block: int, keep_num: int, k
 
 def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
                 cu_seqlens=None, rows: Optional[Sequence[Sequence[int]]] = None,
-                want_mass: bool = True, mask: str = "causal", window: int = 0):
-    """Eq. (2) over the retained blocks given by idx/cnt.
+                want_mass: bool = True, mask: str = "causal", window: int = 0,
+                block_k: Optional[int] = None):
+    """Eq. (2) over the retained blocks given by idx/cnt (query blocks of `block` tokens, key
+    blocks of `block_k` tokens, default the same).
 
     idx/cnt are [heads, NB, kmax]/[heads, NB] (full) or aligned with `rows`.
     Returns dict(O [heads, T, d], lse [heads, T], mass [heads, T]) in fp64; with `rows`,
@@ -283,7 +323,7 @@ def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale:
     H, T, d = Q.shape
     g = heads // kv_heads
     cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
-    bseq, bloc = block_table(cu, block)
+    bseq, bloc = block_table(cu, block, block_k)
     NB = len(bseq)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     cnt = np.ascontiguousarray(cnt, dtype=np.int32)
@@ -312,15 +352,16 @@ def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale:
             i2 = np.ascontiguousarray(idx2[sel])
             c2 = np.ascontiguousarray(cnt2[sel])
             kind, win = _mask_code(mask, window)
-            rc = lib.stream_oracle_attn_head_rule(
+            rc = lib.stream_oracle_attn_head_rect(
                 _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Vh, ctypes.c_float),
-                kind, win, b_ - a, d, int(block), kmax, float(scale), _ptr(ql, ctypes.c_int), len(ql),
+                kind, win, b_ - a, d, int(block), int(block_k or block), kmax, float(scale),
+                _ptr(ql, ctypes.c_int), len(ql),
                 _ptr(i2, ctypes.c_int), _ptr(c2, ctypes.c_int), _ptr(Oh, ctypes.c_double),
                 _ptr(lh, ctypes.c_double), _ptr(mh if want_mass else None, ctypes.c_double))
             if rc != 0:
                 raise ValueError("stream_oracle_attn_head: bad arguments")
             for qb in ql:
-                t0, t1 = qb * block, min((qb + 1) * block, b_ - a)
+                t0, t1 = min(qb * block, b_ - a), min((qb + 1) * block, b_ - a)
                 O[h, a + t0:a + t1] = Oh[t0:t1]
                 lse[h, a + t0:a + t1] = lh[t0:t1]
             mass[h, a:b_] += mh
