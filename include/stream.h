@@ -27,12 +27,18 @@
  *     default.  Query head h reads key/value head h / (heads / kv_heads).
  *   - A ragged batch is packed along the token axis; cu_seqlens (HOST,
  *     int32[batch+1], cu[0] = 0, cu[batch] = T) gives the boundaries.  Blocks
- *     never straddle sequences: sequence s has N_s = ceil(L_s / block) query
- *     (= key) blocks, the last one possibly partial, and NB = sum_s N_s.
- *     Key-block ids in `idx` are local to their sequence.
- *   - b_q = b_k = block; the mask C is one of the rules of stream_mask (a zero-initialised
- *     shape means causal).  A key block is valid for a query block when at least one of its
- *     real keys is visible to one of the block's real queries.
+ *     never straddle sequences.  As in the preamble of Algorithm 2 a sequence of
+ *     L_s tokens is padded (virtually) to T_p = L_s rounded up to a multiple of
+ *     lcm(b_q, b_k) and has N_s = T_p / b_q query blocks and T_p / b_k key blocks;
+ *     NB = sum_s N_s counts query blocks.  With b_q = b_k = b that is
+ *     N_s = ceil(L_s / b) of each.  A query block that holds padding only (possible
+ *     when b_q < b_k) gets an empty list.  Key-block ids in `idx` are local to
+ *     their sequence.
+ *   - b_q = shape.block, b_k = shape.block_k (0 = b_q); the mask C is one of the rules of
+ *     stream_mask (a zero-initialised shape means causal, b_k = b_q).  A key block is valid for
+ *     a query block when at least one of its real keys is visible to one of the block's real
+ *     queries.  stream_prune*, stream_sparse_attn take b_q != b_k; stream_receiver_stats
+ *     does not (STREAM_EUNSUPPORTED).
  *   - Every entry point validates its arguments on the host before any launch
  *     and returns a stream_status; nothing is thrown or logged.  Outputs are
  *     fully overwritten on STREAM_OK and untouched on an argument error.
@@ -69,7 +75,7 @@ typedef struct {
     int heads;       /* query heads H                                                  */
     int kv_heads;    /* key/value heads, divides H                                     */
     int head_dim;    /* 64 or 128                                                      */
-    int block;       /* b_q = b_k: 32, 64 or 128                                       */
+    int block;       /* b_q (and b_k unless block_k is set): 32, 64 or 128             */
     int dtype;       /* stream_dtype of Q, K, V, O                                     */
     int batch;       /* sequences in the packed batch, >= 1                            */
     long long T;     /* total tokens                                                   */
@@ -80,6 +86,7 @@ typedef struct {
     long long o_stride_h, o_stride_t; /* stream_sparse_attn only                        */
     int mask;        /* stream_mask: the attention mask C of Algorithm 2 and Eq. (2)   */
     long long window;/* STREAM_MASK_SLIDING: window length W in tokens, >= 1           */
+    int block_k;     /* b_k: 32, 64 or 128; 0 = the same as block (b_q = b_k)          */
 } stream_shape;
 
 /* Optional diagnostics of stream_prune (each member may be NULL). */
@@ -282,7 +289,7 @@ stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *
  *   workspace   stream_receiver_stats_workspace_bytes(shape) bytes (packed Q and K, one float
  *               per padded token and head), 256-byte aligned
  * The moments are accumulated in fp64 from the fp32 block means.  Errors: as stream_prune;
- * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and block 128.
+ * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and block 128, and for b_q != b_k.
  */
 size_t stream_receiver_stats_workspace_bytes(const stream_shape *shape);
 

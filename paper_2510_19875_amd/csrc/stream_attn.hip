@@ -168,7 +168,8 @@ __device__ __forceinline__ void static_for(F &f)
     }
 }
 
-// NQ: 32-query groups per wavefront, NK: 32-key groups per key sub-tile, B: block size.
+// NQ: 32-query groups per wavefront, NK: 32-key groups per key sub-tile, BQ / BK: query / key
+// block size.
 //
 // Pass 1 handles a key sub-tile in one of two ways.  Plain order (sub-tiles the mask cuts, the
 // sub-tile that sets the softmax reference, the fallback): the K fragments of t are already in
@@ -179,7 +180,7 @@ __device__ __forceinline__ void static_for(F &f)
 // allowed in flight.
 // PASS 1: outputs O, lse (and the base-2 normalisers for pass 2).  PASS 2: received mass, a
 // separate launch with two wavefronts per SIMD so that one's exponentials overlap the other's MFMAs.
-template <bool BF16, int D, int NQ, int NK, int B, int PASS, int OCC>
+template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC>
 __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -188,9 +189,10 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     constexpr int NVF = BF16 ? 2 : 4;          // V fragments per (group, feature block)
     constexpr int QT = 32 * NQ;                // queries per wavefront
     constexpr int KT = 32 * NK;                // keys per sub-tile
-    constexpr int QSUB = B / QT;               // wavefronts per row
-    constexpr int KSUB = B / KT;               // key sub-tiles per block
-    constexpr long long TILE_BYTES = (long long)B * D * ES;
+    constexpr int QSUB = BQ / QT;              // wavefronts per row
+    constexpr int KSUB = BK / KT;              // key sub-tiles per block
+    constexpr long long TILE_BYTES = (long long)BK * D * ES;
+    constexpr long long QBLK_BYTES = (long long)BQ * D * ES;   // packed bytes of one query block's span
     constexpr int GROUP_BYTES = 32 * D * ES;
 
     const int lane = threadIdx.x & 63;
@@ -209,7 +211,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     const SeqDesc sd = p.seqs.d[sq];
     const int q = gb - sd.blk0, L = sd.len;
     const long long row = (long long)h * p.NB + gb;
-    const int qtok0 = q * B + qs * QT;          // first query token (sequence-local) of this wavefront
+    const int qtok0 = q * BQ + qs * QT;         // first query token (sequence-local) of this wavefront
     if (qtok0 >= L) return;
     int n_blk = p.cnt[row];
     n_blk = n_blk < 0 ? 0 : (n_blk > p.kmax ? p.kmax : n_blk);   // never read past the row's list
@@ -221,8 +223,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     int n_tiles = n_blk * KSUB;
     if (n_blk > 0 && p.mask != STREAM_MASK_FULL) {
         const int last_r = my_idx[n_blk - 1];
-        if (last_r * B + (KSUB - 1) * KT > qtok0 + QT - 1) {
-            int vis = (qtok0 + QT - 1 - last_r * B) / KT + 1;
+        if (last_r * BK + (KSUB - 1) * KT > qtok0 + QT - 1) {
+            int vis = (qtok0 + QT - 1 - last_r * BK) / KT + 1;
             vis = vis < 0 ? 0 : (vis > KSUB ? KSUB : vis);
             n_tiles = (n_blk - 1) * KSUB + vis;
         }
@@ -244,11 +246,11 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         }
     }
     // packed K and V tiles of this (kv head, sequence)
-    const unsigned region_bytes = (unsigned)((long long)sd.nblk * TILE_BYTES);
+    const unsigned region_bytes = (unsigned)((long long)sd.nblk * QBLK_BYTES);
     const __amdgpu_buffer_rsrc_t krs =
-        make_tile_rsrc(p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES, region_bytes);
+        make_tile_rsrc(p.Kp + ((long long)kvh * p.NB + sd.blk0) * QBLK_BYTES, region_bytes);
     const __amdgpu_buffer_rsrc_t vrs =
-        make_tile_rsrc(p.Vp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES, region_bytes);
+        make_tile_rsrc(p.Vp + ((long long)kvh * p.NB + sd.blk0) * QBLK_BYTES, region_bytes);
     const unsigned lane_off = lane * 16;
     // the row's block list lives in one register (lane j holds entry j; lists have <= 64 entries)
     // and is read with a scalar lane select: no memory access inside the tile loops
@@ -261,7 +263,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     auto tile_ktok0 = [&](int t) -> int {
         const int ts = __builtin_amdgcn_readfirstlane(t);
         const int r = __builtin_amdgcn_readlane(my_blk, ts / KSUB);
-        return r * B + (ts % KSUB) * KT;
+        return r * BK + (ts % KSUB) * KT;
     };
     // does the mask C (or the end of the sequence) cut through the sub-tile that starts at key k0?
     auto needs_mask = [&](int k0) -> bool {
@@ -790,24 +792,35 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 
 typedef void (*attn_fn)(const AttnParams);
 
+// 64 queries per wavefront (32 for query block 32) against 32-key sub-tiles: with one 32-key
+// group in flight the scores, the K/V fragments and the Q tile fit the 256 architectural VGPRs
+// and the output accumulators live in the accumulation registers.
+template <int PASS, int OCC, bool BF16, int D, int NQ, int BQ>
+static attn_fn pick_attn_kernel_bk(int bk)
+{
+    if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC>;
+    if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC>;
+    return attn_kernel<BF16, D, NQ, 1, BQ, 128, PASS, OCC>;
+}
+
+template <int PASS, int OCC, bool BF16, int D>
+static attn_fn pick_attn_kernel_d(int bq, int bk)
+{
+    constexpr int OCC2 = (BF16 || D == 64) ? OCC : 1;
+    if (bq == 32) return pick_attn_kernel_bk<PASS, OCC, BF16, D, 1, 32>(bk);
+    if (bq == 64) return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 64>(bk);
+    return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 128>(bk);
+}
+
 template <int PASS, int OCC>
 static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
 {
-    // 64 queries per wavefront (32 for block 32) against 32-key sub-tiles: with one 32-key group
-    // in flight the scores, the K/V fragments and the Q tile fit the 256 architectural VGPRs and
-    // the output accumulators live in the accumulation registers.
-    const bool bf = pb.dtype == STREAM_BF16;
     qsub = pb.b == 128 ? 2 : 1;
-    if (pb.b == 32) {
-        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 1, 1, 32, PASS, OCC> : attn_kernel<true, 64, 1, 1, 32, PASS, OCC>;
-        return pb.d == 128 ? attn_kernel<false, 128, 1, 1, 32, PASS, OCC> : attn_kernel<false, 64, 1, 1, 32, PASS, OCC>;
-    }
-    if (pb.b == 64) {
-        if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 64, PASS, OCC> : attn_kernel<true, 64, 2, 1, 64, PASS, OCC>;
-        return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 64, PASS, 1> : attn_kernel<false, 64, 2, 1, 64, PASS, OCC>;
-    }
-    if (bf) return pb.d == 128 ? attn_kernel<true, 128, 2, 1, 128, PASS, OCC> : attn_kernel<true, 64, 2, 1, 128, PASS, OCC>;
-    return pb.d == 128 ? attn_kernel<false, 128, 2, 1, 128, PASS, 1> : attn_kernel<false, 64, 2, 1, 128, PASS, OCC>;
+    if (pb.dtype == STREAM_BF16)
+        return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, true, 128>(pb.b, pb.bk)
+                           : pick_attn_kernel_d<PASS, OCC, true, 64>(pb.b, pb.bk);
+    return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, false, 128>(pb.b, pb.bk)
+                       : pick_attn_kernel_d<PASS, OCC, false, 64>(pb.b, pb.bk);
 }
 
 struct AttnWorkspace {

@@ -17,10 +17,10 @@ constexpr int kXcds = 8;        // MI355X: 8 XCDs, workgroups are dealt to them 
 struct SeqDesc {
     long long tok0;  // first token in the packed token axis
     int len;         // L_s real tokens
-    int nblk;        // N_s = ceil(L_s / block)
+    int nblk;        // query blocks T_p / b_q, T_p = L_s rounded up to a multiple of lcm(b_q, b_k)
     int blk0;        // first global block id
     int k;           // k_s
-    int levels;      // refinement levels to run: max(1, ceil(log2(ceil(N_s / k_s))))
+    int levels;      // refinement levels to run: max(1, ceil(log2(ceil(N_k / k_s)))), N_k = T_p / b_k
     int pad_;
 };
 
@@ -99,18 +99,24 @@ __host__ __device__ __forceinline__ bool mask_token(int mask, int window, int tq
     return (mask == STREAM_MASK_FULL) | (causal_ok & window_ok);
 }
 
-__host__ __device__ __forceinline__ int mask_rmin(int mask, int window, int q, int b)
+// Blocks: queries come in blocks of bq tokens, keys in blocks of bk tokens (b_q, b_k of Alg. 2).
+__host__ __device__ __forceinline__ int mask_rmin(int mask, int window, int q, int bq, int bk)
 {
     if (mask != STREAM_MASK_SLIDING) return 0;
-    // the first query of the block, q*b, sees keys > q*b - window; block r reaches key r*b + b - 1
-    const long long lo = (long long)q * b - window + 1;            // first visible key (may be < 0)
+    // the first query of the block, q*bq, sees keys > q*bq - window
+    const long long lo = (long long)q * bq - window + 1;           // first visible key (may be < 0)
     if (lo <= 0) return 0;
-    return (int)(lo / b);                                           // block that contains it
+    return (int)(lo / bk);                                          // key block that contains it
 }
 
-__host__ __device__ __forceinline__ int mask_rmax(int mask, int q, int nblk)
+// -1 for a query block that holds no real token (padding up to lcm(bq, bk))
+__host__ __device__ __forceinline__ int mask_rmax(int mask, int q, int bq, int bk, int L)
 {
-    return mask == STREAM_MASK_FULL ? nblk - 1 : q;
+    const long long first = (long long)q * bq;
+    if (first >= L) return -1;
+    // the last real query of the block sees keys up to itself (no mask: up to the last key)
+    const long long last = mask == STREAM_MASK_FULL || first + bq > L ? (long long)L - 1 : first + bq - 1;
+    return (int)(last / bk);
 }
 
 #if defined(__HIPCC__)
@@ -136,7 +142,7 @@ __device__ __forceinline__ uint4 load_frag(__amdgpu_buffer_rsrc_t rs, unsigned l
 
 // Host-side validated problem description shared by both entry points.
 struct Problem {
-    int H, Hkv, g, d, b, dtype, esize, batch, kmax;
+    int H, Hkv, g, d, b, bk, dtype, esize, batch, kmax;   // b = b_q (query block), bk = b_k
     int mask, window;         // stream_mask rule; window in tokens (sliding window only)
     long long T;
     int NB;

@@ -14,7 +14,8 @@ static int ceil_log2_ll(long long n)
 }
 
 // Validates a shape (+ optional top-k arguments; topk_max <= 0 skips them) and derives the
-// per-sequence block geometry of the preamble of Alg. 2: T_p = ceil(T / b) * b per sequence.
+// per-sequence block geometry of the preamble of Alg. 2: T_p = T rounded up to a multiple of
+// lcm(b_q, b_k) per sequence.
 stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_seq, int topk_max,
                            Problem *out)
 {
@@ -25,6 +26,7 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
     if (s->batch > 1 && !s->cu_seqlens) return STREAM_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return STREAM_EUNSUPPORTED;
     if (s->block != 32 && s->block != 64 && s->block != 128) return STREAM_EUNSUPPORTED;
+    if (s->block_k != 0 && s->block_k != 32 && s->block_k != 64 && s->block_k != 128) return STREAM_EUNSUPPORTED;
     if (s->batch > kMaxBatch) return STREAM_EUNSUPPORTED;
     if (s->T > (1LL << 31) - 4096) return STREAM_EUNSUPPORTED;
     if (s->mask != STREAM_MASK_CAUSAL && s->mask != STREAM_MASK_FULL && s->mask != STREAM_MASK_SLIDING)
@@ -33,7 +35,8 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
 
     Problem &p = *out;
     p.H = s->heads; p.Hkv = s->kv_heads; p.g = s->heads / s->kv_heads;
-    p.d = s->head_dim; p.b = s->block; p.dtype = s->dtype;
+    p.d = s->head_dim; p.b = s->block; p.bk = s->block_k ? s->block_k : s->block; p.dtype = s->dtype;
+    const int lcm = p.b > p.bk ? p.b : p.bk;          // both are powers of two
     p.esize = s->dtype == STREAM_BF16 ? 2 : 4;
     p.batch = s->batch; p.T = s->T; p.kmax = topk_max;
     p.mask = s->mask;
@@ -49,9 +52,11 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
         SeqDesc &sd = p.seqs.d[i];
         sd.tok0 = a;
         sd.len = (int)(e - a);
-        sd.nblk = (int)((e - a + s->block - 1) / s->block);
+        const long long t_pad = (e - a + lcm - 1) / lcm * lcm;      // T_p of the preamble of Alg. 2
+        sd.nblk = (int)(t_pad / p.b);
+        const long long nkb = t_pad / p.bk;                          // key blocks: the nodes range over these
         // tile offsets inside one (kv head, sequence) region are 32-bit
-        if ((long long)sd.nblk * s->block * s->head_dim * p.esize >= (1LL << 31)) return STREAM_EUNSUPPORTED;
+        if (t_pad * s->head_dim * p.esize >= (1LL << 31)) return STREAM_EUNSUPPORTED;
         sd.blk0 = (int)nb;
         sd.k = 0; sd.levels = 0; sd.pad_ = 0;
         if (topk_max > 0) {
@@ -59,7 +64,7 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
             if (k < 1) return STREAM_EINVAL;
             if (k > topk_max) return STREAM_EINVAL;
             sd.k = k;
-            long long per = (sd.nblk + (long long)k - 1) / k;
+            long long per = (nkb + (long long)k - 1) / k;
             int lv = ceil_log2_ll(per);
             sd.levels = lv < 1 ? 1 : lv;
             if (sd.levels > maxlev) maxlev = sd.levels;

@@ -67,8 +67,9 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int FR = D * ES / 32;                       // fragments per 32-token group
-    constexpr int B = 32 * MB * (WPR == 4 ? 2 : 1);       // block size b_q = b_k
-    constexpr long long TILE_BYTES = (long long)B * D * ES;
+    constexpr int BQ = 32 * MB * (WPR == 4 ? 2 : 1);      // query block b_q
+    constexpr int BK = 32 * NG * (WPR == 4 ? 2 : 1);      // key block b_k
+    constexpr long long TILE_BYTES = (long long)BK * D * ES;
     constexpr int GROUP_BYTES = 32 * D * ES;
     __shared__ int s_rep[4][2 * kMaxTopk];
     __shared__ float s_sc[4][2 * kMaxTopk];
@@ -89,10 +90,11 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int h = kvh * p.g + (int)(rk % p.g);
     const int sq = seq_of_block(p.seqs, gb);
     const SeqDesc sd = p.seqs.d[sq];
-    const int q = gb - sd.blk0, N = sd.nblk, L = sd.len;
+    const int q = gb - sd.blk0, L = sd.len;
+    const int N = sd.nblk * BQ / BK;                      // key blocks of the sequence: the nodes range over these
     int row_k = sd.k, row_levels = sd.levels;
     if (!MULTI && p.vk_den > 0) {
-        const int valid = mask_rmax(p.mask, q, N) - mask_rmin(p.mask, p.window, q, B) + 1;
+        const int valid = mask_rmax(p.mask, q, BQ, BK, L) - mask_rmin(p.mask, p.window, q, BQ, BK) + 1;
         row_k = variable_k(valid, p.vk_num, p.vk_den, p.vk_min, p.kmax);
         row_levels = levels_for(N, row_k);
     }
@@ -112,7 +114,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             (unsigned)((long long)(L - 1) * p.q_st_b + D * ES));
 #pragma unroll
         for (int rb = 0; rb < MB; ++rb) {
-            const unsigned tok = (unsigned)(q * B + qh * 32 * MB + rb * 32 + mrow);
+            const unsigned tok = (unsigned)(q * BQ + qh * 32 * MB + rb * 32 + mrow);
             const unsigned voff = tok * (unsigned)p.q_st_b + gh * 16;
 #pragma unroll
             for (int fr = 0; fr < FR; ++fr) {
@@ -165,17 +167,17 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 
     // K tiles of this (kv head, sequence), from this wavefront's key half on
     const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(
-        p.Kp + ((long long)kvh * p.NB + sd.blk0) * TILE_BYTES + (long long)kh * NG * GROUP_BYTES,
+        p.Kp + ((long long)kvh * p.NB + sd.blk0) * BQ * D * ES + (long long)kh * NG * GROUP_BYTES,
         (unsigned)((long long)N * TILE_BYTES - (long long)kh * NG * GROUP_BYTES));
     const unsigned lane_off = lane * 16;
-    const bool tail_row = (q == N - 1) && (L % B != 0);
-    const int qtok0 = q * B + qh * 32 * MB;
+    const bool tail_row = (q + 1) * BQ > L;               // the query block has padded rows
+    const int qtok0 = q * BQ + qh * 32 * MB;
     // valid key blocks of this row under the mask C: rmin .. rmax (a branch's representative is
     // its first valid block); blocks the mask cuts through need the token-level test
-    const int rmin = mask_rmin(p.mask, p.window, q, B), rmax = mask_rmax(p.mask, q, N);
+    const int rmin = mask_rmin(p.mask, p.window, q, BQ, BK), rmax = mask_rmax(p.mask, q, BQ, BK, L);
     // blocks <= edge_hi hold a key that lies outside the window of the block's last query
-    const int edge_num = q * B + B - 1 - p.window;
-    const int edge_hi = p.mask == STREAM_MASK_SLIDING && edge_num >= 0 ? edge_num / B : -1;
+    const int edge_num = q * BQ + BQ - 1 - p.window;
+    const int edge_hi = p.mask == STREAM_MASK_SLIDING && edge_num >= 0 ? edge_num / BK : -1;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const long long o = row * p.kmax;
 
@@ -258,8 +260,9 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                 }
             }
             float mx = -INFINITY;
-            const bool cut = tail_row || (p.mask != STREAM_MASK_FULL && r == q) || r <= edge_hi ||
-                             (p.mask == STREAM_MASK_FULL && r == N - 1 && L % B != 0);
+            // the block reaches past the row's first query (causal rules) or past the sequence
+            const bool cut = tail_row || (p.mask != STREAM_MASK_FULL && (r + 1) * BK - 1 > q * BQ) ||
+                             r <= edge_hi || (r + 1) * BK > L;
             if (!cut) {
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
@@ -272,7 +275,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                 // token-level test.
                 // 32x32 accumulator layout: lane holds column (lane % 32); element i is row
                 // 8*(i/4) + 4*(lane/32) + (i%4).
-                const int ktok0 = r * B + kh * 32 * NG;
+                const int ktok0 = r * BK + kh * 32 * NG;
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
@@ -395,21 +398,39 @@ constexpr int kDefaultLevelsPerLaunch = 64;
 
 typedef void (*level_fn)(const PruneParams);
 
+// One wavefront per row holds MB x NG accumulator tiles; beyond 2 x 2 only one wavefront fits a
+// SIMD's registers.  fp32 fragments are twice as many: with d = 128 the 4 x 2 and 2 x 4 shapes do
+// not fit at all.
+template <bool MULTI, bool BF16, int D>
+static level_fn pick_level_kernel_d(int bq, int bk, int &wpr)
+{
+    constexpr int OCC2 = (BF16 || D == 64) ? 2 : 1;
+    constexpr bool BIG = BF16 || D == 64;           // 6 fragment groups + 8 accumulator tiles fit
+    wpr = 1;
+    const int mb = bq / 32, ng = bk / 32;
+    if (mb == 4 && ng == 4) { wpr = 4; return level_kernel<BF16, D, 2, 2, 4, OCC2, MULTI>; }
+    if (mb == 1 && ng == 1) return level_kernel<BF16, D, 1, 1, 1, 2, MULTI>;
+    if (mb == 2 && ng == 2) return level_kernel<BF16, D, 2, 2, 1, OCC2, MULTI>;
+    if (mb == 1 && ng == 2) return level_kernel<BF16, D, 1, 2, 1, OCC2, MULTI>;
+    if (mb == 2 && ng == 1) return level_kernel<BF16, D, 2, 1, 1, OCC2, MULTI>;
+    constexpr int OCC41 = (BF16 && D == 64) ? 2 : 1;   // 5 fragment groups of 8 or 16 registers + 4 tiles
+    if (mb == 1 && ng == 4) return level_kernel<BF16, D, 1, 4, 1, OCC41, MULTI>;
+    if (mb == 4 && ng == 1) return level_kernel<BF16, D, 4, 1, 1, OCC41, MULTI>;
+    if constexpr (BIG) {
+        if (mb == 2 && ng == 4) return level_kernel<BF16, D, 2, 4, 1, 1, MULTI>;
+        if (mb == 4 && ng == 2) return level_kernel<BF16, D, 4, 2, 1, 1, MULTI>;
+    }
+    return nullptr;
+}
+
 template <bool MULTI>
 static level_fn pick_level_kernel_t(const Problem &pb, int &wpr)
 {
-    const bool bf = pb.dtype == STREAM_BF16;
-    wpr = pb.b == 128 ? 4 : 1;
-    if (pb.b == 32) {
-        if (bf) return pb.d == 128 ? level_kernel<true, 128, 1, 1, 1, 2, MULTI> : level_kernel<true, 64, 1, 1, 1, 2, MULTI>;
-        return pb.d == 128 ? level_kernel<false, 128, 1, 1, 1, 2, MULTI> : level_kernel<false, 64, 1, 1, 1, 2, MULTI>;
-    }
-    if (pb.b == 64) {
-        if (bf) return pb.d == 128 ? level_kernel<true, 128, 2, 2, 1, 2, MULTI> : level_kernel<true, 64, 2, 2, 1, 2, MULTI>;
-        return pb.d == 128 ? level_kernel<false, 128, 2, 2, 1, 1, MULTI> : level_kernel<false, 64, 2, 2, 1, 2, MULTI>;
-    }
-    if (bf) return pb.d == 128 ? level_kernel<true, 128, 2, 2, 4, 2, MULTI> : level_kernel<true, 64, 2, 2, 4, 2, MULTI>;
-    return pb.d == 128 ? level_kernel<false, 128, 2, 2, 4, 1, MULTI> : level_kernel<false, 64, 2, 2, 4, 2, MULTI>;
+    if (pb.dtype == STREAM_BF16)
+        return pb.d == 128 ? pick_level_kernel_d<MULTI, true, 128>(pb.b, pb.bk, wpr)
+                           : pick_level_kernel_d<MULTI, true, 64>(pb.b, pb.bk, wpr);
+    return pb.d == 128 ? pick_level_kernel_d<MULTI, false, 128>(pb.b, pb.bk, wpr)
+                       : pick_level_kernel_d<MULTI, false, 64>(pb.b, pb.bk, wpr);
 }
 
 static level_fn pick_level_kernel(const Problem &pb, bool multi, int &wpr)
@@ -439,6 +460,9 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     // 16-byte vector loads: base pointers and strides must keep rows 16-byte aligned
     if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
     if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
+    int wpr = 1;
+    level_fn fn = pick_level_kernel(pb, multi, wpr);
+    if (!fn) return STREAM_EUNSUPPORTED;
     const PruneWorkspace w = prune_layout(pb);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return STREAM_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -464,8 +488,6 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     p.vk_num = vk.num; p.vk_den = vk.den; p.vk_min = vk.kmin;
     p.n_k = multi ? n_k : 1;
     for (int i = 0; i < kMaxSweep; ++i) p.klist[i] = multi && i < n_k ? topk_list[i] : 0;
-    int wpr = 1;
-    level_fn fn = pick_level_kernel(pb, multi, wpr);
     const long long rows_per_kv = (long long)pb.NB * pb.g;
     const long long per_kv = wpr == 1 ? (rows_per_kv + 3) / 4 : rows_per_kv;
     if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;

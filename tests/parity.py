@@ -17,22 +17,34 @@ from oracle import stream_oracle as so
 TIE_RTOL = 1e-3
 
 
-def valid_range(mask, window, q, block, N):
-    """First and last key block with a key visible to a query of block q under the mask rule."""
-    rmax = N - 1 if mask == "full" else q
+def valid_range(mask, window, q, block, N, block_k=None, L=None):
+    """First and last key block with a key visible to a query of block q under the mask rule
+    (square blocks: N = blocks of the sequence; b_q != b_k: pass block_k and the length L)."""
+    if block_k is None or block_k == block:
+        rmax = N - 1 if mask == "full" else q
+        rmin = 0
+        if mask == "sliding":
+            lo = q * block - window + 1           # first key the block's first query sees
+            rmin = max(0, lo // block) if lo > 0 else 0
+        return rmin, rmax
+    if q * block >= L:
+        return 0, -1                              # a query block of padding only
+    last_q = min(L, (q + 1) * block) - 1
+    rmax = (L - 1) // block_k if mask == "full" else last_q // block_k
     rmin = 0
     if mask == "sliding":
-        lo = q * block - window + 1           # first key the block's first query sees
-        rmin = max(0, lo // block) if lo > 0 else 0
+        lo = q * block - window + 1
+        rmin = lo // block_k if lo > 0 else 0
     return rmin, rmax
 
 
-def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0):
+def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0, block_k=None):
     """trace_row: int array [levels, k, 2] of (f, l) kept after each GPU level (-1 = dead).
     Returns (ok, reason)."""
     T = Qh.shape[0]
-    N = -(-T // block)
-    rmin, rmax = valid_range(mask, window, q, block, N)
+    bk = block_k or block
+    N = so.padded_len(T, block, bk) // bk     # key blocks: the nodes range over these
+    rmin, rmax = valid_range(mask, window, q, block, N, block_k, T)
     rep = lambda f: max(f, rmin)              # a branch's representative: its first valid block
     nodes = [((j * N) // k, ((j + 1) * N) // k - 1) for j in range(k)]
     nodes = [(f, l) for (f, l) in nodes if f <= l]
@@ -52,8 +64,8 @@ def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0):
             return False, f"level {lv}: kept {len(kept)} of {len(children)} valid, k={k}"
         dropped = [c for c in children if c not in set(kept)]
         if dropped:
-            s_keep = min(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window) for f, _ in kept)
-            s_drop = max(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window) for f, _ in dropped)
+            s_keep = min(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window, block_k=block_k) for f, _ in kept)
+            s_drop = max(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window, block_k=block_k) for f, _ in dropped)
             if s_keep < s_drop - TIE_RTOL * max(abs(s_drop), abs(s_keep)):
                 return False, f"level {lv}: dropped {s_drop} > kept {s_keep}"
         nodes = kept
@@ -63,7 +75,7 @@ def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0):
 
 
 def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None, rows=None,
-                  mask="causal", window=0):
+                  mask="causal", window=0, block_k=None):
     """gpu: dict of numpy arrays idx [H,NB,kmax], cnt [H,NB], optional score, trace
     [levels,H,NB,kmax,2].  ref: output of so.prune(...) for the same rows (or all).
     Q, K: numpy float32 (exact input values).  Returns dict with counts; raises on failure."""
@@ -73,7 +85,7 @@ def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None,
     cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
     nseq = len(cu) - 1
     ks = [int(topk)] * nseq if np.isscalar(topk) else [int(x) for x in topk]
-    bseq, bloc = so.block_table(cu, block)
+    bseq, bloc = so.block_table(cu, block, block_k)
     NB = len(bseq)
     if rows is None:
         rows_arr = np.asarray([(h, gb) for h in range(H) for gb in range(NB)], dtype=np.int64)
@@ -89,8 +101,8 @@ def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None,
         k = ks[s]
         gi, gc = gpu["idx"][h, gb], int(gpu["cnt"][h, gb])
         Ns = -(-(cu[s + 1] - cu[s]) // block)
-        rmin, rmax = valid_range(mask, window, q, block, Ns)
-        assert gc == int(rcnt[i]) == min(k, rmax - rmin + 1), (h, gb, gc, int(rcnt[i]))
+        rmin, rmax = valid_range(mask, window, q, block, Ns, block_k, cu[s + 1] - cu[s])
+        assert gc == int(rcnt[i]) == min(k, max(0, rmax - rmin + 1)), (h, gb, gc, int(rcnt[i]))
         assert np.all(gi[gc:] == -1), (h, gb)
         assert np.all(np.diff(gi[:gc]) > 0) and (gc == 0 or (gi[0] >= rmin and gi[gc - 1] <= rmax)), (h, gb)
         Qh = Q[h, cu[s]:cu[s + 1]]
@@ -99,15 +111,17 @@ def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None,
             equal += 1
             if gpu.get("score") is not None:
                 gs = gpu["score"][h, gb]
-                np.testing.assert_allclose(gs[:gc], rscore[i, :gc], rtol=1e-4,
-                                           atol=1e-4 * float(np.abs(rscore[i, :gc]).max()))
+                if gc:
+                    np.testing.assert_allclose(gs[:gc], rscore[i, :gc], rtol=1e-4,
+                                               atol=1e-4 * float(np.abs(rscore[i, :gc]).max()))
                 assert np.all(np.isneginf(gs[gc:]))
         else:
             assert gpu.get("trace") is not None, f"row {(h, gb)} differs and no trace was taken"
             tr = gpu["trace"][:, h, gb, :k, :]
-            n_eff = max(1, math.ceil(math.log2(math.ceil((-(-Qh.shape[0] // block)) / k))))
+            n_key = so.padded_len(Qh.shape[0], block, block_k) // (block_k or block)
+            n_eff = max(1, math.ceil(math.log2(math.ceil(n_key / k))))
             tr = tr[:n_eff]
-            ok, why = certify_row(Qh, Kh, block, k, q, tr, mask=mask, window=window)
+            ok, why = certify_row(Qh, Kh, block, k, q, tr, mask=mask, window=window, block_k=block_k)
             assert ok, f"row (h={h}, block={gb}): {why}; gpu={gi[:gc]} oracle={ridx[i][:gc]}"
             assert list(tr[-1][:gc, 0]) == list(gi[:gc])
             ties += 1
