@@ -233,6 +233,7 @@ def main():
         result["mask_rules"] = mask_rules(w, layers[0], scale)
         result["variable_k"] = variable_k(w, layers[0])
         result["receiver_stats"] = receiver_stats(w, layers[0], scale)
+        result["block_shapes"] = block_shapes(w, layers[0], scale)
     if args.dense_reference and w.batch == 1:
         result["dense_reference"] = dense_reference(w, layers[0])
     if not args.no_cpu_baseline:
@@ -376,6 +377,47 @@ def variable_k(w, layer, reps=3):
     torch.cuda.synchronize()
     return {"rule": f"k(row) = clamp(ceil(valid/64), 1, {kmax})", "prune_ms": e0.elapsed_time(e1) / reps,
             "block_scores": int(st["tiles"].item()), "retained_blocks": int(st["out"]["cnt"].sum().item())}
+
+
+def block_shapes(w, layer, scale, reps=3):
+    """The step with b_q != b_k on the same Q, K, V: k scaled so that every shape keeps the same
+    2048 keys per query row as the headline shape."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, V = layer
+    out = {}
+    for bq, bk in ((32, 128), (128, 32), (64, 128), (128, 64)):
+        k = w.topk[0] * w.block // bk
+        st = {}
+
+        def prune():
+            r = binding.stream_prune(Q, K, w.heads, w.kv_heads, bq, k, workspace=st.get("wp"),
+                                     out=st.get("op"), block_k=bk, want_tiles=True)
+            st["wp"], st["op"], st["tiles"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}, r["tiles"]
+
+        def attn():
+            r = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, bq, st["op"]["idx"], st["op"]["cnt"],
+                                           scale, want_lse=True, want_mass=True, workspace=st.get("wa"),
+                                           out=st.get("oa"), block_k=bk)
+            st["wa"], st["oa"] = r["workspace"], {"O": r["O"], "lse": r["lse"], "mass": r["mass"]}
+
+        res = {"topk": k}
+        for key, fn in (("prune_ms", prune), ("attn_ms", attn)):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res[key] = e0.elapsed_time(e1) / reps
+        res["block_scores"] = int(st["tiles"].item())
+        res["prune_tflops"] = res["block_scores"] * 2.0 * bq * bk * w.head_dim / (res["prune_ms"] * 1e-3) / 1e12
+        out[f"bq{bq}_bk{bk}"] = res
+    return out
 
 
 def receiver_stats(w, layer, scale, reps=2):

@@ -51,6 +51,15 @@ def test_block_geometry(lib):
     assert lib.stream_prune_levels(ctypes.byref(shape(T=4096)), 64, None) == 1
     ks = (ctypes.c_int * 3)(1, 1, 2)
     assert lib.stream_prune_levels(ctypes.byref(s), 0, ks) == 3  # 14 blocks, k=2 -> ceil(log2 7)
+    # b_q != b_k: sequences are padded to a multiple of lcm(b_q, b_k); NB counts query blocks,
+    # the levels follow the key blocks
+    assert lib.stream_num_blocks(ctypes.byref(shape(block=32, block_k=128))) == 32      # T_p = 1024
+    assert lib.stream_num_blocks(ctypes.byref(shape(block=128, block_k=32))) == 8
+    assert lib.stream_num_blocks(ctypes.byref(shape(block=64, block_k=64))) == 16
+    s.block, s.block_k = 32, 128
+    assert lib.stream_num_blocks(ctypes.byref(s)) == 4 + 4 + 28                         # 128, 128, 896
+    assert lib.stream_prune_levels(ctypes.byref(shape(T=131072, block=32, block_k=128)), 16, None) == 6
+    assert lib.stream_prune_levels(ctypes.byref(shape(T=131072, block=128, block_k=32)), 64, None) == 6
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -61,6 +70,8 @@ def test_block_geometry(lib):
     (dict(batch=2), B.STREAM_EINVAL),            # batch > 1 without cu_seqlens
     (dict(head_dim=96), B.STREAM_EUNSUPPORTED),
     (dict(block=48), B.STREAM_EUNSUPPORTED),
+    (dict(block_k=16), B.STREAM_EUNSUPPORTED),
+    (dict(block_k=256), B.STREAM_EUNSUPPORTED),
     (dict(batch=33), B.STREAM_EINVAL),
 ])
 def test_bad_shapes_are_rejected_on_the_host(lib, kw, code):
@@ -185,6 +196,7 @@ def test_bad_arguments_of_receiver_stats(lib):
     assert call(wsz=need - 1) == B.STREAM_EWORKSPACE
     assert call(wsp=None) == B.STREAM_EWORKSPACE
     assert call(sh=shape(dtype=B.STREAM_F32, head_dim=128, block=128)) == B.STREAM_EUNSUPPORTED
+    assert call(sh=shape(block_k=128)) == B.STREAM_EUNSUPPORTED              # b_q != b_k
     assert lib.stream_receiver_stats_workspace_bytes(ctypes.byref(shape(block=48))) == 0
 
 

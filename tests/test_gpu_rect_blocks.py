@@ -151,3 +151,52 @@ def test_attention_ragged_batch():
     attn_case(w, 128)
     w = workload((700, 1300, 64, 33, 2049), (2, 3, 1, 4, 2), 128, heads=14, kv_heads=2, cfg=5, anchors_per_seq=3)
     attn_case(w, 64, "sliding", 300)
+
+
+@pytest.mark.parametrize("bq,bk,k", [(32, 128, 16), (128, 32, 64)])
+def test_config3_shape_sampled(bq, bk, k):
+    """T = 131072, 32/8 heads, d = 128, bf16 with b_q != b_k: sampled rows against the oracle
+    (lists, scores, and Eq. (2) on the library's own lists), count law over every row."""
+    w = wl.scaled(wl.config(3), (131072,), topk=k, block=bq)
+    dev = torch.device(DEV)
+    print(f"[rect-full] {w.name} b_q={bq} b_k={bk} k={k}: generating inputs", flush=True)
+    Q, K, V, _ = wl.make_inputs(w, device=dev)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    out = binding.stream_prune(Q, K, w.heads, w.kv_heads, bq, k, want_score=True, want_trace=True, block_k=bk)
+    att = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, bq, out["idx"], out["cnt"], scale,
+                                     want_lse=True, want_mass=True, block_k=bk)
+    torch.cuda.synchronize()
+    T = w.T
+    NQ = T // bq
+    cnt = out["cnt"]
+    valid = (torch.arange(NQ, device=dev) * bq + bq - 1) // bk + 1
+    assert torch.equal(cnt, torch.clamp(valid, max=k).to(torch.int32)[None, :].expand_as(cnt))
+    np.testing.assert_allclose(att["mass"].sum(dim=1).cpu().numpy(), float(T), rtol=2e-4)
+    rng = np.random.default_rng(bq + bk)
+    g = w.heads // w.kv_heads
+    idx_c, cnt_c, score_c = out["idx"].cpu().numpy(), cnt.cpu().numpy(), out["score"].cpu().numpy()
+    trace_c = out["trace"].cpu().numpy()
+    equal = ties = 0
+    worst_o = worst_l = 0.0
+    for h in (3, 28):
+        Qh, Kh, Vh = Q[h].float().cpu().numpy(), K[h // g].float().cpu().numpy(), V[h // g].float().cpu().numpy()
+        qs = sorted({0, 1, k - 1, k, NQ // 2, NQ - 1} | set(int(x) for x in rng.integers(0, NQ, size=6)))
+        for q in qs:
+            r = so.prune_head(Qh, Kh, bq, k, qblocks=[q], block_k=bk)
+            c = int(r["cnt"][0])
+            if np.array_equal(r["idx"][0], idx_c[h, q, :k]):
+                equal += 1
+                np.testing.assert_allclose(score_c[h, q, :c], r["score"][0, :c], rtol=1e-4)
+            else:
+                n_eff = max(1, math.ceil(math.log2(math.ceil((T // bk) / k))))
+                ok, why = parity.certify_row(Qh, Kh, bq, k, q, trace_c[:n_eff, h, q, :k], block_k=bk)
+                assert ok, (h, q, why)
+                ties += 1
+            gi = np.ascontiguousarray(idx_c[h, q][None, :])
+            gc = np.ascontiguousarray(cnt_c[h, q][None])
+            ra = so.sparse_attn(Qh[None], Kh[None], Vh[None], 1, 1, bq, gi, gc, scale, rows=[(0, q)], block_k=bk)
+            t0, t1 = q * bq, (q + 1) * bq
+            worst_o = max(worst_o, float(np.abs(att["O"][h, t0:t1].float().cpu().numpy() - ra["O"][0, t0:t1]).max()))
+            worst_l = max(worst_l, float(np.abs(att["lse"][h, t0:t1].cpu().numpy() - ra["lse"][0, t0:t1]).max()))
+    print(f"[rect-full] equal={equal} ties={ties} max|dO|={worst_o:.3e} max|dlse|={worst_l:.3e}", flush=True)
+    assert worst_o <= 2e-2 and worst_l <= 1e-3 and ties <= 2
