@@ -13,16 +13,20 @@ probability matrix of one (head, sequence) in memory:
              n_q, n_k the real tokens of the two blocks (a hidden pair counts as probability 0);
              defined where block j is valid for block i (C^blk[i, j] = 1 in the notation of
              Alg. 2), 0 elsewhere
+  (b_q and b_k may differ: the sequence is then padded to a multiple of lcm(b_q, b_k) as in the
+   preamble of Alg. 2, M is T_p / b_q by T_p / b_k, and a block of padding only is never valid)
   column j : the values M[i, j] over the valid i ("vertical" = along the query axis);
              col_mean[j] their mean (the vertical score of block j), col_kurt[j] their excess
              kurtosis m4 / m2^2 - 3 with biased central moments, 0 when there are fewer than
              4 values or no spread
   head     : max_kurt = max of col_kurt over the columns with at least 4 values (0 if none);
-             vert_kurt = excess kurtosis of col_mean over all columns of the sequence (0 for
-             fewer than 4 columns): the per-head statistic of the thought-anchors work the
+             vert_kurt = excess kurtosis of col_mean over the columns of the sequence that
+             hold a real key (0 for fewer than 4 columns): the per-head statistic of the thought-anchors work the
              section follows, with blocks in place of sentences.
 """
 from __future__ import annotations
+
+import math
 
 import numpy as np
 
@@ -54,19 +58,23 @@ def dense_probabilities(Qh: np.ndarray, Kh: np.ndarray, scale: float, mask: str 
     return E / E.sum(axis=1, keepdims=True)
 
 
-def block_means(P: np.ndarray, block: int, mask: str = "causal", window: int = 0):
-    """(M [N, N], Cblk [N, N] bool) of one L x L probability matrix."""
+def block_means(P: np.ndarray, block: int, mask: str = "causal", window: int = 0, block_k=None):
+    """(M [T_p / b_q, T_p / b_k], Cblk of the same shape) of one L x L probability matrix:
+    spans of b_q = block queries by b_k = block_k keys (default b_k = b_q); T_p is L rounded up
+    to a multiple of lcm(b_q, b_k) as in the preamble of Alg. 2."""
     L = P.shape[0]
-    N = -(-L // block)
-    pad = N * block - L
-    Pp = np.pad(P, ((0, pad), (0, pad)))
-    sums = Pp.reshape(N, block, N, block).sum(axis=(1, 3))
-    n_tok = np.minimum(block, L - np.arange(N) * block).astype(np.float64)
-    t = np.arange(N * block)
+    bq, bk = block, (block_k or block)
+    ell = bq * bk // math.gcd(bq, bk)
+    Tp = -(-L // ell) * ell
+    Pp = np.pad(P, ((0, Tp - L), (0, Tp - L)))
+    sums = Pp.reshape(Tp // bq, bq, Tp // bk, bk).sum(axis=(1, 3))
+    nq = np.clip(L - np.arange(Tp // bq) * bq, 0, bq).astype(np.float64)   # real tokens per block
+    nk = np.clip(L - np.arange(Tp // bk) * bk, 0, bk).astype(np.float64)
+    t = np.arange(Tp)
     real = t < L
     C = visible(mask, window, t[:, None], t[None, :]) & real[:, None] & real[None, :]
-    Cblk = C.reshape(N, block, N, block).any(axis=(1, 3))
-    M = np.where(Cblk, sums / np.outer(n_tok, n_tok), 0.0)
+    Cblk = C.reshape(Tp // bq, bq, Tp // bk, bk).any(axis=(1, 3))
+    M = np.where(Cblk, sums / np.maximum(np.outer(nq, nk), 1.0), 0.0)
     return M, Cblk
 
 
@@ -102,50 +110,54 @@ def head_stats(col_mean: np.ndarray, col_kurt: np.ndarray, col_n: np.ndarray):
     """(max_kurt, vert_kurt) of one (head, sequence)."""
     enough = col_n >= 4
     max_kurt = float(col_kurt[enough].max()) if enough.any() else 0.0
-    return max_kurt, excess_kurtosis(col_mean)
+    # (a key block of padding only - possible when b_k < b_q - is no column of the pattern)
+    return max_kurt, excess_kurtosis(np.asarray(col_mean)[np.asarray(col_n) > 0])
 
 
 def receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: float, cu_seqlens=None,
-                   mask: str = "causal", window: int = 0, want_block_mean: bool = True):
+                   mask: str = "causal", window: int = 0, want_block_mean: bool = True, block_k=None):
     """Q [heads, T, d], K [kv_heads, T, d].  Returns a dict with
-    block_mean [heads, NB, NB] (global block ids, zero across sequences; None if not wanted),
-    col_mean, col_kurt [heads, NB], head [heads, batch, 2] = (max_kurt, vert_kurt)."""
+    block_mean [heads, NBq, NBk] (global block ids, zero across sequences; None if not wanted),
+    col_mean, col_kurt [heads, NBk], head [heads, batch, 2] = (max_kurt, vert_kurt); NBq / NBk
+    count the query / key blocks of all sequences (equal when b_q = b_k)."""
     Q = np.asarray(Q)
     K = np.asarray(K)
     T = Q.shape[1]
+    bq, bk = block, (block_k or block)
+    ell = bq * bk // math.gcd(bq, bk)
     cu = [0, T] if cu_seqlens is None else [int(c) for c in cu_seqlens]
-    nblk = [-(-(cu[s + 1] - cu[s]) // block) for s in range(len(cu) - 1)]
-    blk0 = np.concatenate([[0], np.cumsum(nblk)]).astype(int)
-    NB = int(blk0[-1])
+    tp = [-(-(cu[s + 1] - cu[s]) // ell) * ell for s in range(len(cu) - 1)]
+    q0 = np.concatenate([[0], np.cumsum([t // bq for t in tp])]).astype(int)
+    k0 = np.concatenate([[0], np.cumsum([t // bk for t in tp])]).astype(int)
     g = heads // kv_heads
-    bm = np.zeros((heads, NB, NB)) if want_block_mean else None
-    cm = np.zeros((heads, NB))
-    ck = np.zeros((heads, NB))
-    hs = np.zeros((heads, len(nblk), 2))
+    bm = np.zeros((heads, q0[-1], k0[-1])) if want_block_mean else None
+    cm = np.zeros((heads, k0[-1]))
+    ck = np.zeros((heads, k0[-1]))
+    hs = np.zeros((heads, len(tp), 2))
     for h in range(heads):
-        for s in range(len(nblk)):
+        for s in range(len(tp)):
             a, e = cu[s], cu[s + 1]
             P = dense_probabilities(Q[h, a:e], K[h // g, a:e], scale, mask, window)
-            M, Cblk = block_means(P, block, mask, window)
+            M, Cblk = block_means(P, bq, mask, window, bk)
             mean, kurt, n = column_stats(M, Cblk)
-            lo, hi = blk0[s], blk0[s + 1]
             if bm is not None:
-                bm[h, lo:hi, lo:hi] = M
-            cm[h, lo:hi] = mean
-            ck[h, lo:hi] = kurt
+                bm[h, q0[s]:q0[s + 1], k0[s]:k0[s + 1]] = M
+            cm[h, k0[s]:k0[s + 1]] = mean
+            ck[h, k0[s]:k0[s + 1]] = kurt
             hs[h, s] = head_stats(mean, kurt, n)
     return {"block_mean": bm, "col_mean": cm, "col_kurt": ck, "head": hs}
 
 
 def block_mean_entry(Qh, Kh, block: int, scale: float, i: int, j: int, mask: str = "causal",
-                     window: int = 0) -> float:
+                     window: int = 0, block_k=None) -> float:
     """M[i, j] of one head and one sequence from the rows of block i alone (no L x L matrix):
     for checks at sizes where the dense pattern does not fit in memory."""
     Qh = np.asarray(Qh)
     Kh = np.asarray(Kh, dtype=np.float64)
     L = Qh.shape[0]
+    bk = block_k or block
     q0, q1 = i * block, min(L, (i + 1) * block)
-    k0, k1 = j * block, min(L, (j + 1) * block)
+    k0, k1 = j * bk, min(L, (j + 1) * bk)
     S = scale * (np.asarray(Qh[q0:q1], dtype=np.float64) @ Kh.T)
     C = visible(mask, window, np.arange(q0, q1)[:, None], np.arange(L)[None, :])
     S = np.where(C, S, -np.inf)

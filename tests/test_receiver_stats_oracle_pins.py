@@ -190,3 +190,36 @@ def test_packed_batch_gqa_and_entry_helper():
             for (i, j) in ((nblk[s] - 1, nblk[s] - 1), (nblk[s] - 1, nblk[s] - 2), (2, 1)):
                 got = rs.block_mean_entry(Q[h, a:e], K[h // 2, a:e], b, 0.3, i, j, "sliding", 20)
                 assert got == pytest.approx(alone["block_mean"][0][i, j], rel=1e-12, abs=1e-300)
+
+
+def test_rectangular_spans_are_weighted_means_of_square_ones():
+    # a span of 2b queries is the union of two spans of b queries (likewise for keys): its mean is
+    # the mean of the two, weighted by their real tokens; and every real query's row still sums to 1
+    rng = np.random.default_rng(12)
+    L, b = 45, 4
+    Q, K = rng.standard_normal((L, 5)), rng.standard_normal((L, 5))
+    for mask, w in (("causal", 0), ("sliding", 11), ("full", 0)):
+        P = rs.dense_probabilities(Q, K, 0.6, mask, w)
+        Ms, Cs = rs.block_means(P, b, mask, w)                       # square, 12 x 12 (T_p = 48)
+        n = np.clip(L - np.arange(12) * b, 0, b)
+        Mq, Cq = rs.block_means(P, 2 * b, mask, w, block_k=b)        # 6 x 12
+        Mk, Ck = rs.block_means(P, b, mask, w, block_k=2 * b)        # 12 x 6
+        assert Mq.shape == (6, 12) and Mk.shape == (12, 6)
+        for i in range(6):
+            for j in range(12):
+                num = Ms[2 * i, j] * n[2 * i] + Ms[2 * i + 1, j] * n[2 * i + 1]
+                assert Mq[i, j] == pytest.approx(num / max(n[2 * i] + n[2 * i + 1], 1), rel=1e-12, abs=1e-300)
+                assert Cq[i, j] == (Cs[2 * i, j] or Cs[2 * i + 1, j])
+        for i in range(12):
+            for j in range(6):
+                num = Ms[i, 2 * j] * n[2 * j] + Ms[i, 2 * j + 1] * n[2 * j + 1]
+                assert Mk[i, j] == pytest.approx(num / max(n[2 * j] + n[2 * j + 1], 1), rel=1e-12, abs=1e-300)
+                assert Ck[i, j] == (Cs[i, 2 * j] or Cs[i, 2 * j + 1])
+        np.testing.assert_allclose(Mq @ n, np.where(np.arange(6) * 2 * b < L, 1.0, 0.0), rtol=1e-12)
+    # lcm padding: b_q = 2, b_k = 8, L = 5 -> T_p = 8: four query blocks (the last is padding), one key block
+    M, C = rs.block_means(rs.dense_probabilities(Q[:5], K[:5], 1.0), 2, block_k=8)
+    assert M.shape == (4, 1) and C[:, 0].tolist() == [True, True, True, False] and M[3, 0] == 0
+    out = rs.receiver_stats(Q[None], K[None], 1, 1, 2, 1.0, block_k=8)
+    assert out["block_mean"].shape == (1, 23 * 4 // 4 + 1, 6)        # T_p = 48: 24 x 6
+    got = rs.block_mean_entry(Q, K, 2, 1.0, 9, 2, block_k=8)
+    assert got == pytest.approx(out["block_mean"][0, 9, 2], rel=1e-12)
