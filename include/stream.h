@@ -37,8 +37,7 @@
  *   - b_q = shape.block, b_k = shape.block_k (0 = b_q); the mask C is one of the rules of
  *     stream_mask (a zero-initialised shape means causal, b_k = b_q).  A key block is valid for
  *     a query block when at least one of its real keys is visible to one of the block's real
- *     queries.  stream_prune*, stream_sparse_attn take b_q != b_k; stream_receiver_stats
- *     does not (STREAM_EUNSUPPORTED).
+ *     queries.
  *   - Every entry point validates its arguments on the host before any launch
  *     and returns a stream_status; nothing is thrown or logged.  Outputs are
  *     fully overwritten on STREAM_OK and untouched on an argument error.
@@ -112,6 +111,9 @@ typedef struct {
 
 /* NB = total number of query blocks of the (packed) shape, or -1 on a bad shape. */
 long long stream_num_blocks(const stream_shape *shape);
+
+/* NBk = total number of key blocks (sum over sequences of T_p / b_k; = NB when b_q = b_k), or -1. */
+long long stream_num_key_blocks(const stream_shape *shape);
 
 /* Number of refinement levels stream_prune runs for these arguments (max over sequences):
    max(1, ceil(log2(ceil(N_s / k_s)))).  The listing's n_it = ceil(log2 N) iterations give the
@@ -279,17 +281,18 @@ stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *
  *             central moments; 0 with fewer than 4 values or no spread)
  *
  *   scale       as stream_sparse_attn (> 0, finite)
- *   block_mean  float [heads, NB, NB] (query block, key block; global block ids) or NULL;
- *               zero outside the valid blocks and across sequences of a packed batch
- *   col_mean    float [heads, NB]
- *   col_kurt    float [heads, NB]
+ *   block_mean  float [heads, NB, NBk] (query block, key block; global block ids; NBk =
+ *               stream_num_key_blocks(), = NB when b_q = b_k) or NULL; zero outside the valid
+ *               blocks and across sequences of a packed batch
+ *   col_mean    float [heads, NBk]
+ *   col_kurt    float [heads, NBk]
  *   head_stats  float [heads, batch, 2]: [0] the maximum of col_kurt over the sequence's columns
  *               with at least 4 values (0 if there is none), [1] the excess kurtosis of
- *               col_mean over the sequence's columns (0 for fewer than 4 columns)
+ *               col_mean over the sequence's columns that hold a real key (0 for fewer than 4)
  *   workspace   stream_receiver_stats_workspace_bytes(shape) bytes (packed Q and K, one float
  *               per padded token and head), 256-byte aligned
  * The moments are accumulated in fp64 from the fp32 block means.  Errors: as stream_prune;
- * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and block 128, and for b_q != b_k.
+ * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and b_k = 128.
  */
 size_t stream_receiver_stats_workspace_bytes(const stream_shape *shape);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libstream_hip.so")
 STREAM_OK, STREAM_EINVAL, STREAM_EUNSUPPORTED, STREAM_EWORKSPACE, STREAM_EDEVICE = range(5)
 STREAM_F32, STREAM_BF16 = 0, 1
 
-EXPORTS = ["stream_num_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
+EXPORTS = ["stream_num_blocks", "stream_num_key_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
            "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
            "stream_prune_multi_workspace_bytes", "stream_prune_multi", "stream_prune_variable",
            "stream_select_update", "stream_mask_diff", "stream_receiver_stats_workspace_bytes",
@@ -64,6 +64,8 @@ def load():
     vp, ip = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)
     lib.stream_num_blocks.restype = ctypes.c_longlong
     lib.stream_num_blocks.argtypes = [sp]
+    lib.stream_num_key_blocks.restype = ctypes.c_longlong
+    lib.stream_num_key_blocks.argtypes = [sp]
     lib.stream_prune_levels.restype = ctypes.c_int
     lib.stream_prune_levels.argtypes = [sp, ctypes.c_int, ip]
     lib.stream_prune_workspace_bytes.restype = ctypes.c_size_t
@@ -387,10 +389,10 @@ def stream_mask_diff(idx_a, cnt_a, score_a, idx_b, cnt_b, want_weight: bool = Tr
 
 def stream_receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: float, cu_seqlens=None,
                           want_block_mean: bool = False, workspace=None, out=None, mask="causal",
-                          window: int = 0):
+                          window: int = 0, block_k: int = 0):
     """Block means of the dense attention pattern and their vertical kurtosis (Section 4.1).
 
-    Returns dict(block_mean [H, NB, NB] or None, col_mean [H, NB], col_kurt [H, NB],
+    Returns dict(block_mean [H, NB, NBk] or None, col_mean [H, NBk], col_kurt [H, NBk],
     head [H, batch, 2] = (max column kurtosis, kurtosis of the column means))."""
     lib = load()
     if not (Q.is_cuda and K.is_cuda):
@@ -398,15 +400,16 @@ def stream_receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: fl
     H, T, d = Q.shape
     dev = Q.device
     shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
-                             mask=mask, window=window)
+                             mask=mask, window=window, block_k=block_k)
     NB = lib.stream_num_blocks(ctypes.byref(shape))
-    if NB < 0:
+    NBk = lib.stream_num_key_blocks(ctypes.byref(shape))
+    if NB < 0 or NBk < 0:
         raise StreamError(1, "stream_num_blocks")
     batch = shape.batch
     if out is None:
-        bm = torch.empty((H, NB, NB), dtype=torch.float32, device=dev) if want_block_mean else None
-        cm = torch.empty((H, NB), dtype=torch.float32, device=dev)
-        ck = torch.empty((H, NB), dtype=torch.float32, device=dev)
+        bm = torch.empty((H, NB, NBk), dtype=torch.float32, device=dev) if want_block_mean else None
+        cm = torch.empty((H, NBk), dtype=torch.float32, device=dev)
+        ck = torch.empty((H, NBk), dtype=torch.float32, device=dev)
         hs = torch.empty((H, batch, 2), dtype=torch.float32, device=dev)
     else:
         bm, cm, ck, hs = out.get("block_mean"), out["col_mean"], out["col_kurt"], out["head"]

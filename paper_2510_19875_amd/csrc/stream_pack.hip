@@ -158,6 +158,13 @@ long long stream_num_blocks(const stream_shape *shape)
     return pb.NB;
 }
 
+long long stream_num_key_blocks(const stream_shape *shape)
+{
+    stream::Problem pb;
+    if (stream::make_problem(shape, 0, nullptr, 0, &pb) != STREAM_OK) return -1;
+    return (long long)pb.NB * pb.b / pb.bk;
+}
+
 int stream_prune_levels(const stream_shape *shape, int topk, const int *topk_per_seq)
 {
     stream::Problem pb;

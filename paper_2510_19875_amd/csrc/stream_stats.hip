@@ -20,26 +20,42 @@ namespace stream {
 struct StatsParams {
     const char *Qp, *Kp;        // packed fragments: [heads | kv_heads][global block][b * d]
     float *lse2;                // [heads, NB * b]: log2-domain log-sum-exp per (padded) query
-    float *block_mean;          // nullable [heads, NB, NB]
-    float *col_mean, *col_kurt; // [heads, NB]
+    float *block_mean;          // nullable [heads, NB, NBk]
+    float *col_mean, *col_kurt; // [heads, NBk]
     float *head_stats;          // [heads, batch, 2]
     float c;                    // scale * log2(e)
-    int H, g, NB, b;
+    int H, g, NB, b;            // NB query blocks of b = b_q tokens
+    int NBk, bk;                // NBk key blocks of b_k tokens (NB * b = NBk * bk padded tokens)
     int mask, window;
     WgMap map;
     SeqTable seqs;
 };
 
-// Query blocks that can see key block j of an N-block sequence: imin .. imax (contiguous for
-// all three mask rules; the counterpart of mask_rmin / mask_rmax).
-__host__ __device__ __forceinline__ int mask_imin(int mask, int j) { return mask == STREAM_MASK_FULL ? 0 : j; }
-
-__host__ __device__ __forceinline__ int mask_imax(int mask, int window, int j, int b, int N)
+// Query blocks (of bq tokens) that can see key block j (of bk tokens) of a sequence of L tokens:
+// imin .. imax, contiguous for all three mask rules (the counterpart of mask_rmin / mask_rmax);
+// imin > imax for a key block of padding only.
+__host__ __device__ __forceinline__ void mask_irange(int mask, int window, int j, int bq, int bk, int L,
+                                                     int &imin, int &imax)
 {
-    if (mask != STREAM_MASK_SLIDING) return N - 1;
-    // the last key of the block, j*b + b - 1, is seen by queries < j*b + b - 1 + window
-    const long long hi = ((long long)(j + 1) * b + window - 2) / b;
-    return (int)(hi < N - 1 ? hi : N - 1);
+    const long long k_first = (long long)j * bk;
+    if (k_first >= L) { imin = 0; imax = -1; return; }
+    // causal rules: the first query block whose last query is at or after the block's first key
+    imin = mask == STREAM_MASK_FULL ? 0 : (int)(k_first / bq);
+    long long hi = ((long long)L - 1) / bq;                       // last query block with a real token
+    if (mask == STREAM_MASK_SLIDING) {
+        // the block's last key, j*bk + bk - 1, is seen by queries < j*bk + bk - 1 + window
+        const long long w = (k_first + bk + window - 2) / bq;
+        hi = w < hi ? w : hi;
+    }
+    imax = (int)hi;
+}
+
+// Sequence that owns global key block gk (key blocks are counted like query blocks, per sequence).
+__device__ __forceinline__ int seq_of_key_block(const SeqTable &t, int gk, int bq, int bk)
+{
+    int s = 0;
+    while (s + 1 < t.n && gk >= (int)((long long)t.d[s + 1].blk0 * bq / bk)) ++s;
+    return s;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -186,29 +202,30 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int FR = D * ES / 32;
     constexpr int GROUP_BYTES = 32 * D * ES;
-    constexpr int B = 32 * NG;
+    constexpr int BK = 32 * NG;                     // key block b_k
     constexpr int QT = 32 * NS;
-    static_assert(QT * TPB == B, "a query block is TPB streamed tiles");
+    constexpr int BQ = QT * TPB;                    // query block b_q = TPB streamed tiles
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int kvh, slot;
     if (!wg_decode(p.map, blockIdx.x, kvh, slot)) return;
-    const long long items_per_kv = (long long)p.NB * p.g;
+    const long long items_per_kv = (long long)p.NBk * p.g;
     const long long rk = (long long)slot * 4 + wave;
     if (rk >= items_per_kv) return;
-    const int gbj = (int)(rk / p.g);                // causal: early columns are the long ones
+    const int gbj = (int)(rk / p.g);                // global key block; causal: early columns are the long ones
     const int h = kvh * p.g + (int)(rk % p.g);
-    const SeqDesc sd = p.seqs.d[seq_of_block(p.seqs, gbj)];
-    const int L = sd.len, N = sd.nblk;
-    const int j = gbj - sd.blk0;
-    const int tk0 = j * B;
+    const SeqDesc sd = p.seqs.d[seq_of_key_block(p.seqs, gbj, BQ, BK)];
+    const int L = sd.len;
+    const int kblk0 = (int)((long long)sd.blk0 * BQ / BK);
+    const int j = gbj - kblk0;
+    const int tk0 = j * BK;
     const unsigned lane_off = lane * 16;
-    const long long seq_bytes = (long long)N * B * D * ES;
+    const long long seq_bytes = (long long)sd.nblk * BQ * D * ES;
     const __amdgpu_buffer_rsrc_t qrs = make_tile_rsrc(
-        p.Qp + ((long long)h * p.NB + sd.blk0) * B * D * ES, (unsigned)seq_bytes);
+        p.Qp + ((long long)h * p.NB + sd.blk0) * BQ * D * ES, (unsigned)seq_bytes);
     const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(
-        p.Kp + ((long long)kvh * p.NB + sd.blk0) * B * D * ES, (unsigned)seq_bytes);
-    const float *lse_seq = p.lse2 + (long long)h * p.NB * B + (long long)sd.blk0 * B;
+        p.Kp + ((long long)kvh * p.NB + sd.blk0) * BQ * D * ES, (unsigned)seq_bytes);
+    const float *lse_seq = p.lse2 + (long long)h * p.NB * BQ + (long long)sd.blk0 * BQ;
 
     uint4 kf[NG][FR];
 #pragma unroll
@@ -217,9 +234,14 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
         for (int fr = 0; fr < FR; ++fr)
             kf[kg][fr] = load_frag(krs, lane_off, (unsigned)(j * NG + kg) * GROUP_BYTES, fr);
 
-    const int imin = mask_imin(p.mask, j), imax = mask_imax(p.mask, p.window, j, B, N);
-    const int nk = L - tk0 < B ? L - tk0 : B;       // real keys of the block
-    float *bm = p.block_mean ? p.block_mean + ((long long)h * p.NB + sd.blk0) * p.NB + gbj : nullptr;
+    int imin, imax;
+    mask_irange(p.mask, p.window, j, BQ, BK, L, imin, imax);
+    if (imin > imax) {                              // a key block of padding only: no column
+        if (lane == 0) { p.col_mean[(long long)h * p.NBk + gbj] = 0.f; p.col_kurt[(long long)h * p.NBk + gbj] = 0.f; }
+        return;
+    }
+    const int nk = L - tk0 < BK ? L - tk0 : BK;     // real keys of the block
+    float *bm = p.block_mean ? p.block_mean + ((long long)h * p.NB + sd.blk0) * p.NBk + gbj : nullptr;
 
     // power sums of the column's means, in fp64, shifted by the column's first value (the
     // diagonal block) so that the central moments formed from them at the end lose nothing that
@@ -229,7 +251,7 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
     uint4 qf[NS][FR];
     float lq[NS];
     {
-        const int tq0 = imin * B;
+        const int tq0 = imin * BQ;
 #pragma unroll
         for (int fr = 0; fr < FR; ++fr)
 #pragma unroll
@@ -243,7 +265,7 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
     const int n_tiles = (imax - imin + 1) * TPB;
     float psum = 0.f;
     for (int t = 0; t < n_tiles; ++t) {
-        const int tq0 = imin * B + t * QT;
+        const int tq0 = imin * BQ + t * QT;
         const int tqn = t + 1 < n_tiles ? tq0 + QT : tq0;
         const unsigned nxt = (unsigned)(tqn / 32) * GROUP_BYTES;
         floatx16 acc[NG][NS];
@@ -271,8 +293,8 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
             lcur[qs] = lq[qs];
             lq[qs] = lse_seq[tqn + qs * 32 + (lane & 31)];
         }
-        const bool cut = (tq0 + QT > L) | (tk0 + B > L) |
-                         ((p.mask != STREAM_MASK_FULL) & (tk0 + B - 1 > tq0)) |
+        const bool cut = (tq0 + QT > L) | (tk0 + BK > L) |
+                         ((p.mask != STREAM_MASK_FULL) & (tk0 + BK - 1 > tq0)) |
                          ((p.mask == STREAM_MASK_SLIDING) & (tq0 + QT - 1 - tk0 >= p.window));
 #pragma unroll
         for (int kg = 0; kg < NG; ++kg)
@@ -292,10 +314,10 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
         if ((t + 1) % TPB == 0) {
             // a b x b span is complete: its mean over the real token pairs
             const int i_blk = imin + t / TPB;
-            const int nq = L - i_blk * B < B ? L - i_blk * B : B;
+            const int nq = L - i_blk * BQ < BQ ? L - i_blk * BQ : BQ;
             const float mval = wave_sum(psum) / (float)(nq * nk);
             psum = 0.f;
-            if (bm && lane == 0) bm[(long long)i_blk * p.NB] = mval;
+            if (bm && lane == 0) bm[(long long)i_blk * p.NBk] = mval;
             const double x = (double)mval;
             if (t + 1 == TPB) x0 = x;
             const double y = x - x0, y2 = y * y;
@@ -306,7 +328,7 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
         }
     }
     if (lane == 0) {
-        const long long o = (long long)h * p.NB + gbj;
+        const long long o = (long long)h * p.NBk + gbj;
         const double cn = (double)(imax - imin + 1);
         const double mu = s1 / cn;                                  // mean of the shifted values
         const double m2 = s2 / cn - mu * mu;
@@ -331,15 +353,18 @@ __global__ void __launch_bounds__(64) stats_heads_kernel(const StatsParams p)
     const int lane = threadIdx.x;
     const int h = blockIdx.x / p.seqs.n, s = blockIdx.x % p.seqs.n;
     const SeqDesc sd = p.seqs.d[s];
-    const int N = sd.nblk;
-    const float *cm = p.col_mean + (long long)h * p.NB + sd.blk0;
-    const float *ck = p.col_kurt + (long long)h * p.NB + sd.blk0;
+    const int L = sd.len;
+    const int N = (L + p.bk - 1) / p.bk;            // columns: the key blocks that hold a real key
+    const long long kblk0 = (long long)sd.blk0 * p.b / p.bk;
+    const float *cm = p.col_mean + (long long)h * p.NBk + kblk0;
+    const float *ck = p.col_kurt + (long long)h * p.NBk + kblk0;
     double s1 = 0.0;
     float mx = -INFINITY;
     for (int j = lane; j < N; j += 64) {
         s1 += (double)cm[j];
-        const int n = mask_imax(p.mask, p.window, j, p.b, N) - mask_imin(p.mask, j) + 1;
-        if (n >= 4) mx = fmaxf(mx, ck[j]);
+        int imin, imax;
+        mask_irange(p.mask, p.window, j, p.b, p.bk, L, imin, imax);
+        if (imax - imin + 1 >= 4) mx = fmaxf(mx, ck[j]);
     }
     const double mean = wave_sum_f64(s1) / (double)N;
     double c2 = 0.0, c4 = 0.0;
@@ -380,22 +405,31 @@ static StatsWorkspace stats_layout(const Problem &pb)
 
 typedef void (*stats_fn)(const StatsParams);
 
-template <bool BF16, int D>
-static void pick_stats_kernels_t(int b, stats_fn &rows, stats_fn &cols)
+template <bool BF16, int D, int NS, int TPB>
+static stats_fn pick_stats_cols_bk(int bk)
 {
     constexpr int OCC = (BF16 || D == 64) ? 2 : 1;   // fp32 with d = 128 holds 16 fragments per group
-    if (b == 32) {
+    if (bk == 32) return stats_cols_kernel<BF16, D, 1, NS, TPB, OCC>;
+    if (bk == 64) return stats_cols_kernel<BF16, D, 2, NS, TPB, OCC>;
+    if constexpr (BF16 || D == 64)
+        return stats_cols_kernel<BF16, D, 4, NS, TPB, 1>;
+    else
+        return nullptr;                              // 128 keys of fp32 x 128 do not fit a wavefront's registers
+}
+
+template <bool BF16, int D>
+static void pick_stats_kernels_t(int bq, int bk, stats_fn &rows, stats_fn &cols)
+{
+    constexpr int OCC = (BF16 || D == 64) ? 2 : 1;
+    if (bq == 32) {
         rows = stats_rows_kernel<BF16, D, 1, OCC>;
-        cols = stats_cols_kernel<BF16, D, 1, 1, 1, OCC>;
-    } else if (b == 64) {
+        cols = pick_stats_cols_bk<BF16, D, 1, 1>(bk);
+    } else if (bq == 64) {
         rows = stats_rows_kernel<BF16, D, 2, OCC>;
-        cols = stats_cols_kernel<BF16, D, 2, 2, 1, OCC>;
+        cols = pick_stats_cols_bk<BF16, D, 2, 1>(bk);
     } else {
         rows = stats_rows_kernel<BF16, D, 2, OCC>;
-        if constexpr (BF16 || D == 64)
-            cols = stats_cols_kernel<BF16, D, 4, 2, 2, 1>;
-        else
-            cols = nullptr;                          // 128 keys of fp32 x 128 do not fit a wavefront's registers
+        cols = pick_stats_cols_bk<BF16, D, 2, 2>(bk);
     }
 }
 
@@ -422,7 +456,6 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     Problem pb;
     stream_status rc = make_problem(shape, 0, nullptr, 0, &pb);
     if (rc != STREAM_OK) return rc;
-    if (pb.bk != pb.b) return STREAM_EUNSUPPORTED;
     const long long q_sh = shape->q_stride_h ? shape->q_stride_h : pb.T * pb.d;
     const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;
     const long long k_sh = shape->k_stride_h ? shape->k_stride_h : pb.T * pb.d;
@@ -432,11 +465,11 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
     stats_fn rows = nullptr, cols = nullptr;
     if (pb.dtype == STREAM_BF16) {
-        if (pb.d == 128) pick_stats_kernels_t<true, 128>(pb.b, rows, cols);
-        else pick_stats_kernels_t<true, 64>(pb.b, rows, cols);
+        if (pb.d == 128) pick_stats_kernels_t<true, 128>(pb.b, pb.bk, rows, cols);
+        else pick_stats_kernels_t<true, 64>(pb.b, pb.bk, rows, cols);
     } else {
-        if (pb.d == 128) pick_stats_kernels_t<false, 128>(pb.b, rows, cols);
-        else pick_stats_kernels_t<false, 64>(pb.b, rows, cols);
+        if (pb.d == 128) pick_stats_kernels_t<false, 128>(pb.b, pb.bk, rows, cols);
+        else pick_stats_kernels_t<false, 64>(pb.b, pb.bk, rows, cols);
     }
     if (!rows || !cols) return STREAM_EUNSUPPORTED;
     const StatsWorkspace w = stats_layout(pb);
@@ -460,12 +493,13 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     p.col_mean = col_mean; p.col_kurt = col_kurt; p.head_stats = head_stats;
     p.c = scale * 1.4426950408889634f;
     p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.b = pb.b;
+    p.bk = pb.bk; p.NBk = (int)((long long)pb.NB * pb.b / pb.bk);
     p.mask = pb.mask; p.window = pb.window;
     p.seqs = pb.seqs;
 
     if (block_mean) {
         // entries no kernel writes (blocks the mask hides, pairs of different sequences) are zero
-        const long long n = (long long)pb.H * pb.NB * pb.NB;
+        const long long n = (long long)pb.H * pb.NB * p.NBk;
         const long long wgs = (n + 255) / 256;
         hipLaunchKernelGGL(stats_zero_kernel, dim3((unsigned)(wgs < 8192 ? wgs : 8192)), dim3(256), 0, st,
                            block_mean, n);
@@ -474,7 +508,7 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
 
     const int qt = pb.b == 32 ? 32 : 64;
     const long long row_items = (long long)pb.NB * (pb.b / qt) * pb.g;
-    const long long col_items = (long long)pb.NB * pb.g;
+    const long long col_items = (long long)p.NBk * pb.g;
     if ((row_items + 3) / 4 * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
     p.map = make_wg_map(pb.Hkv, (int)((row_items + 3) / 4));
     hipLaunchKernelGGL(rows, dim3((unsigned)p.map.grid), dim3(256), 0, st, p);

@@ -55,6 +55,8 @@ def test_block_geometry(lib):
     # the levels follow the key blocks
     assert lib.stream_num_blocks(ctypes.byref(shape(block=32, block_k=128))) == 32      # T_p = 1024
     assert lib.stream_num_blocks(ctypes.byref(shape(block=128, block_k=32))) == 8
+    assert lib.stream_num_key_blocks(ctypes.byref(shape(block=128, block_k=32))) == 32
+    assert lib.stream_num_key_blocks(ctypes.byref(shape())) == 16
     assert lib.stream_num_blocks(ctypes.byref(shape(block=64, block_k=64))) == 16
     s.block, s.block_k = 32, 128
     assert lib.stream_num_blocks(ctypes.byref(s)) == 4 + 4 + 28                         # 128, 128, 896
@@ -196,7 +198,7 @@ def test_bad_arguments_of_receiver_stats(lib):
     assert call(wsz=need - 1) == B.STREAM_EWORKSPACE
     assert call(wsp=None) == B.STREAM_EWORKSPACE
     assert call(sh=shape(dtype=B.STREAM_F32, head_dim=128, block=128)) == B.STREAM_EUNSUPPORTED
-    assert call(sh=shape(block_k=128)) == B.STREAM_EUNSUPPORTED              # b_q != b_k
+    assert call(sh=shape(dtype=B.STREAM_F32, head_dim=128, block_k=128)) == B.STREAM_EUNSUPPORTED
     assert lib.stream_receiver_stats_workspace_bytes(ctypes.byref(shape(block=48))) == 0
 
 

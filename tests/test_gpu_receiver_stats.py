@@ -21,29 +21,35 @@ DEV = "cuda:0"
 RTOL_M = 2e-4
 
 
-def run(Q, K, H, Hkv, b, scale, cu=None, mask="causal", window=0, want_block_mean=True):
+def run(Q, K, H, Hkv, b, scale, cu=None, mask="causal", window=0, want_block_mean=True, block_k=0):
     r = binding.stream_receiver_stats(Q.to(DEV), K.to(DEV), H, Hkv, b, scale, cu_seqlens=cu,
-                                      want_block_mean=want_block_mean, mask=mask, window=window)
+                                      want_block_mean=want_block_mean, mask=mask, window=window,
+                                      block_k=block_k)
     torch.cuda.synchronize()
     return {k: (v.cpu().numpy() if isinstance(v, torch.Tensor) and k != "workspace" else v)
             for k, v in r.items()}
 
 
-def seq_blocks(cu, T, b):
+def seq_blocks(cu, T, b, bk):
+    """Sequence boundaries, and the first global query / key block of every sequence."""
     cu = [0, T] if cu is None else list(cu)
-    nblk = [-(-(cu[s + 1] - cu[s]) // b) for s in range(len(cu) - 1)]
-    blk0 = np.concatenate([[0], np.cumsum(nblk)]).astype(int)
-    return cu, nblk, blk0
+    ell = max(b, bk)
+    tp = [-(-(cu[s + 1] - cu[s]) // ell) * ell for s in range(len(cu) - 1)]
+    q0 = np.concatenate([[0], np.cumsum([t // b for t in tp])]).astype(int)
+    k0 = np.concatenate([[0], np.cumsum([t // bk for t in tp])]).astype(int)
+    return cu, q0, k0
 
 
-def check(w, mask="causal", window=0, scale=None):
+def check(w, mask="causal", window=0, scale=None, bk=None):
     Q, K, _, _ = wl.make_inputs(w, with_v=False)
     H, Hkv, b, d = w.heads, w.kv_heads, w.block, w.head_dim
     scale = 1.0 / math.sqrt(d) if scale is None else scale
+    bk = bk or b
     cu = list(w.cu_seqlens) if len(w.seq_lens) > 1 else None
-    got = run(Q, K, H, Hkv, b, scale, cu, mask, window)
+    got = run(Q, K, H, Hkv, b, scale, cu, mask, window, block_k=bk)
     Qn, Kn = Q.to(torch.float64).numpy(), K.to(torch.float64).numpy()
-    want = rs.receiver_stats(Qn, Kn, H, Hkv, b, scale, cu_seqlens=cu, mask=mask, window=window)
+    want = rs.receiver_stats(Qn, Kn, H, Hkv, b, scale, cu_seqlens=cu, mask=mask, window=window, block_k=bk)
+    assert got["block_mean"].shape == want["block_mean"].shape
 
     bm = got["block_mean"].astype(np.float64)
     np.testing.assert_allclose(bm, want["block_mean"], rtol=RTOL_M, atol=1e-30)
@@ -51,21 +57,21 @@ def check(w, mask="causal", window=0, scale=None):
     np.testing.assert_allclose(got["col_mean"], want["col_mean"], rtol=RTOL_M, atol=1e-30)
 
     # statistics recomputed in fp64 from the library's own block means
-    cu_l, nblk, blk0 = seq_blocks(cu, w.T, b)
+    cu_l, q0, k0 = seq_blocks(cu, w.T, b, bk)
     worst = 0.0
     for h in range(H):
-        for s in range(len(nblk)):
-            lo, hi = blk0[s], blk0[s + 1]
+        for s in range(len(q0) - 1):
+            qlo, qhi, lo, hi = q0[s], q0[s + 1], k0[s], k0[s + 1]
             L = cu_l[s + 1] - cu_l[s]
-            _, Cblk = rs.block_means(np.zeros((L, L)), b, mask, window)
-            mean, kurt, n = rs.column_stats(bm[h, lo:hi, lo:hi], Cblk)
+            _, Cblk = rs.block_means(np.zeros((L, L)), b, mask, window, bk)
+            mean, kurt, n = rs.column_stats(bm[h, qlo:qhi, lo:hi], Cblk)
             np.testing.assert_allclose(got["col_mean"][h, lo:hi], mean, rtol=1e-6, atol=1e-37)
             np.testing.assert_allclose(got["col_kurt"][h, lo:hi], kurt, rtol=1e-4, atol=1e-4)
             mx, vk = rs.head_stats(got["col_mean"][h, lo:hi].astype(np.float64), got["col_kurt"][h, lo:hi].astype(np.float64), n)
             np.testing.assert_allclose(got["head"][h, s], [mx, vk], rtol=1e-5, atol=1e-5)
             # against the oracle, conditioning-aware
             for j in range(hi - lo):
-                vals = want["block_mean"][h, lo:hi, lo + j][Cblk[:, j]]
+                vals = want["block_mean"][h, qlo:qhi, lo + j][Cblk[:, j]]
                 if vals.size < 4:
                     assert got["col_kurt"][h, lo + j] == 0.0
                     continue
@@ -77,7 +83,7 @@ def check(w, mask="causal", window=0, scale=None):
             wm, wv = want["head"][h, s]
             assert abs(got["head"][h, s, 0] - wm) <= 5e-3 * (1 + abs(wm)) * 10
             assert abs(got["head"][h, s, 1] - wv) <= 5e-3 * (1 + abs(wv)) * 10
-    print(f"[stats] {w.name} b={b} {mask}/{window}: worst kurt err/tol {worst:.3f}", flush=True)
+    print(f"[stats] {w.name} b_q={b} b_k={bk} {mask}/{window}: worst kurt err/tol {worst:.3f}", flush=True)
     return got, want
 
 
@@ -104,6 +110,30 @@ def test_against_oracle(cfg, lens, H, Hkv, b, mask, window):
     kw = {"needles_per_kv_head": 2} if cfg != 5 else {}
     w = wl.scaled(wl.config(cfg), lens, topk=4, heads=H, kv_heads=Hkv, block=b, **kw)
     check(w, mask, window)
+
+
+RECT_CASES = [
+    # (dtype cfg, seq_lens, heads, kv_heads, b_q, b_k, mask, window)
+    (2, (1000,), 2, 1, 32, 64, "causal", 0),
+    (2, (1000,), 2, 1, 64, 32, "causal", 0),
+    (2, (1100,), 2, 1, 32, 128, "causal", 0),        # query blocks of padding only
+    (2, (1100,), 2, 1, 128, 32, "causal", 0),        # key blocks of padding only
+    (2, (1000,), 2, 1, 64, 128, "sliding", 200),
+    (2, (1000,), 2, 1, 128, 64, "sliding", 77),
+    (2, (700,), 2, 1, 32, 128, "full", 0),
+    (2, (700,), 2, 1, 128, 32, "full", 0),
+    (1, (600,), 2, 2, 128, 64, "causal", 0),         # fp32, d = 64
+    (1, (600,), 2, 2, 64, 128, "sliding", 150),
+    (5, (300, 64, 1, 517), 7, 1, 32, 128, "causal", 0),
+    (5, (300, 129, 40), 7, 1, 128, 32, "sliding", 130),
+]
+
+
+@pytest.mark.parametrize("cfg,lens,H,Hkv,bq,bk,mask,window", RECT_CASES)
+def test_rectangular_spans_against_oracle(cfg, lens, H, Hkv, bq, bk, mask, window):
+    kw = {"needles_per_kv_head": 2} if cfg != 5 else {}
+    w = wl.scaled(wl.config(cfg), lens, topk=4, heads=H, kv_heads=Hkv, block=bq, **kw)
+    check(w, mask, window, bk=bk)
 
 
 def test_without_block_mean_output_and_repeat_call():
