@@ -295,7 +295,7 @@ int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char
 
 /*
  * Eq. (2) with the mask M given by idx/cnt (block ids per query block) and the
- * mask C (causal, or the rule named by mask_kind) inside retained blocks:  for each real query token t of the query
+ * mask C (an explicit [T, T] array, else the rule named by mask_kind) inside retained blocks:  for each real query token t of the query
  * blocks in qlist,
  *     S~[t,u] = scale * <Q_t, K_u>   for u in retained blocks of block(t), u <= t
  *     P~ = softmax(S~),  O_t = sum_u P~[t,u] V_u,  lse_t = log sum_u exp(S~[t,u])
@@ -303,8 +303,8 @@ int stream_oracle_prune_head(const float *Q, const float *K, const unsigned char
  * idx is [nq, k] (rows aligned with qlist), O is [T, d] and lse [T] (only rows of
  * the listed blocks are written), mass [T] is accumulated into (caller zeroes).
  */
-int stream_oracle_attn_head_rect(const float *Q, const float *K, const float *V,
-                                 int mask_kind, long window,
+int stream_oracle_attn_head_mask(const float *Q, const float *K, const float *V,
+                                 const unsigned char *C, int mask_kind, long window,
                                  long T, int d, int bq, int bk, int k, double scale,
                                  const int *qlist, int nq, const int *idx, const int *cnt,
                                  double *O, double *lse, double *mass)
@@ -312,7 +312,7 @@ int stream_oracle_attn_head_rect(const float *Q, const float *K, const float *V,
     if (!Q || !K || !V || !idx || !cnt || T <= 0) return 1;
     if (mask_kind < MASK_CAUSAL || mask_kind > MASK_SLIDING) return 1;
     if (mask_kind == MASK_SLIDING && window < 1) return 1;
-    problem_t p = {Q, K, NULL, T, d, bq, bk, mask_kind, window};
+    problem_t p = {Q, K, C, T, d, bq, bk, mask_kind, window};
 #pragma omp parallel for schedule(dynamic, 1)
     for (int qi = 0; qi < nq; ++qi) {
         const long q = qlist[qi];
@@ -356,6 +356,17 @@ int stream_oracle_attn_head_rect(const float *Q, const float *K, const float *V,
         free(sc); free(key);
     }
     return 0;
+}
+
+/* The mask C given by a rule. */
+int stream_oracle_attn_head_rect(const float *Q, const float *K, const float *V,
+                                 int mask_kind, long window,
+                                 long T, int d, int bq, int bk, int k, double scale,
+                                 const int *qlist, int nq, const int *idx, const int *cnt,
+                                 double *O, double *lse, double *mass)
+{
+    return stream_oracle_attn_head_mask(Q, K, V, NULL, mask_kind, window, T, d, bq, bk, k, scale, qlist, nq,
+                                        idx, cnt, O, lse, mass);
 }
 
 int stream_oracle_attn_head_rule(const float *Q, const float *K, const float *V,

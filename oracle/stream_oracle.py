@@ -80,6 +80,11 @@ def _load():
                                                      ctypes.c_long, ctypes.c_int, ctypes.c_int,
                                                      ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
                                                      ctypes.c_int, ip, ip, dp, dp, dp]
+        lib.stream_oracle_attn_head_mask.restype = ctypes.c_int
+        lib.stream_oracle_attn_head_mask.argtypes = [fp, fp, fp, up, ctypes.c_int, ctypes.c_long,
+                                                     ctypes.c_long, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_int, ctypes.c_double, ip,
+                                                     ctypes.c_int, ip, ip, dp, dp, dp]
         lib.stream_oracle_block_score_rect.restype = ctypes.c_double
         lib.stream_oracle_block_score_rect.argtypes = [fp, fp, up, ctypes.c_int, ctypes.c_long,
                                                        ctypes.c_long, ctypes.c_int, ctypes.c_int,
@@ -200,8 +205,9 @@ def block_table(cu_seqlens: Sequence[int], block: int, block_k: Optional[int] = 
 def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
           rows: Optional[Sequence[Sequence[int]]] = None, n_levels: int = -1,
           want_trace: bool = False, mask: str = "causal", window: int = 0,
-          block_k: Optional[int] = None):
-    """Stream for every (head, query block), or for the listed rows only.
+          block_k: Optional[int] = None, C=None):
+    """Stream for every (head, query block), or for the listed rows only.  C: explicit [T, T]
+    mask shared by all heads (single sequence only), else the rule `mask` / `window`.
 
     Q [heads, T, d], K [kv_heads, T, d]; topk is an int or one int per sequence.
     rows: optional list of (head, global query block).  Output arrays are
@@ -236,8 +242,10 @@ def prune(Q, K, heads: int, kv_heads: int, block: int, topk, cu_seqlens=None,
             ql = bloc[rows_arr[sel, 1]].astype(np.int32)
             Qh = Q[h, cu[s]:cu[s + 1]]
             Kh = K[h // g, cu[s]:cu[s + 1]]
+            if C is not None and nseq != 1:
+                raise ValueError("an explicit mask is taken for a single sequence only")
             out = prune_head(Qh, Kh, block, ks[s], ql, n_levels=n_levels, want_trace=want_trace,
-                             mask=mask, window=window, block_k=block_k)
+                             mask=mask, window=window, block_k=block_k, C=C)
             idx[sel, :ks[s]] = out["idx"]
             cnt[sel] = out["cnt"]
             score[sel, :ks[s]] = out["score"]
@@ -310,9 +318,10 @@ def prune_variable(Q, K, heads: int, kv_heads: int, block: int, keep_num: int, k
 def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
                 cu_seqlens=None, rows: Optional[Sequence[Sequence[int]]] = None,
                 want_mass: bool = True, mask: str = "causal", window: int = 0,
-                block_k: Optional[int] = None):
+                block_k: Optional[int] = None, C=None):
     """Eq. (2) over the retained blocks given by idx/cnt (query blocks of `block` tokens, key
-    blocks of `block_k` tokens, default the same).
+    blocks of `block_k` tokens, default the same).  The mask C inside the retained blocks is the
+    explicit [T, T] array C (single sequence only) if given, else the rule `mask` / `window`.
 
     idx/cnt are [heads, NB, kmax]/[heads, NB] (full) or aligned with `rows`.
     Returns dict(O [heads, T, d], lse [heads, T], mass [heads, T]) in fp64; with `rows`,
@@ -352,9 +361,12 @@ def sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale:
             i2 = np.ascontiguousarray(idx2[sel])
             c2 = np.ascontiguousarray(cnt2[sel])
             kind, win = _mask_code(mask, window)
-            rc = lib.stream_oracle_attn_head_rect(
+            Cc = None if C is None else np.ascontiguousarray(C, dtype=np.uint8)
+            if Cc is not None and len(cu) != 2:
+                raise ValueError("an explicit mask is taken for a single sequence only")
+            rc = lib.stream_oracle_attn_head_mask(
                 _ptr(Qh, ctypes.c_float), _ptr(Kh, ctypes.c_float), _ptr(Vh, ctypes.c_float),
-                kind, win, b_ - a, d, int(block), int(block_k or block), kmax, float(scale),
+                _ptr(Cc, ctypes.c_ubyte), kind, win, b_ - a, d, int(block), int(block_k or block), kmax, float(scale),
                 _ptr(ql, ctypes.c_int), len(ql),
                 _ptr(i2, ctypes.c_int), _ptr(c2, ctypes.c_int), _ptr(Oh, ctypes.c_double),
                 _ptr(lh, ctypes.c_double), _ptr(mh if want_mass else None, ctypes.c_double))

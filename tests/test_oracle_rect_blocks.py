@@ -145,3 +145,33 @@ def test_attention_with_rectangular_blocks_equals_dense_masked_softmax():
             np.testing.assert_allclose(at["O"][h], O, atol=1e-12)
             np.testing.assert_allclose(at["lse"][h], lse, atol=1e-12)
             np.testing.assert_allclose(at["mass"][h], mass, atol=1e-12)
+
+
+def test_attention_with_an_explicit_mask_equals_dense_masked_softmax():
+    # Eq. (2) with M from Alg. 2 and an arbitrary C inside the retained blocks; a query that sees
+    # none of its retained keys gets lse = -inf and a zero output
+    rng = np.random.default_rng(12)
+    H, T, d = 2, 45, 4
+    Q, K, V = (rng.standard_normal((H, T, d)).astype(np.float32).astype(np.float64) for _ in range(3))
+    C = (rng.random((T, T)) < 0.3).astype(np.uint8)
+    C[np.arange(0, T, 2), np.arange(0, T, 2)] = 1
+    for (bq, bk) in ((4, 4), (2, 8), (8, 2)):
+        pr = so.prune(Q, K, H, H, bq, 3, block_k=bk, C=C)
+        at = so.sparse_attn(Q, K, V, H, H, bq, pr["idx"], pr["cnt"], 0.5, block_k=bk, C=C)
+        for h in range(H):
+            A, Cb = bf.block_score_table(Q[h], K[h], bq, C, block_k=bk)
+            assert [sorted(int(x) for x in r[:c]) for r, c in zip(pr["idx"][h], pr["cnt"][h])] == \
+                bf.stream_from_table(A, Cb, 3)
+            M = np.zeros((T, T), np.uint8)
+            for q, (row, c) in enumerate(zip(pr["idx"][h], pr["cnt"][h])):
+                for r in row[:c]:
+                    M[q * bq:(q + 1) * bq, r * bk:(r + 1) * bk] = 1
+            seen = (M * C).any(axis=1)
+            assert seen.any() and not seen.all()
+            with np.errstate(invalid="ignore"):
+                O, lse, _ = bf.dense_attention(Q[h], K[h], V[h], M * C, 0.5)
+            np.testing.assert_allclose(at["O"][h][seen], O[seen], atol=1e-12)
+            np.testing.assert_allclose(at["lse"][h][seen], lse[seen], atol=1e-12)
+            assert np.isneginf(at["lse"][h][~seen]).all() and (at["O"][h][~seen] == 0).all()
+            P = np.where((M * C)[seen] != 0, np.exp(0.5 * (Q[h][seen] @ K[h].T) - lse[seen][:, None]), 0.0)
+            np.testing.assert_allclose(at["mass"][h], P.sum(axis=0), atol=1e-12)
