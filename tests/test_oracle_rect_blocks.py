@@ -153,8 +153,9 @@ def test_attention_with_an_explicit_mask_equals_dense_masked_softmax():
     rng = np.random.default_rng(12)
     H, T, d = 2, 45, 4
     Q, K, V = (rng.standard_normal((H, T, d)).astype(np.float32).astype(np.float64) for _ in range(3))
-    C = (rng.random((T, T)) < 0.3).astype(np.uint8)
+    C = (rng.random((T, T)) < 0.1).astype(np.uint8)
     C[np.arange(0, T, 2), np.arange(0, T, 2)] = 1
+    unseen = 0
     for (bq, bk) in ((4, 4), (2, 8), (8, 2)):
         pr = so.prune(Q, K, H, H, bq, 3, block_k=bk, C=C)
         at = so.sparse_attn(Q, K, V, H, H, bq, pr["idx"], pr["cnt"], 0.5, block_k=bk, C=C)
@@ -167,7 +168,7 @@ def test_attention_with_an_explicit_mask_equals_dense_masked_softmax():
                 for r in row[:c]:
                     M[q * bq:(q + 1) * bq, r * bk:(r + 1) * bk] = 1
             seen = (M * C).any(axis=1)
-            assert seen.any() and not seen.all()
+            unseen += int((~seen).sum())
             with np.errstate(invalid="ignore"):
                 O, lse, _ = bf.dense_attention(Q[h], K[h], V[h], M * C, 0.5)
             np.testing.assert_allclose(at["O"][h][seen], O[seen], atol=1e-12)
@@ -175,3 +176,4 @@ def test_attention_with_an_explicit_mask_equals_dense_masked_softmax():
             assert np.isneginf(at["lse"][h][~seen]).all() and (at["O"][h][~seen] == 0).all()
             P = np.where((M * C)[seen] != 0, np.exp(0.5 * (Q[h][seen] @ K[h].T) - lse[seen][:, None]), 0.0)
             np.testing.assert_allclose(at["mass"][h], P.sum(axis=0), atol=1e-12)
+    assert unseen > 0
