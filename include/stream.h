@@ -35,7 +35,8 @@
  *     when b_q < b_k) gets an empty list.  Key-block ids in `idx` are local to
  *     their sequence.
  *   - b_q = shape.block, b_k = shape.block_k (0 = b_q); the mask C is one of the rules of
- *     stream_mask (a zero-initialised shape means causal, b_k = b_q).  A key block is valid for
+ *     stream_mask or an explicit T x T bit array (a zero-initialised shape means causal,
+ *     b_k = b_q).  A key block is valid for
  *     a query block when at least one of its real keys is visible to one of the block's real
  *     queries.
  *   - Every entry point validates its arguments on the host before any launch
@@ -67,7 +68,8 @@ typedef enum { STREAM_F32 = 0, STREAM_BF16 = 1 } stream_dtype;
 typedef enum {
     STREAM_MASK_CAUSAL = 0,  /* u <= t                                                       */
     STREAM_MASK_FULL = 1,    /* always (no mask)                                             */
-    STREAM_MASK_SLIDING = 2  /* u <= t and t - u < window                                    */
+    STREAM_MASK_SLIDING = 2, /* u <= t and t - u < window                                    */
+    STREAM_MASK_ARRAY = 3    /* bit u of row t of the T x T bit array mask_bits is set        */
 } stream_mask;
 
 typedef struct {
@@ -86,6 +88,12 @@ typedef struct {
     int mask;        /* stream_mask: the attention mask C of Algorithm 2 and Eq. (2)   */
     long long window;/* STREAM_MASK_SLIDING: window length W in tokens, >= 1           */
     int block_k;     /* b_k: 32, 64 or 128; 0 = the same as block (b_q = b_k)          */
+    /* STREAM_MASK_ARRAY: the mask C of Algorithm 2 as an explicit array, shared by all heads.
+       DEVICE pointer to T rows of mask_pitch 32-bit words; C[t][u] is bit (u % 32) of word
+       t * mask_pitch + u / 32; mask_pitch >= ceil(T / 32); bits at u >= T are ignored.  Single
+       sequence only (batch = 1).  The array must stay unchanged until the call's work is done. */
+    const unsigned int *mask_bits;
+    long long mask_pitch;
 } stream_shape;
 
 /* Optional diagnostics of stream_prune (each member may be NULL). */

@@ -33,7 +33,8 @@ class StreamShape(ctypes.Structure):
                 ("k_stride_h", ctypes.c_longlong), ("k_stride_t", ctypes.c_longlong),
                 ("v_stride_h", ctypes.c_longlong), ("v_stride_t", ctypes.c_longlong),
                 ("o_stride_h", ctypes.c_longlong), ("o_stride_t", ctypes.c_longlong),
-                ("mask", ctypes.c_int), ("window", ctypes.c_longlong), ("block_k", ctypes.c_int)]
+                ("mask", ctypes.c_int), ("window", ctypes.c_longlong), ("block_k", ctypes.c_int),
+                ("mask_bits", ctypes.c_void_p), ("mask_pitch", ctypes.c_longlong)]
 
 
 class StreamPruneDiag(ctypes.Structure):
@@ -109,18 +110,26 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
-MASKS = {"causal": 0, "full": 1, "sliding": 2}
+MASKS = {"causal": 0, "full": 1, "sliding": 2, "array": 3}
 
 
 def make_shape(heads, kv_heads, head_dim, block, dtype_code, T, cu_seqlens=None, Q=None, K=None,
-               V=None, O=None, mask="causal", window=0, block_k=0):
-    """Build a stream_shape; returns (shape, keepalive) - keepalive owns the host cu_seqlens array."""
+               V=None, O=None, mask="causal", window=0, block_k=0, mask_bits=None):
+    """Build a stream_shape; returns (shape, keepalive) - keepalive owns the host cu_seqlens array.
+    mask_bits: int32 device tensor [T, pitch] holding the explicit mask C as bits (bit u % 32 of
+    word [t, u // 32]); selects STREAM_MASK_ARRAY."""
     s = StreamShape()
     s.heads, s.kv_heads, s.head_dim, s.block, s.dtype = heads, kv_heads, head_dim, block, dtype_code
     s.T = int(T)
     s.mask = MASKS[mask] if isinstance(mask, str) else int(mask)
     s.window = int(window)
     s.block_k = int(block_k or 0)
+    if mask_bits is not None:
+        if not mask_bits.is_cuda or mask_bits.dtype != torch.int32 or mask_bits.dim() != 2 or mask_bits.stride(1) != 1:
+            raise ValueError("mask_bits must be a device int32 tensor [T, pitch] with contiguous rows")
+        s.mask = MASKS["array"]
+        s.mask_bits = mask_bits.data_ptr()
+        s.mask_pitch = mask_bits.stride(0)
     keep = None
     if cu_seqlens is not None:
         cu = [int(x) for x in cu_seqlens]
@@ -150,7 +159,7 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
                  topk, cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
                  want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None,
                  level_events=None, levels_per_launch: int = 0, mask="causal", window: int = 0,
-                 block_k: int = 0):
+                 block_k: int = 0, mask_bits=None):
     """Algorithm 2 for every (head, query block).  Q [H, T, d], K [Hkv, T, d] on the GPU.
 
     topk: int, or one int per sequence.  Returns dict(idx [H, NB, kmax] int32, cnt [H, NB] int32,
@@ -161,7 +170,7 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
         raise ValueError("Q and K must be device tensors (the library has no CPU path)")
     H, T, d = Q.shape
     shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
-                             mask=mask, window=window, block_k=block_k)
+                             mask=mask, window=window, block_k=block_k, mask_bits=mask_bits)
     nseq = shape.batch
     if isinstance(topk, int):
         ks, kmax, k_arr = None, int(topk), None
@@ -255,7 +264,7 @@ def stream_prune_variable(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads
                           keep_num: int, keep_den: int, topk_min: int, topk_max: int,
                           cu_seqlens: Optional[Sequence[int]] = None, want_score: bool = False,
                           want_trace: bool = False, want_tiles: bool = False, workspace=None, out=None,
-                          mask="causal", window: int = 0, block_k: int = 0):
+                          mask="causal", window: int = 0, block_k: int = 0, mask_bits=None):
     """Algorithm 2 with k(row) = clamp(ceil(valid(row) * keep_num / keep_den), topk_min, topk_max).
     Returns dict(idx [H, NB, topk_max], cnt [H, NB], score, trace, tiles)."""
     lib = load()
@@ -263,7 +272,7 @@ def stream_prune_variable(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads
         raise ValueError("Q and K must be device tensors (the library has no CPU path)")
     H, T, d = Q.shape
     shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
-                             mask=mask, window=window, block_k=block_k)
+                             mask=mask, window=window, block_k=block_k, mask_bits=mask_bits)
     NB = num_blocks(shape)
     if NB < 0:
         raise StreamError(STREAM_EINVAL, "stream_num_blocks")
@@ -300,7 +309,8 @@ def stream_prune_variable(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads
 
 def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt, scale: float,
                        cu_seqlens=None, want_lse: bool = False, want_mass: bool = False,
-                       workspace=None, out=None, mask="causal", window: int = 0, block_k: int = 0):
+                       workspace=None, out=None, mask="causal", window: int = 0, block_k: int = 0,
+                       mask_bits=None):
     """Eq. (2) on the retained blocks.  Returns dict(O [H, T, d], lse [H, T], mass [H, T])."""
     lib = load()
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -309,7 +319,7 @@ def stream_sparse_attn(Q, K, V, heads: int, kv_heads: int, block: int, idx, cnt,
     dev = Q.device
     O = torch.empty_like(Q) if out is None else out["O"]
     shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K, V=V, O=O,
-                             mask=mask, window=window, block_k=block_k)
+                             mask=mask, window=window, block_k=block_k, mask_bits=mask_bits)
     kmax = idx.shape[-1]
     if idx.dtype != torch.int32 or cnt.dtype != torch.int32 or not idx.is_contiguous() or not cnt.is_contiguous():
         raise ValueError("idx/cnt must be contiguous int32 device tensors")

@@ -144,6 +144,8 @@ __device__ __forceinline__ uint4 load_frag(__amdgpu_buffer_rsrc_t rs, unsigned l
 struct Problem {
     int H, Hkv, g, d, b, bk, dtype, esize, batch, kmax;   // b = b_q (query block), bk = b_k
     int mask, window;         // stream_mask rule; window in tokens (sliding window only)
+    const unsigned *cbits;    // STREAM_MASK_ARRAY: the T x T bit array (device) and its row pitch in words
+    long long cpitch;
     long long T;
     int NB;
     SeqTable seqs;
@@ -157,6 +159,13 @@ size_t align_up(size_t x, size_t a);
 
 // Packs a [kv_heads, T, d] tensor into block tiles whose 16-byte chunks are ordered the way the
 // 32x32 MFMA operand fragments are read: see pack_kernel in stream_pack.hip.
+// STREAM_MASK_ARRAY: block-level summaries of the bit array C for query blocks of b_q and key
+// blocks of b_k tokens, one bit per (query block, key block), rows of block_bitmap_words(pb)
+// words: any = C^blk of Alg. 2 (some real pair of the block is visible), all = every pair of
+// the block is real and visible (no token-level test needed).
+int block_bitmap_words(const Problem &pb);
+stream_status launch_block_bitmaps(const Problem &pb, unsigned *any_bits, unsigned *all_bits, hipStream_t st);
+
 stream_status launch_pack(const void *src, long long stride_h, long long stride_t, void *dst,
                           const Problem &pb, hipStream_t st);
 

@@ -29,9 +29,15 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
     if (s->block_k != 0 && s->block_k != 32 && s->block_k != 64 && s->block_k != 128) return STREAM_EUNSUPPORTED;
     if (s->batch > kMaxBatch) return STREAM_EUNSUPPORTED;
     if (s->T > (1LL << 31) - 4096) return STREAM_EUNSUPPORTED;
-    if (s->mask != STREAM_MASK_CAUSAL && s->mask != STREAM_MASK_FULL && s->mask != STREAM_MASK_SLIDING)
+    if (s->mask != STREAM_MASK_CAUSAL && s->mask != STREAM_MASK_FULL && s->mask != STREAM_MASK_SLIDING &&
+        s->mask != STREAM_MASK_ARRAY)
         return STREAM_EINVAL;
     if (s->mask == STREAM_MASK_SLIDING && s->window < 1) return STREAM_EINVAL;
+    if (s->mask == STREAM_MASK_ARRAY) {
+        if (!s->mask_bits || ((uintptr_t)s->mask_bits & 3)) return STREAM_EINVAL;
+        if (s->mask_pitch < (s->T + 31) / 32) return STREAM_EINVAL;
+        if (s->batch != 1) return STREAM_EUNSUPPORTED;
+    }
 
     Problem &p = *out;
     p.H = s->heads; p.Hkv = s->kv_heads; p.g = s->heads / s->kv_heads;
@@ -42,6 +48,8 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
     p.mask = s->mask;
     // a window that reaches past the longest possible sequence is the causal mask
     p.window = s->mask == STREAM_MASK_SLIDING ? (int)(s->window < s->T ? s->window : s->T) : 0;
+    p.cbits = s->mask == STREAM_MASK_ARRAY ? s->mask_bits : nullptr;
+    p.cpitch = s->mask == STREAM_MASK_ARRAY ? s->mask_pitch : 0;
     p.seqs.n = s->batch;
     long long nb = 0, tok = 0;
     int maxlev = 0;
@@ -144,6 +152,72 @@ stream_status launch_pack(const void *src, long long stride_h, long long stride_
     long long grid = (long long)pb.Hkv * pb.NB * (pb.b / 32);
     if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)grid), dim3(256), 0, st, p);
+    return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block-level summaries of an explicit mask (STREAM_MASK_ARRAY).  A thread owns one (query block,
+// key block) pair and walks the b_q rows of its b_k / 32 words; consecutive threads own
+// consecutive key blocks, so a wavefront reads consecutive words of every row.
+// ---------------------------------------------------------------------------------------------
+struct BitmapParams {
+    const unsigned *cbits;
+    long long cpitch;
+    unsigned *any_bits, *all_bits;
+    int T, bq, bk, nq, nk, words;
+};
+
+__global__ void __launch_bounds__(64) block_bitmap_kernel(BitmapParams p)
+{
+    const int lane = threadIdx.x;
+    const int q = blockIdx.y;
+    const int r = blockIdx.x * 64 + lane;
+    bool any = false, all = false;
+    if (r < p.nk && (long long)r * p.bk < p.T && (long long)q * p.bq < p.T) {
+        const int t0 = q * p.bq, u0 = r * p.bk;
+        const int t1 = t0 + p.bq < p.T ? t0 + p.bq : p.T;
+        const int wpb = p.bk / 32;
+        unsigned acc_or = 0, acc_and = ~0u;
+        for (int t = t0; t < t1; ++t)
+            for (int w = 0; w < wpb; ++w) {
+                const int ub = u0 + w * 32;                       // first key of this word
+                unsigned x = 0;
+                if (ub < p.T) {
+                    x = p.cbits[(long long)t * p.cpitch + (ub >> 5)];
+                    if (ub + 32 > p.T) x &= (1u << (p.T - ub)) - 1u;   // keys past the end do not exist
+                }
+                acc_or |= x;
+                acc_and &= x;
+            }
+        any = acc_or != 0;
+        all = acc_and == ~0u && t0 + p.bq <= p.T && u0 + p.bk <= p.T;
+    }
+    const unsigned long long ba = __ballot(any), bl = __ballot(all);
+    if (lane == 0 || lane == 32) {
+        const int w = blockIdx.x * 2 + (lane >> 5);
+        if (w < p.words) {
+            p.any_bits[(long long)q * p.words + w] = (unsigned)(ba >> lane);
+            p.all_bits[(long long)q * p.words + w] = (unsigned)(bl >> lane);
+        }
+    }
+}
+
+int block_bitmap_words(const Problem &pb)
+{
+    const long long nk = (long long)pb.NB * pb.b / pb.bk;
+    return (int)((nk + 31) / 32);
+}
+
+stream_status launch_block_bitmaps(const Problem &pb, unsigned *any_bits, unsigned *all_bits, hipStream_t st)
+{
+    BitmapParams p;
+    p.cbits = pb.cbits; p.cpitch = pb.cpitch;
+    p.any_bits = any_bits; p.all_bits = all_bits;
+    p.T = (int)pb.T; p.bq = pb.b; p.bk = pb.bk;
+    p.nq = pb.NB; p.nk = (int)((long long)pb.NB * pb.b / pb.bk);
+    p.words = block_bitmap_words(pb);
+    if (pb.NB > 65535) return STREAM_EUNSUPPORTED;                 // grid.y
+    hipLaunchKernelGGL(block_bitmap_kernel, dim3((unsigned)((p.nk + 63) / 64), (unsigned)pb.NB), dim3(64), 0, st, p);
     return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
 }
 

@@ -37,6 +37,11 @@ struct PruneParams {
     WgMap map;
     SeqTable seqs;
     int mask, window;            // the mask rule C (stream_mask) and its window
+    // STREAM_MASK_ARRAY (ARB kernels): the bit array C, its block-level summaries [NB, cw] (any =
+    // C^blk of Alg. 2, all = no token-level test needed) and the words per row of either
+    const unsigned *cbits, *cany, *call;
+    long long cpitch;
+    int cw;
     int vk_num, vk_den, vk_min;  // variable k (vk_den > 0): k(row) = clamp(ceil(valid * num / den), min, kmax)
     int n_k;                     // k sweep (MULTI kernels): values of k, outputs [H, n_k, NB, ...]
     int klist[kMaxSweep];
@@ -62,7 +67,10 @@ __host__ __device__ __forceinline__ int variable_k(int valid, int num, int den, 
 // Template parameters: element type, head dim, 32-row groups of Q per wavefront (MB), 32-key
 // groups of K per wavefront (NG), wavefronts per row (WPR: 1, or 4 = 2 query halves x 2 key
 // halves for block 128), occupancy hint, k sweep with the block-score cache (MULTI).
-template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI>
+// ARB: the mask C is an explicit bit array (STREAM_MASK_ARRAY) instead of a rule: a branch's
+// representative is found by scanning the row's C^blk bits, and every block that is not wholly
+// visible takes the token-level test against the array.
+template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI, bool ARB = false>
 __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -94,7 +102,11 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int N = sd.nblk * BQ / BK;                      // key blocks of the sequence: the nodes range over these
     int row_k = sd.k, row_levels = sd.levels;
     if (!MULTI && p.vk_den > 0) {
-        const int valid = mask_rmax(p.mask, q, BQ, BK, L) - mask_rmin(p.mask, p.window, q, BQ, BK) + 1;
+        int valid = mask_rmax(p.mask, q, BQ, BK, L) - mask_rmin(p.mask, p.window, q, BQ, BK) + 1;
+        if constexpr (ARB) {
+            valid = 0;
+            for (int w = 0; w < p.cw; ++w) valid += __popc(p.cany[(long long)gb * p.cw + w]);
+        }
         row_k = variable_k(valid, p.vk_num, p.vk_den, p.vk_min, p.kmax);
         row_levels = levels_for(N, row_k);
     }
@@ -180,6 +192,19 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     const int edge_hi = p.mask == STREAM_MASK_SLIDING && edge_num >= 0 ? edge_num / BK : -1;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const long long o = row * p.kmax;
+    // ARB: first key block of [a, b] that C^blk leaves to this row, or -1
+    const unsigned *anyrow = ARB ? p.cany + (long long)gb * p.cw : nullptr;
+    const unsigned *allrow = ARB ? p.call + (long long)gb * p.cw : nullptr;
+    auto first_valid = [&](int a, int b) -> int {
+        if (a > b) return -1;
+        for (int w = a >> 5; w <= (b >> 5); ++w) {
+            unsigned x = anyrow[w];
+            if (w == (a >> 5)) x &= ~0u << (a & 31);
+            if (w == (b >> 5) && (b & 31) != 31) x &= (1u << ((b & 31) + 1)) - 1u;
+            if (x) return w * 32 + __builtin_ctz(x);
+        }
+        return -1;
+    };
 
     // A row runs its levels level_begin .. level_last back to back: the Q tile stays in
     // registers and the node list moves from one level to the next through LDS.
@@ -188,11 +213,18 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         // ---- split at the midpoint; causal validity: a branch is valid iff it is non-empty and
         //      starts at or before the query block; its representative is its first block.
         const int m = (f + l + 1) >> 1;
-        const int rep_p = f > rmin ? f : rmin;                // the node's own representative
-        const int rep0 = rep_p;                               // left child [f, m-1]
-        const int rep1 = m > rmin ? m : rmin;                 // right child [m, l] (never empty)
-        const bool v0 = live && m > f && rep0 <= (m - 1 < rmax ? m - 1 : rmax);
-        const bool v1 = live && rep1 <= (l < rmax ? l : rmax);
+        int rep_p = f > rmin ? f : rmin;                      // the node's own representative
+        int rep0 = rep_p;                                     // left child [f, m-1]
+        int rep1 = m > rmin ? m : rmin;                       // right child [m, l] (never empty)
+        bool v0 = live && m > f && rep0 <= (m - 1 < rmax ? m - 1 : rmax);
+        bool v1 = live && rep1 <= (l < rmax ? l : rmax);
+        if constexpr (ARB) {
+            rep0 = live ? first_valid(f, m - 1) : -1;
+            rep1 = live ? first_valid(m, l) : -1;
+            v0 = rep0 >= 0;
+            v1 = rep1 >= 0;
+            rep_p = v0 ? rep0 : rep1;                         // the node's first valid block
+        }
         // a child whose representative is the node's own inherits the node's score
         bool need0 = v0 && first;
         bool need1 = v1 && (first || rep1 != rep_p);
@@ -261,8 +293,9 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             }
             float mx = -INFINITY;
             // the block reaches past the row's first query (causal rules) or past the sequence
-            const bool cut = tail_row || (p.mask != STREAM_MASK_FULL && (r + 1) * BK - 1 > q * BQ) ||
-                             r <= edge_hi || (r + 1) * BK > L;
+            bool cut = tail_row || (p.mask != STREAM_MASK_FULL && (r + 1) * BK - 1 > q * BQ) ||
+                       r <= edge_hi || (r + 1) * BK > L;
+            if constexpr (ARB) cut = !((allrow[r >> 5] >> (r & 31)) & 1u);
             if (!cut) {
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
@@ -284,7 +317,14 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                         for (int i = 0; i < 16; ++i) {
                             const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
                             const int tk = ktok0 + cb * 32 + (lane & 31);
-                            const bool visible = (tq < L) & (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                            bool visible = (tq < L) & (tk < L);
+                            if constexpr (ARB) {
+                                // the word of row tq that holds keys ktok0 + cb*32 .. +31 (same for all lanes of a half)
+                                const unsigned cwd = tq < L ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + cb)] : 0u;
+                                visible = visible & ((cwd >> (lane & 31)) & 1u);
+                            } else {
+                                visible = visible & mask_token(p.mask, p.window, tq, tk);
+                            }
                             mx = visible ? fmaxf(mx, acc[rb][cb][i]) : mx;
                         }
             }
@@ -375,7 +415,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 }
 
 struct PruneWorkspace {
-    size_t kp, nf, nl, ns, ncnt, total;
+    size_t kp, nf, nl, ns, ncnt, cany, call, total;
 };
 
 static PruneWorkspace prune_layout(const Problem &pb)
@@ -389,6 +429,10 @@ static PruneWorkspace prune_layout(const Problem &pb)
     w.nl = off;   off += align_up(rows * pb.kmax * 4, 256);
     w.ns = off;   off += align_up(rows * pb.kmax * 4, 256);
     w.ncnt = off; off += align_up(rows * 4, 256);
+    // block-level summaries of an explicit mask array
+    const size_t bm = pb.mask == STREAM_MASK_ARRAY ? align_up((size_t)pb.NB * block_bitmap_words(pb) * 4, 256) : 0;
+    w.cany = off; off += bm;
+    w.call = off; off += bm;
     w.total = off;
     return w;
 }
@@ -401,41 +445,43 @@ typedef void (*level_fn)(const PruneParams);
 // One wavefront per row holds MB x NG accumulator tiles; beyond 2 x 2 only one wavefront fits a
 // SIMD's registers.  fp32 fragments are twice as many: with d = 128 the 4 x 2 and 2 x 4 shapes do
 // not fit at all.
-template <bool MULTI, bool BF16, int D>
+template <bool MULTI, bool BF16, int D, bool ARB>
 static level_fn pick_level_kernel_d(int bq, int bk, int &wpr)
 {
     constexpr int OCC2 = (BF16 || D == 64) ? 2 : 1;
     constexpr bool BIG = BF16 || D == 64;           // 6 fragment groups + 8 accumulator tiles fit
     wpr = 1;
     const int mb = bq / 32, ng = bk / 32;
-    if (mb == 4 && ng == 4) { wpr = 4; return level_kernel<BF16, D, 2, 2, 4, OCC2, MULTI>; }
-    if (mb == 1 && ng == 1) return level_kernel<BF16, D, 1, 1, 1, 2, MULTI>;
-    if (mb == 2 && ng == 2) return level_kernel<BF16, D, 2, 2, 1, OCC2, MULTI>;
-    if (mb == 1 && ng == 2) return level_kernel<BF16, D, 1, 2, 1, OCC2, MULTI>;
-    if (mb == 2 && ng == 1) return level_kernel<BF16, D, 2, 1, 1, OCC2, MULTI>;
+    if (mb == 4 && ng == 4) { wpr = 4; return level_kernel<BF16, D, 2, 2, 4, OCC2, MULTI, ARB>; }
+    if (mb == 1 && ng == 1) return level_kernel<BF16, D, 1, 1, 1, 2, MULTI, ARB>;
+    if (mb == 2 && ng == 2) return level_kernel<BF16, D, 2, 2, 1, OCC2, MULTI, ARB>;
+    if (mb == 1 && ng == 2) return level_kernel<BF16, D, 1, 2, 1, OCC2, MULTI, ARB>;
+    if (mb == 2 && ng == 1) return level_kernel<BF16, D, 2, 1, 1, OCC2, MULTI, ARB>;
     constexpr int OCC41 = (BF16 && D == 64) ? 2 : 1;   // 5 fragment groups of 8 or 16 registers + 4 tiles
-    if (mb == 1 && ng == 4) return level_kernel<BF16, D, 1, 4, 1, OCC41, MULTI>;
-    if (mb == 4 && ng == 1) return level_kernel<BF16, D, 4, 1, 1, OCC41, MULTI>;
+    if (mb == 1 && ng == 4) return level_kernel<BF16, D, 1, 4, 1, OCC41, MULTI, ARB>;
+    if (mb == 4 && ng == 1) return level_kernel<BF16, D, 4, 1, 1, OCC41, MULTI, ARB>;
     if constexpr (BIG) {
-        if (mb == 2 && ng == 4) return level_kernel<BF16, D, 2, 4, 1, 1, MULTI>;
-        if (mb == 4 && ng == 2) return level_kernel<BF16, D, 4, 2, 1, 1, MULTI>;
+        if (mb == 2 && ng == 4) return level_kernel<BF16, D, 2, 4, 1, 1, MULTI, ARB>;
+        if (mb == 4 && ng == 2) return level_kernel<BF16, D, 4, 2, 1, 1, MULTI, ARB>;
     }
     return nullptr;
 }
 
-template <bool MULTI>
+template <bool MULTI, bool ARB>
 static level_fn pick_level_kernel_t(const Problem &pb, int &wpr)
 {
     if (pb.dtype == STREAM_BF16)
-        return pb.d == 128 ? pick_level_kernel_d<MULTI, true, 128>(pb.b, pb.bk, wpr)
-                           : pick_level_kernel_d<MULTI, true, 64>(pb.b, pb.bk, wpr);
-    return pb.d == 128 ? pick_level_kernel_d<MULTI, false, 128>(pb.b, pb.bk, wpr)
-                       : pick_level_kernel_d<MULTI, false, 64>(pb.b, pb.bk, wpr);
+        return pb.d == 128 ? pick_level_kernel_d<MULTI, true, 128, ARB>(pb.b, pb.bk, wpr)
+                           : pick_level_kernel_d<MULTI, true, 64, ARB>(pb.b, pb.bk, wpr);
+    return pb.d == 128 ? pick_level_kernel_d<MULTI, false, 128, ARB>(pb.b, pb.bk, wpr)
+                       : pick_level_kernel_d<MULTI, false, 64, ARB>(pb.b, pb.bk, wpr);
 }
 
+// (a sweep over k with an explicit mask array is not built: nullptr)
 static level_fn pick_level_kernel(const Problem &pb, bool multi, int &wpr)
 {
-    return multi ? pick_level_kernel_t<true>(pb, wpr) : pick_level_kernel_t<false>(pb, wpr);
+    if (pb.mask == STREAM_MASK_ARRAY) return multi ? nullptr : pick_level_kernel_t<false, true>(pb, wpr);
+    return multi ? pick_level_kernel_t<true, false>(pb, wpr) : pick_level_kernel_t<false, false>(pb, wpr);
 }
 
 }  // namespace stream
@@ -470,6 +516,10 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
 
     stream_status rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st);
     if (rc != STREAM_OK) return rc;
+    if (pb.mask == STREAM_MASK_ARRAY) {
+        rc = launch_block_bitmaps(pb, (unsigned *)(ws + w.cany), (unsigned *)(ws + w.call), st);
+        if (rc != STREAM_OK) return rc;
+    }
 
     PruneParams p;
     p.Q = (const char *)Q;
@@ -484,6 +534,9 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     p.trace = diag ? diag->trace : nullptr;
     p.seqs = pb.seqs;
     p.mask = pb.mask; p.window = pb.window;
+    p.cbits = pb.cbits; p.cpitch = pb.cpitch;
+    p.cany = (const unsigned *)(ws + w.cany); p.call = (const unsigned *)(ws + w.call);
+    p.cw = pb.mask == STREAM_MASK_ARRAY ? block_bitmap_words(pb) : 0;
     p.max_levels = pb.max_levels;
     p.vk_num = vk.num; p.vk_den = vk.den; p.vk_min = vk.kmin;
     p.n_k = multi ? n_k : 1;

@@ -1,0 +1,111 @@
+"""The mask C of Alg. 2 as an explicit T x T bit array (STREAM_MASK_ARRAY) on the GPU path,
+through the C ABI, against the oracle run with the same array: causal / sliding arrays must
+reproduce the rule-based kernels bit for bit, random and document-structured masks the oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import stream_oracle as so
+from paper_2510_19875_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {"bf16": 2e-2, "f32": 1e-4}
+
+
+def pack_bits(C, extra_words=0):
+    """bool [T, T] -> int32 device tensor [T, ceil(T/32) + extra_words], bit u % 32 of word u // 32."""
+    T = C.shape[0]
+    W = -(-T // 32) + extra_words
+    padded = np.zeros((T, W * 32), dtype=np.uint8)
+    padded[:, :T] = C != 0
+    words = np.packbits(padded, axis=1, bitorder="little").view(np.uint32)
+    return torch.from_numpy(words.view(np.int32).copy()).to(DEV)
+
+
+def masks(T, seed):
+    rng = np.random.default_rng(seed)
+    t = np.arange(T)
+    causal = t[None, :] <= t[:, None]
+    out = {"causal": causal, "sliding": causal & (t[:, None] - t[None, :] < 150)}
+    rnd = rng.random((T, T)) < 0.02
+    rnd[t, t] = True
+    out["random"] = rnd
+    # packed documents: causal inside a document, nothing across documents, plus a shared prefix
+    cuts = np.sort(rng.choice(np.arange(1, T), size=5, replace=False))
+    doc = np.searchsorted(cuts, t, side="right")
+    out["documents"] = causal & ((doc[:, None] == doc[None, :]) | (t[None, :] < 40))
+    rows_off = causal.copy()
+    rows_off[T // 3: T // 3 + 70] = False                        # queries that see nothing at all
+    out["blank_rows"] = rows_off
+    return out
+
+
+def lists(idx, cnt):
+    return [[int(x) for x in r[:c]] for r, c in zip(idx, cnt)]
+
+
+def prune_case(w, C, bk=0, pitch_extra=0):
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    k = w.topk[0]
+    bits = pack_bits(C, pitch_extra)
+    out = binding.stream_prune(Q.to(DEV), K.to(DEV), w.heads, w.kv_heads, w.block, k, want_score=True,
+                               want_tiles=True, block_k=bk, mask_bits=bits)
+    torch.cuda.synchronize()
+    ref = so.prune(Q.float().numpy(), K.float().numpy(), w.heads, w.kv_heads, w.block, k,
+                   block_k=bk or None, C=C.astype(np.uint8))
+    gi, gc, gs = out["idx"].cpu().numpy(), out["cnt"].cpu().numpy(), out["score"].cpu().numpy()
+    np.testing.assert_array_equal(gc, ref["cnt"])
+    diff = [(h, q) for h in range(w.heads) for q in range(gi.shape[1]) if not np.array_equal(gi[h, q], ref["idx"][h, q])]
+    # (near-ties could differ legitimately; none is expected at these sizes)
+    assert not diff, diff[:5]
+    live = np.arange(gi.shape[2])[None, None, :] < gc[:, :, None]
+    np.testing.assert_allclose(gs[live], ref["score"][live], rtol=1e-4, atol=1e-4)
+    assert np.isneginf(gs[~live]).all()
+    assert int(out["tiles"].item()) == int(ref["evals"][1])
+    return out, ref
+
+
+@pytest.mark.parametrize("name", ["causal", "sliding", "random", "documents", "blank_rows"])
+@pytest.mark.parametrize("bq,bk,dtype,d,T", [(64, 0, "bf16", 128, 64 * 30 + 9), (32, 0, "f32", 64, 32 * 40 + 3),
+                                              (128, 0, "bf16", 128, 128 * 14 + 77), (32, 128, "bf16", 128, 2000),
+                                              (128, 32, "bf16", 64, 2000), (64, 128, "f32", 64, 1500)])
+def test_prune_with_mask_array(name, bq, bk, dtype, d, T):
+    w = wl.scaled(wl.config(2), (T,), topk=5, heads=4, kv_heads=2, block=bq, dtype=dtype, head_dim=d,
+                  needles_per_kv_head=2)
+    C = masks(T, 3)[name]
+    print(f"[array] {name} b_q={bq} b_k={bk or bq} {dtype} T={T}", flush=True)
+    out, _ = prune_case(w, C, bk, pitch_extra=1 if name == "random" else 0)
+    if name in ("causal", "sliding"):
+        # the same mask as a rule: identical lists and scores from the rule-based kernels
+        Q, K, _, _ = wl.make_inputs(w, with_v=False)
+        rule = binding.stream_prune(Q.to(DEV), K.to(DEV), w.heads, w.kv_heads, bq, 5, want_score=True,
+                                    block_k=bk, mask=name, window=150)
+        torch.cuda.synchronize()
+        assert torch.equal(rule["idx"], out["idx"]) and torch.equal(rule["score"], out["score"])
+
+
+def test_variable_k_and_split_levels_with_mask_array():
+    T = 64 * 40 + 5
+    w = wl.scaled(wl.config(2), (T,), topk=8, heads=4, kv_heads=2, needles_per_kv_head=2)
+    C = masks(T, 4)["documents"]
+    bits = pack_bits(C)
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    Qd, Kd = Q.to(DEV), K.to(DEV)
+    a = binding.stream_prune(Qd, Kd, 4, 2, 64, 8, want_score=True, mask_bits=bits)
+    b = binding.stream_prune(Qd, Kd, 4, 2, 64, 8, want_score=True, mask_bits=bits, levels_per_launch=1)
+    torch.cuda.synchronize()
+    assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["score"], b["score"])
+    # k(row) = ceil(valid / 4) clamped to [1, 8], valid = key blocks C^blk leaves to the row
+    v = binding.stream_prune_variable(Qd, Kd, 4, 2, 64, 1, 4, 1, 8, mask_bits=bits)
+    torch.cuda.synchronize()
+    Tp = -(-T // 64) * 64
+    Cp = np.zeros((Tp, Tp), bool); Cp[:T, :T] = C
+    valid = Cp.reshape(Tp // 64, 64, Tp // 64, 64).any(axis=(1, 3)).sum(axis=1)
+    want = np.minimum(np.clip(-(-valid // 4), 1, 8), valid)
+    np.testing.assert_array_equal(v["cnt"].cpu().numpy(), np.broadcast_to(want, (4, Tp // 64)))
+    with pytest.raises(binding.StreamError) as e:
+        binding.stream_prune(Qd, Kd, 4, 2, 64, 8, mask_bits=bits[:, :3].contiguous())   # rows too short
+    assert e.value.code == 1
