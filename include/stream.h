@@ -195,7 +195,7 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
  *              `levels` = stream_prune_levels() of the smallest k; tiles_scored counts the
  *              block scores actually computed; levels_per_launch is ignored
  *   workspace  stream_prune_multi_workspace_bytes(shape, n_k, topk_max) bytes, 256-byte aligned
- * Errors: as stream_prune; STREAM_EUNSUPPORTED when n_k > 32.
+ * Errors: as stream_prune; STREAM_EUNSUPPORTED when n_k > 32 and for STREAM_MASK_ARRAY.
  */
 size_t stream_prune_multi_workspace_bytes(const stream_shape *shape, int n_k, int topk_max);
 
@@ -300,7 +300,7 @@ stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *
  *   workspace   stream_receiver_stats_workspace_bytes(shape) bytes (packed Q and K, one float
  *               per padded token and head), 256-byte aligned
  * The moments are accumulated in fp64 from the fp32 block means.  Errors: as stream_prune;
- * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and b_k = 128.
+ * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and b_k = 128, and for STREAM_MASK_ARRAY.
  */
 size_t stream_receiver_stats_workspace_bytes(const stream_shape *shape);
 

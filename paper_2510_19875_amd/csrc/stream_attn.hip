@@ -93,6 +93,11 @@ struct AttnParams {
     int H, g, NB, kmax;
     float scale_log2e;           // scale * log2(e): softmax runs in base 2
     int mask, window;            // the mask rule C (stream_mask) and its window
+    // STREAM_MASK_ARRAY (ARB kernels): the bit array C, its "wholly visible" block summary
+    // [NB, cw] and the words per row of the summary
+    const unsigned *cbits, *call;
+    long long cpitch;
+    int cw;
     WgMap map;
     SeqTable seqs;
 };
@@ -180,7 +185,9 @@ __device__ __forceinline__ void static_for(F &f)
 // allowed in flight.
 // PASS 1: outputs O, lse (and the base-2 normalisers for pass 2).  PASS 2: received mass, a
 // separate launch with two wavefronts per SIMD so that one's exponentials overlap the other's MFMAs.
-template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC>
+// ARB: the mask C is an explicit bit array (STREAM_MASK_ARRAY): every sub-tile of a block that is
+// not wholly visible takes the token-level test against the array, in the plain order.
+template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC, bool ARB = false>
 __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -221,7 +228,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // sub-tiles of the diagonal block lying entirely after this wavefront's queries are dropped
     // (lists are ascending, so the diagonal block, if present, is the last one)
     int n_tiles = n_blk * KSUB;
-    if (n_blk > 0 && p.mask != STREAM_MASK_FULL) {
+    if (!ARB && n_blk > 0 && p.mask != STREAM_MASK_FULL) {
         const int last_r = my_idx[n_blk - 1];
         if (last_r * BK + (KSUB - 1) * KT > qtok0 + QT - 1) {
             int vis = (qtok0 + QT - 1 - last_r * BK) / KT + 1;
@@ -266,7 +273,12 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         return r * BK + (ts % KSUB) * KT;
     };
     // does the mask C (or the end of the sequence) cut through the sub-tile that starts at key k0?
+    const unsigned *allrow = ARB ? p.call + (long long)gb * p.cw : nullptr;
     auto needs_mask = [&](int k0) -> bool {
+        if constexpr (ARB) {
+            const int r = k0 / BK;
+            return !((allrow[r >> 5] >> (r & 31)) & 1u);
+        }
         bool m = k0 + KT > L;
         if (p.mask != STREAM_MASK_FULL) m = m || (k0 + KT - 1 > qtok0);                       // keys after a query
         if (p.mask == STREAM_MASK_SLIDING) m = m || (k0 <= qtok0 + QT - 1 - p.window);         // keys before a window
@@ -282,7 +294,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     float lr_run[NQ];
     const float c2 = p.scale_log2e;
     // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
-    constexpr bool PIPE = NK == 1 && (BF16 || D == 64);
+    constexpr bool PIPE = !ARB && NK == 1 && (BF16 || D == 64);
     // The pipelined loop reads the Q fragments from the accumulation registers (an MFMA takes
     // its B operand from either file), which leaves the vector registers to the scores.
     u32x4_t qacc[NQ][FR];
@@ -368,7 +380,14 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         const int tq = qtok0 + cq * 32 + col;
                         // (a select, not a conditional store: `if (!visible) acc_s[..][i] = -inf` on a
                         // vector element was dropped by this compiler inside the lambda)
-                        const bool visible = (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                        bool visible = tk < L;
+                        if constexpr (ARB) {
+                            // the word of this lane's query row that holds keys ktok0 + rb*32 .. +31
+                            const unsigned cwd = tq < L ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + rb)] : 0u;
+                            visible = visible & ((cwd >> ((i >> 2) * 8 + gh * 4 + (i & 3))) & 1u);
+                        } else {
+                            visible = visible & mask_token(p.mask, p.window, tq, tk);
+                        }
                         acc_s[rb][cq][i] = visible ? acc_s[rb][cq][i] : -INFINITY;
                     }
         }
@@ -780,7 +799,14 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                     for (int i = 0; i < 16; ++i) {
                         const int tq = qtok0 + rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
                         const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
-                        colsum += ((tq < L) & mask_token(p.mask, p.window, tq, tk)) ? e : 0.f;
+                        bool visible = tq < L;
+                        if constexpr (ARB) {
+                            const unsigned cwd = tq < L ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + ck)] : 0u;
+                            visible = visible & ((cwd >> col) & 1u);
+                        } else {
+                            visible = visible & mask_token(p.mask, p.window, tq, tk);
+                        }
+                        colsum += visible ? e : 0.f;
                     }
             }
             colsum += __shfl_xor(colsum, 32);
@@ -796,35 +822,41 @@ typedef void (*attn_fn)(const AttnParams);
 // group in flight the scores, the K/V fragments and the Q tile fit the 256 architectural VGPRs
 // and the output accumulators live in the accumulation registers.
 template <int PASS, int OCC, bool BF16, int D, int NQ, int BQ>
-static attn_fn pick_attn_kernel_bk(int bk)
+static attn_fn pick_attn_kernel_bk(int bk, bool arb)
 {
+    if (arb) {
+        if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC, true>;
+        if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC, true>;
+        return attn_kernel<BF16, D, NQ, 1, BQ, 128, PASS, OCC, true>;
+    }
     if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC>;
     if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC>;
     return attn_kernel<BF16, D, NQ, 1, BQ, 128, PASS, OCC>;
 }
 
 template <int PASS, int OCC, bool BF16, int D>
-static attn_fn pick_attn_kernel_d(int bq, int bk)
+static attn_fn pick_attn_kernel_d(int bq, int bk, bool arb)
 {
     constexpr int OCC2 = (BF16 || D == 64) ? OCC : 1;
-    if (bq == 32) return pick_attn_kernel_bk<PASS, OCC, BF16, D, 1, 32>(bk);
-    if (bq == 64) return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 64>(bk);
-    return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 128>(bk);
+    if (bq == 32) return pick_attn_kernel_bk<PASS, OCC, BF16, D, 1, 32>(bk, arb);
+    if (bq == 64) return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 64>(bk, arb);
+    return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 128>(bk, arb);
 }
 
 template <int PASS, int OCC>
 static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
 {
     qsub = pb.b == 128 ? 2 : 1;
+    const bool arb = pb.mask == STREAM_MASK_ARRAY;
     if (pb.dtype == STREAM_BF16)
-        return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, true, 128>(pb.b, pb.bk)
-                           : pick_attn_kernel_d<PASS, OCC, true, 64>(pb.b, pb.bk);
-    return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, false, 128>(pb.b, pb.bk)
-                       : pick_attn_kernel_d<PASS, OCC, false, 64>(pb.b, pb.bk);
+        return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, true, 128>(pb.b, pb.bk, arb)
+                           : pick_attn_kernel_d<PASS, OCC, true, 64>(pb.b, pb.bk, arb);
+    return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, false, 128>(pb.b, pb.bk, arb)
+                       : pick_attn_kernel_d<PASS, OCC, false, 64>(pb.b, pb.bk, arb);
 }
 
 struct AttnWorkspace {
-    size_t kp, vp, lse2, total;
+    size_t kp, vp, lse2, cany, call, total;
 };
 
 static AttnWorkspace attn_layout(const Problem &pb)
@@ -834,7 +866,12 @@ static AttnWorkspace attn_layout(const Problem &pb)
     w.kp = 0;
     w.vp = tile;
     w.lse2 = 2 * tile;
-    w.total = 2 * tile + align_up((size_t)pb.H * pb.T * 4, 256);
+    size_t off = 2 * tile + align_up((size_t)pb.H * pb.T * 4, 256);
+    // block-level summaries of an explicit mask array
+    const size_t bm = pb.mask == STREAM_MASK_ARRAY ? align_up((size_t)pb.NB * block_bitmap_words(pb) * 4, 256) : 0;
+    w.cany = off; off += bm;
+    w.call = off; off += bm;
+    w.total = off;
     return w;
 }
 
@@ -918,6 +955,13 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
     p.T = pb.T; p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.kmax = topk_max;
     p.scale_log2e = scale * 1.4426950408889634f;
     p.mask = pb.mask; p.window = pb.window;
+    p.cbits = pb.cbits; p.cpitch = pb.cpitch;
+    p.call = (const unsigned *)(ws + w.call);
+    p.cw = pb.mask == STREAM_MASK_ARRAY ? block_bitmap_words(pb) : 0;
+    if (pb.mask == STREAM_MASK_ARRAY) {
+        rc = launch_block_bitmaps(pb, (unsigned *)(ws + w.cany), (unsigned *)(ws + w.call), st);
+        if (rc != STREAM_OK) return rc;
+    }
     p.seqs = pb.seqs;
     p.lse2 = mass ? (float *)(ws + w.lse2) : nullptr;
     for (int pass = 1; pass <= (mass ? 2 : 1); ++pass) {

@@ -456,6 +456,7 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     Problem pb;
     stream_status rc = make_problem(shape, 0, nullptr, 0, &pb);
     if (rc != STREAM_OK) return rc;
+    if (pb.mask == STREAM_MASK_ARRAY) return STREAM_EUNSUPPORTED;   // the statistics take the three rules
     const long long q_sh = shape->q_stride_h ? shape->q_stride_h : pb.T * pb.d;
     const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;
     const long long k_sh = shape->k_stride_h ? shape->k_stride_h : pb.T * pb.d;

@@ -117,6 +117,31 @@ def test_bad_arguments_of_prune(lib):
     assert call(sh=bad) == B.STREAM_EINVAL
 
 
+def test_bad_arguments_of_the_mask_array(lib):
+    fake = ctypes.c_void_p(4096)
+    ws = ctypes.c_void_p(256 * 16)
+
+    def prune(s):
+        return lib.stream_prune(fake, fake, ctypes.byref(s), 8, None, 8, fake, fake, None, None, ws, 1 << 40, None)
+
+    arr = dict(mask=B.MASKS["array"], mask_bits=8192, mask_pitch=32)          # T = 1000: 32 words per row
+    assert lib.stream_prune_workspace_bytes(ctypes.byref(shape(**arr)), 8) > \
+        lib.stream_prune_workspace_bytes(ctypes.byref(shape()), 8)            # + the block summaries
+    assert prune(shape(**{**arr, "mask_bits": None})) == B.STREAM_EINVAL
+    assert prune(shape(**{**arr, "mask_bits": 8194})) == B.STREAM_EINVAL      # words are 4-byte aligned
+    assert prune(shape(**{**arr, "mask_pitch": 31})) == B.STREAM_EINVAL       # rows shorter than T bits
+    cu = (ctypes.c_int * 3)(0, 600, 1000)
+    two = shape(batch=2, cu_seqlens=ctypes.cast(cu, ctypes.POINTER(ctypes.c_int)), **arr)
+    assert prune(two) == B.STREAM_EUNSUPPORTED                                 # single sequence only
+    ks = (ctypes.c_int * 2)(8, 4)
+    rc = lib.stream_prune_multi(fake, fake, ctypes.byref(shape(**arr)), ks, 2, 8, fake, fake, None, None,
+                                ws, 1 << 40, None)
+    assert rc == B.STREAM_EUNSUPPORTED
+    rc = lib.stream_receiver_stats(fake, fake, ctypes.byref(shape(**arr)), 0.125, None, fake, fake, fake,
+                                   ws, 1 << 40, None)
+    assert rc == B.STREAM_EUNSUPPORTED
+
+
 def test_bad_arguments_of_sparse_attn(lib):
     s = shape()
     fake = ctypes.c_void_p(4096)

@@ -109,3 +109,53 @@ def test_variable_k_and_split_levels_with_mask_array():
     with pytest.raises(binding.StreamError) as e:
         binding.stream_prune(Qd, Kd, 4, 2, 64, 8, mask_bits=bits[:, :3].contiguous())   # rows too short
     assert e.value.code == 1
+
+
+def attn_case(w, C, bk=0):
+    Q, K, V, _ = wl.make_inputs(w)
+    k = w.topk[0]
+    Qf, Kf, Vf = Q.float().numpy(), K.float().numpy(), V.float().numpy()
+    Cu = C.astype(np.uint8)
+    ref_p = so.prune(Qf, Kf, w.heads, w.kv_heads, w.block, k, block_k=bk or None, C=Cu)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    out = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), w.heads, w.kv_heads, w.block,
+                                     torch.from_numpy(ref_p["idx"]).to(DEV), torch.from_numpy(ref_p["cnt"]).to(DEV),
+                                     scale, want_lse=True, want_mass=True, block_k=bk, mask_bits=pack_bits(C))
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Qf, Kf, Vf, w.heads, w.kv_heads, w.block, ref_p["idx"], ref_p["cnt"], scale,
+                         block_k=bk or None, C=Cu)
+    glse, gO = out["lse"].cpu().numpy(), out["O"].float().cpu().numpy()
+    empty = np.isneginf(ref["lse"])
+    assert np.isneginf(glse[empty]).all() and (gO[empty] == 0).all()
+    err = np.abs(gO - ref["O"]).max()
+    lerr = np.abs(np.where(empty, 0.0, glse - np.where(empty, 0.0, ref["lse"]))).max()
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    merr = (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max()
+    print(f"[array-attn] max|dO|={err:.3e} max|dlse|={lerr:.3e} mass rel err={merr:.3e} "
+          f"queries without a key={int(empty.sum())}", flush=True)
+    assert err <= TOL[w.dtype] and lerr <= 1e-3 and merr <= 1e-3
+    np.testing.assert_allclose(mass.sum(axis=1), w.T - empty.sum(axis=1), rtol=1e-4)
+    return out
+
+
+@pytest.mark.parametrize("name", ["causal", "sliding", "random", "documents", "blank_rows"])
+@pytest.mark.parametrize("bq,bk,dtype,d,T", [(64, 0, "bf16", 128, 64 * 30 + 9), (32, 0, "f32", 64, 32 * 40 + 3),
+                                              (128, 0, "bf16", 128, 128 * 14 + 77), (32, 128, "bf16", 128, 2000),
+                                              (128, 32, "bf16", 64, 2000), (64, 0, "f32", 128, 64 * 12 + 1)])
+def test_attention_with_mask_array(name, bq, bk, dtype, d, T):
+    w = wl.scaled(wl.config(2), (T,), topk=5, heads=4, kv_heads=2, block=bq, dtype=dtype, head_dim=d,
+                  needles_per_kv_head=2)
+    C = masks(T, 5)[name]
+    print(f"[array-attn] {name} b_q={bq} b_k={bk or bq} {dtype} T={T}", flush=True)
+    out = attn_case(w, C, bk)
+    if name in ("causal", "sliding"):
+        # the same mask as a rule, same lists: the rule-based kernels agree (summation order differs)
+        Q, K, V, _ = wl.make_inputs(w)
+        Qf, Kf = Q.float().numpy(), K.float().numpy()
+        ref_p = so.prune(Qf, Kf, w.heads, w.kv_heads, bq, 5, block_k=bk or None, C=C.astype(np.uint8))
+        rule = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), w.heads, w.kv_heads, bq,
+                                          torch.from_numpy(ref_p["idx"]).to(DEV), torch.from_numpy(ref_p["cnt"]).to(DEV),
+                                          1.0 / math.sqrt(d), want_lse=True, block_k=bk, mask=name, window=150)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(rule["lse"].cpu().numpy(), out["lse"].cpu().numpy(), atol=1e-4)
+        assert (rule["O"].float() - out["O"].float()).abs().max().item() <= TOL[dtype]
