@@ -793,6 +793,13 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 // (the empty asm keeps this a real branch: merged into the path above, the mask
                 // arithmetic would run on every sub-tile)
                 asm volatile("" ::: "memory");
+                // ARB: lane j fetches the mask word of query row j for this 32-key group; an
+                // element takes its row's word from the lane that fetched it
+                unsigned rowword = 0u;
+                if constexpr (ARB) {
+                    const int tqr = qtok0 + lane;
+                    if (lane < QT && tqr < L) rowword = p.cbits[(long long)tqr * p.cpitch + ((ktok0 >> 5) + ck)];
+                }
 #pragma unroll
                 for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
@@ -801,7 +808,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[rq][ck][i], c2, -lq[rq][i]));
                         bool visible = tq < L;
                         if constexpr (ARB) {
-                            const unsigned cwd = tq < L ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + ck)] : 0u;
+                            const unsigned cwd = (unsigned)__shfl((int)rowword, rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3));
                             visible = visible & ((cwd >> col) & 1u);
                         } else {
                             visible = visible & mask_token(p.mask, p.window, tq, tk);

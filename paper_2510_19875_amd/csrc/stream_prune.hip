@@ -309,6 +309,20 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                 // 32x32 accumulator layout: lane holds column (lane % 32); element i is row
                 // 8*(i/4) + 4*(lane/32) + (i%4).
                 const int ktok0 = r * BK + kh * 32 * NG;
+                // ARB: lane j fetches the mask words of query row j (and j + 64) of this tile, one per
+                // 32-key group; an element then takes its row's word from the lane that fetched it
+                constexpr int RS = (32 * MB + 63) / 64;
+                unsigned rowword[RS][NG];
+                if constexpr (ARB) {
+#pragma unroll
+                    for (int sl = 0; sl < RS; ++sl) {
+                        const int tq = qtok0 + sl * 64 + lane;
+                        const bool ok = (sl * 64 + lane < 32 * MB) & (tq < L);
+#pragma unroll
+                        for (int cb = 0; cb < NG; ++cb)
+                            rowword[sl][cb] = ok ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + cb)] : 0u;
+                    }
+                }
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
@@ -319,8 +333,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                             const int tk = ktok0 + cb * 32 + (lane & 31);
                             bool visible = (tq < L) & (tk < L);
                             if constexpr (ARB) {
-                                // the word of row tq that holds keys ktok0 + cb*32 .. +31 (same for all lanes of a half)
-                                const unsigned cwd = tq < L ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + cb)] : 0u;
+                                const int src = (rb & 1) * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                                const unsigned cwd = (unsigned)__shfl((int)rowword[rb >> 1][cb], src);
                                 visible = visible & ((cwd >> (lane & 31)) & 1u);
                             } else {
                                 visible = visible & mask_token(p.mask, p.window, tq, tk);
