@@ -195,7 +195,7 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
  *              `levels` = stream_prune_levels() of the smallest k; tiles_scored counts the
  *              block scores actually computed; levels_per_launch is ignored
  *   workspace  stream_prune_multi_workspace_bytes(shape, n_k, topk_max) bytes, 256-byte aligned
- * Errors: as stream_prune; STREAM_EUNSUPPORTED when n_k > 32 and for STREAM_MASK_ARRAY.
+ * Errors: as stream_prune; STREAM_EUNSUPPORTED when n_k > 32.
  */
 size_t stream_prune_multi_workspace_bytes(const stream_shape *shape, int n_k, int topk_max);
 

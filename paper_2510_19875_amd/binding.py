@@ -221,7 +221,7 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
 def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
                        topk_list: Sequence[int], cu_seqlens: Optional[Sequence[int]] = None,
                        want_score: bool = False, want_tiles: bool = False, workspace=None, out=None,
-                       mask="causal", window: int = 0, block_k: int = 0):
+                       mask="causal", window: int = 0, block_k: int = 0, mask_bits=None):
     """Algorithm 2 for several k over the same Q, K in one call.  Returns dict(idx
     [H, n_k, NB, kmax] int32, cnt [H, n_k, NB] int32, score (optional) fp32, tiles (optional))."""
     lib = load()
@@ -229,7 +229,7 @@ def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: i
         raise ValueError("Q and K must be device tensors (the library has no CPU path)")
     H, T, d = Q.shape
     shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
-                             mask=mask, window=window, block_k=block_k)
+                             mask=mask, window=window, block_k=block_k, mask_bits=mask_bits)
     ks = [int(x) for x in topk_list]
     n_k, kmax = len(ks), max(ks)
     k_arr = (ctypes.c_int * n_k)(*ks)

@@ -491,10 +491,10 @@ static level_fn pick_level_kernel_t(const Problem &pb, int &wpr)
                        : pick_level_kernel_d<MULTI, false, 64, ARB>(pb.b, pb.bk, wpr);
 }
 
-// (a sweep over k with an explicit mask array is not built: nullptr)
 static level_fn pick_level_kernel(const Problem &pb, bool multi, int &wpr)
 {
-    if (pb.mask == STREAM_MASK_ARRAY) return multi ? nullptr : pick_level_kernel_t<false, true>(pb, wpr);
+    if (pb.mask == STREAM_MASK_ARRAY)
+        return multi ? pick_level_kernel_t<true, true>(pb, wpr) : pick_level_kernel_t<false, true>(pb, wpr);
     return multi ? pick_level_kernel_t<true, false>(pb, wpr) : pick_level_kernel_t<false, false>(pb, wpr);
 }
 

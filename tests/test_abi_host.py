@@ -133,10 +133,6 @@ def test_bad_arguments_of_the_mask_array(lib):
     cu = (ctypes.c_int * 3)(0, 600, 1000)
     two = shape(batch=2, cu_seqlens=ctypes.cast(cu, ctypes.POINTER(ctypes.c_int)), **arr)
     assert prune(two) == B.STREAM_EUNSUPPORTED                                 # single sequence only
-    ks = (ctypes.c_int * 2)(8, 4)
-    rc = lib.stream_prune_multi(fake, fake, ctypes.byref(shape(**arr)), ks, 2, 8, fake, fake, None, None,
-                                ws, 1 << 40, None)
-    assert rc == B.STREAM_EUNSUPPORTED
     rc = lib.stream_receiver_stats(fake, fake, ctypes.byref(shape(**arr)), 0.125, None, fake, fake, fake,
                                    ws, 1 << 40, None)
     assert rc == B.STREAM_EUNSUPPORTED

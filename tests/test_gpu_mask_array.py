@@ -106,6 +106,15 @@ def test_variable_k_and_split_levels_with_mask_array():
     valid = Cp.reshape(Tp // 64, 64, Tp // 64, 64).any(axis=(1, 3)).sum(axis=1)
     want = np.minimum(np.clip(-(-valid // 4), 1, 8), valid)
     np.testing.assert_array_equal(v["cnt"].cpu().numpy(), np.broadcast_to(want, (4, Tp // 64)))
+    # the k sweep with the array: result i equals the single call
+    ks = [8, 3, 1, 5]
+    m = binding.stream_prune_multi(Qd, Kd, 4, 2, 64, ks, want_score=True, mask_bits=bits)
+    for i, k in enumerate(ks):
+        one = binding.stream_prune(Qd, Kd, 4, 2, 64, k, want_score=True, mask_bits=bits)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(m["idx"][:, i, :, :k].cpu().numpy(), one["idx"].cpu().numpy())
+        np.testing.assert_array_equal(m["cnt"][:, i].cpu().numpy(), one["cnt"].cpu().numpy())
+        np.testing.assert_array_equal(m["score"][:, i, :, :k].cpu().numpy(), one["score"].cpu().numpy())
     with pytest.raises(binding.StreamError) as e:
         binding.stream_prune(Qd, Kd, 4, 2, 64, 8, mask_bits=bits[:, :3].contiguous())   # rows too short
     assert e.value.code == 1
