@@ -1,18 +1,23 @@
 /*
  * stream.h - C ABI of the MI355X (gfx950) Stream library.
  *
- * Two operations of the paper's method, each a sequence of HIP kernels:
+ * The two operations of the paper's method on the hot path, each a sequence of HIP kernels:
  *
  *   stream_prune        Algorithm 2 ("Stream", Appendix C; prose in Section 3):
  *                       hierarchical, binary-search-style estimation of a
  *                       per-head block-sparse attention mask that keeps the
- *                       top-k key blocks of every query block under the causal
- *                       mask C, in O(T log T) time and O(T) memory.
+ *                       top-k key blocks of every query block under the
+ *                       attention mask C, in O(T log T) time and O(T) memory.
  *   stream_sparse_attn  Eq. (2): softmax attention restricted to the retained
- *                       blocks (mask M, causal inside blocks), plus the column
+ *                       blocks (mask M, C inside blocks), plus the column
  *                       sums of the probabilities (the "vertical attention
  *                       scores" of Section 4.1 = attention mass received by
  *                       every key).
+ *
+ * and what the paper builds around them: stream_prune_multi (the sweep over k of the tracing
+ * driver), stream_prune_variable (a sparsity constant per row), stream_select_update (the
+ * selection step alone), stream_mask_diff (difference of two estimated masks),
+ * stream_receiver_stats (block means of the dense pattern and their vertical kurtosis).
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller unless it is
@@ -159,10 +164,13 @@ size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_ma
 
 /*
  * Eq. (2) on the retained blocks:  for every real query token t of query block q,
- *     S~[t,u] = scale * <Q_t, K_u>  for keys u of the blocks idx[h, q, 0..cnt-1] with u <= t,
+ *     S~[t,u] = scale * <Q_t, K_u>  for keys u of the blocks idx[h, q, 0..cnt-1] that the mask C
+ *                                   of `shape` shows to t (causal: u <= t),
  *     P~ = softmax(S~),  O_t = sum_u P~[t,u] V_u.
+ * A query that sees none of its row's retained keys (possible under a window or a mask array)
+ * gets O_t = 0 and lse = -inf.
  *
- *   idx, cnt      as written by stream_prune (any ascending block lists with ids <= q work)
+ *   idx, cnt      as written by stream_prune (any ascending lists of valid key-block ids work)
  *   scale         multiplies the dot products (the paper's Eq. (2) has scale = 1; models use
  *                 1/sqrt(head_dim))
  *   O             [heads, T, head_dim] in the input dtype
