@@ -26,6 +26,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_FP32_MFMA_TFLOPS = 157.3    # MI355X fp32 (the contraction of the fp32 workload)
+
+
+def mfma_peak(dtype: str) -> float:
+    return PEAK_BF16_MFMA_TFLOPS if dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
 PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per level-kernel launch at the headline workload, from the
 # rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/cfg3_pmc_counters.txt, per
@@ -200,7 +205,7 @@ def main():
         "attn_ms": float(np.mean(attn_ms)),
         "prune_only_value": tok_heads / (float(np.mean(prune_ms)) * 1e-3),
         "attn_tflops": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12,
-        "attn_frac_of_mfma_peak": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+        "attn_frac_of_mfma_peak": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12 / mfma_peak(w.dtype),
         "level_kernel_ms": [float(x) for x in level_ms.mean(axis=0)],
         "levels": levels, "level_kernel_launches_per_step": n_launch,
         "tiles_scored_per_step": float(np.mean(tile_counts)),
@@ -213,9 +218,9 @@ def main():
                       "level_kernel (branch scorer + top-k select + in-place compaction)",
             "bound": "mfma",
             "achieved": achieved_tflops,
-            "peak": PEAK_BF16_MFMA_TFLOPS,
+            "peak": mfma_peak(w.dtype),
             "unit": "TFLOP/s",
-            "frac": achieved_tflops / PEAK_BF16_MFMA_TFLOPS,
+            "frac": achieved_tflops / mfma_peak(w.dtype),
             "flop_per_launch": float(flops_per_step.sum() / launches),
             "avg_launch_ms": float(level_ms.sum() / launches),
             "launches": launches,
@@ -389,7 +394,7 @@ def block_shapes(w, layer, scale, reps=3):
     Q, K, V = layer
     out = {}
     for bq, bk in ((32, 128), (128, 32), (64, 128), (128, 64)):
-        k = w.topk[0] * w.block // bk
+        k = max(1, min(64, w.topk[0] * w.block // bk))        # the library keeps at most 64 blocks per row
         st = {}
 
         def prune():
@@ -448,7 +453,7 @@ def receiver_stats(w, layer, scale, reps=2):
     N = w.blocks_per_seq[0]
     flop = 2.0 * w.heads * (N * (N + 1) / 2) * 2.0 * w.block * w.block * w.head_dim
     return {"ms": ms, "tflops": flop / (ms * 1e-3) / 1e12, "bound": "mfma",
-            "frac_of_mfma_peak": flop / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+            "frac_of_mfma_peak": flop / (ms * 1e-3) / 1e12 / mfma_peak(w.dtype),
             "max_column_kurtosis_head0": float(st["out"]["head"][0, 0, 0].item())}
 
 
