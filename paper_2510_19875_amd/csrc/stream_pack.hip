@@ -167,6 +167,7 @@ struct BitmapParams {
     int T, bq, bk, nq, nk, words;
 };
 
+template <int WPB>   // 32-bit words of a row per key block: b_k / 32
 __global__ void __launch_bounds__(64) block_bitmap_kernel(BitmapParams p)
 {
     const int lane = threadIdx.x;
@@ -176,16 +177,19 @@ __global__ void __launch_bounds__(64) block_bitmap_kernel(BitmapParams p)
     if (r < p.nk && (long long)r * p.bk < p.T && (long long)q * p.bq < p.T) {
         const int t0 = q * p.bq, u0 = r * p.bk;
         const int t1 = t0 + p.bq < p.T ? t0 + p.bq : p.T;
-        const int wpb = p.bk / 32;
         unsigned acc_or = 0, acc_and = ~0u;
-        for (int t = t0; t < t1; ++t)
-            for (int w = 0; w < wpb; ++w) {
-                const int ub = u0 + w * 32;                       // first key of this word
-                unsigned x = 0;
-                if (ub < p.T) {
-                    x = p.cbits[(long long)t * p.cpitch + (ub >> 5)];
-                    if (ub + 32 > p.T) x &= (1u << (p.T - ub)) - 1u;   // keys past the end do not exist
-                }
+        unsigned keep[WPB];                                       // keys past the end do not exist
+#pragma unroll
+        for (int w = 0; w < WPB; ++w) {
+            const int ub = u0 + w * 32;                           // first key of this word
+            keep[w] = ub >= p.T ? 0u : (ub + 32 > p.T ? (1u << (p.T - ub)) - 1u : ~0u);
+        }
+        const unsigned *src = p.cbits + (long long)t0 * p.cpitch + (u0 >> 5);
+#pragma unroll 8
+        for (int t = t0; t < t1; ++t, src += p.cpitch)
+#pragma unroll
+            for (int w = 0; w < WPB; ++w) {
+                const unsigned x = keep[w] ? src[w] & keep[w] : 0u;   // (words wholly past the end are not read)
                 acc_or |= x;
                 acc_and &= x;
             }
@@ -217,7 +221,10 @@ stream_status launch_block_bitmaps(const Problem &pb, unsigned *any_bits, unsign
     p.nq = pb.NB; p.nk = (int)((long long)pb.NB * pb.b / pb.bk);
     p.words = block_bitmap_words(pb);
     if (pb.NB > 65535) return STREAM_EUNSUPPORTED;                 // grid.y
-    hipLaunchKernelGGL(block_bitmap_kernel, dim3((unsigned)((p.nk + 63) / 64), (unsigned)pb.NB), dim3(64), 0, st, p);
+    const dim3 grid((unsigned)((p.nk + 63) / 64), (unsigned)pb.NB);
+    if (pb.bk == 32) hipLaunchKernelGGL(block_bitmap_kernel<1>, grid, dim3(64), 0, st, p);
+    else if (pb.bk == 64) hipLaunchKernelGGL(block_bitmap_kernel<2>, grid, dim3(64), 0, st, p);
+    else hipLaunchKernelGGL(block_bitmap_kernel<4>, grid, dim3(64), 0, st, p);
     return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
 }
 
