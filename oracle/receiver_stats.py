@@ -23,6 +23,11 @@ probability matrix of one (head, sequence) in memory:
              vert_kurt = excess kurtosis of col_mean over the columns of the sequence that
              hold a real key (0 for fewer than 4 columns): the per-head statistic of the thought-anchors work the
              section follows, with blocks in place of sentences.
+
+The arithmetic is pinned (tests/test_receiver_stats_oracle_pins.py: closed forms, brute force,
+library kurtosis).  Which of the two head numbers the section means by "maximum vertical
+kurtosis" is a reading of one sentence; the paper prints no value that would decide it: parity
+unpinned for that choice, both numbers are returned.
 """
 from __future__ import annotations
 
