@@ -130,3 +130,34 @@ def test_fixed_reference_falls_back_to_the_tracked_order(kind):
     np.testing.assert_allclose(out["lse"].cpu().numpy(), ref["lse"], rtol=1e-5, atol=1e-3)
     mass = out["mass"].cpu().numpy().astype(np.float64)
     assert (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max() <= 1e-3
+
+
+def test_strided_inputs_and_output():
+    """Token-major [T, H, d] storage (one fused projection buffer) viewed as [H, T, d], for Q, K,
+    V and the output: same results as the contiguous call, for the attention and for the
+    receiver statistics."""
+    w = wl.scaled(wl.config(2), (64 * 33 + 11,), topk=4, heads=4, kv_heads=2, needles_per_kv_head=1)
+    dev = torch.device("cuda:0")
+    Q, K, V, _ = wl.make_inputs(w)
+    Qd, Kd, Vd = Q.to(dev), K.to(dev), V.to(dev)
+    T, d = w.T, w.head_dim
+    fused = torch.empty((T, w.heads + 2 * w.kv_heads, d), dtype=Qd.dtype, device=dev)
+    fused[:, :w.heads] = Qd.transpose(0, 1)
+    fused[:, w.heads:w.heads + w.kv_heads] = Kd.transpose(0, 1)
+    fused[:, w.heads + w.kv_heads:] = Vd.transpose(0, 1)
+    Qs = fused[:, :w.heads].transpose(0, 1)
+    Ks = fused[:, w.heads:w.heads + w.kv_heads].transpose(0, 1)
+    Vs = fused[:, w.heads + w.kv_heads:].transpose(0, 1)
+    assert not Qs.is_contiguous() and Qs.stride(1) == (w.heads + 2 * w.kv_heads) * d
+    scale = 1.0 / math.sqrt(d)
+    p = binding.stream_prune(Qs, Ks, w.heads, w.kv_heads, w.block, 4)
+    a = binding.stream_sparse_attn(Qd, Kd, Vd, w.heads, w.kv_heads, w.block, p["idx"], p["cnt"], scale, want_lse=True)
+    O_tok = torch.zeros((T, w.heads, d), dtype=Qd.dtype, device=dev)       # token-major output
+    b = binding.stream_sparse_attn(Qs, Ks, Vs, w.heads, w.kv_heads, w.block, p["idx"], p["cnt"], scale,
+                                   want_lse=True, out={"O": O_tok.transpose(0, 1), "lse": torch.empty_like(a["lse"])})
+    torch.cuda.synchronize()
+    assert torch.equal(a["O"], O_tok.transpose(0, 1)) and torch.equal(a["lse"], b["lse"])
+    ra = binding.stream_receiver_stats(Qd, Kd, w.heads, w.kv_heads, w.block, scale)
+    rb = binding.stream_receiver_stats(Qs, Ks, w.heads, w.kv_heads, w.block, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(ra["col_mean"], rb["col_mean"]) and torch.equal(ra["head"], rb["head"])
