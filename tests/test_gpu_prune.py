@@ -171,3 +171,38 @@ def test_levels_per_launch_does_not_change_the_result(block, seq_lens, k):
     for o in outs[1:]:
         for x in ("idx", "cnt", "score", "trace", "tiles"):
             np.testing.assert_array_equal(o[x], outs[0][x], err_msg=x)
+
+
+def test_two_streams_with_their_own_workspaces():
+    """Two different problems enqueued on two streams at once (separate workspaces and outputs):
+    each equals its result when run alone."""
+    dev = torch.device("cuda:0")
+    ws = [wl.scaled(wl.config(2), (64 * 90 + 3,), topk=8, heads=8, kv_heads=2),
+          wl.scaled(wl.config(2), (128 * 50 + 70,), topk=5, heads=4, kv_heads=4, block=128)]
+    data = []
+    for w in ws:
+        Q, K, V, _ = wl.make_inputs(w)
+        data.append((Q.to(dev), K.to(dev), V.to(dev)))
+    import math
+
+    def run(i):
+        w = ws[i]
+        Q, K, V = data[i]
+        p = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, w.topk[0], want_score=True)
+        a = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, w.block, p["idx"], p["cnt"],
+                                       1.0 / math.sqrt(w.head_dim), want_lse=True)
+        return p, a
+
+    alone = [run(0), run(1)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    both = [None, None]
+    for rep in range(3):
+        for i in (0, 1):
+            with torch.cuda.stream(streams[i]):
+                both[i] = run(i)
+    for s in streams:
+        s.synchronize()
+    for i in (0, 1):
+        assert torch.equal(alone[i][0]["idx"], both[i][0]["idx"]) and torch.equal(alone[i][0]["score"], both[i][0]["score"])
+        assert torch.equal(alone[i][1]["O"], both[i][1]["O"]) and torch.equal(alone[i][1]["lse"], both[i][1]["lse"])
