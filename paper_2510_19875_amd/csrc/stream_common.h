@@ -10,7 +10,8 @@
 namespace stream {
 
 constexpr int kMaxBatch = 32;   // sequence descriptors travel as kernel arguments
-constexpr int kMaxTopk = 64;    // one node per lane of a 64-wide wavefront
+constexpr int kMaxTopk = 64;    // one node per lane of a 64-wide wavefront (narrow kernels)
+constexpr int kMaxTopkWide = 512;   // stream_prune / stream_prune_variable / stream_sparse_attn: lists of up to 512 blocks
 constexpr int kXcds = 8;        // MI355X: 8 XCDs, workgroups are dealt to them round-robin
 
 // One sequence of the packed batch.

@@ -82,7 +82,7 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
     }
     if (tok != s->T) return STREAM_EINVAL;
     if (nb > (1LL << 30)) return STREAM_EUNSUPPORTED;
-    if (topk_max > kMaxTopk) return STREAM_EUNSUPPORTED;
+    if (topk_max > kMaxTopkWide) return STREAM_EUNSUPPORTED;
     p.NB = (int)nb;
     p.max_levels = maxlev;
     return STREAM_OK;
@@ -249,7 +249,7 @@ long long stream_num_key_blocks(const stream_shape *shape)
 int stream_prune_levels(const stream_shape *shape, int topk, const int *topk_per_seq)
 {
     stream::Problem pb;
-    if (stream::make_problem(shape, topk, topk_per_seq, stream::kMaxTopk, &pb) != STREAM_OK)
+    if (stream::make_problem(shape, topk, topk_per_seq, stream::kMaxTopkWide, &pb) != STREAM_OK)
         return -1;
     return pb.max_levels;
 }

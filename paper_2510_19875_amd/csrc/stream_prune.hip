@@ -10,59 +10,11 @@
 // caller splits a row's levels over several launches): O(T) memory either way.
 // Variants of the same kernel: a sweep over several k with a per-row cache of block scores
 // (stream_prune_multi) and a sparsity constant per row (stream_prune_variable).
-#include "stream_mfma.h"
-#include "stream_select.h"
+#include "stream_prune.h"
 
 #include <math.h>
 
 namespace stream {
-
-constexpr int kMaxSweep = 32;        // values of k in one stream_prune_multi call
-constexpr int kScoreCache = 1024;    // entries of a row's block-score cache (k sweep)
-
-struct PruneParams {
-    const char *Q;
-    const char *Kp;              // packed K tiles [kv_head][global block][b * d]
-    long long q_sh_b, q_st_b;    // byte strides of Q (head, token)
-    int H, g, NB, kmax;
-    int level_begin, level_end;  // 1-based refinement levels this launch runs for every row
-    int max_levels;              // levels of the deepest row (length of the trace)
-    int *nf, *nl;                // node ranges [H, NB, kmax]
-    float *ns;                   // node scores (score of the node's representative block)
-    int *ncnt;                   // live nodes per row [H, NB]
-    int *idx, *cnt;              // outputs, written by a row's last level
-    float *score;                // nullable
-    unsigned long long *tiles;   // nullable diagnostic counter
-    int *trace;                  // nullable diagnostic [max_levels, H, NB, kmax, 2]
-    WgMap map;
-    SeqTable seqs;
-    int mask, window;            // the mask rule C (stream_mask) and its window
-    // STREAM_MASK_ARRAY (ARB kernels): the bit array C, its block-level summaries [NB, cw] (any =
-    // C^blk of Alg. 2, all = no token-level test needed) and the words per row of either
-    const unsigned *cbits, *cany, *call;
-    long long cpitch;
-    int cw;
-    int vk_num, vk_den, vk_min;  // variable k (vk_den > 0): k(row) = clamp(ceil(valid * num / den), min, kmax)
-    int n_k;                     // k sweep (MULTI kernels): values of k, outputs [H, n_k, NB, ...]
-    int klist[kMaxSweep];
-};
-
-// max(1, ceil(log2(ceil(N / k)))): the levels after which every node is a single block
-__host__ __device__ __forceinline__ int levels_for(int N, int k)
-{
-    const int per = (N + k - 1) / k;
-    int lv = 0;
-    for (long long v = 1; v < per; v <<= 1) ++lv;
-    return lv < 1 ? 1 : lv;
-}
-
-// k of a row under the variable-k rule: a fixed share of the row's valid key blocks
-__host__ __device__ __forceinline__ int variable_k(int valid, int num, int den, int kmin, int kmax)
-{
-    long long k = ((long long)valid * num + den - 1) / den;
-    k = k < kmin ? kmin : k;
-    return (int)(k > kmax ? kmax : k);
-}
 
 // Template parameters: element type, head dim, 32-row groups of Q per wavefront (MB), 32-key
 // groups of K per wavefront (NG), wavefronts per row (WPR: 1, or 4 = 2 query halves x 2 key
@@ -438,10 +390,12 @@ static PruneWorkspace prune_layout(const Problem &pb)
     size_t off = 0;
     const size_t rows = (size_t)pb.H * pb.NB;
     w.kp = off;   off += align_up((size_t)pb.Hkv * pb.NB * pb.b * pb.d * pb.esize, 256);
-    // node lists: used only when a row's levels are split over several launches
-    w.nf = off;   off += align_up(rows * pb.kmax * 4, 256);
-    w.nl = off;   off += align_up(rows * pb.kmax * 4, 256);
-    w.ns = off;   off += align_up(rows * pb.kmax * 4, 256);
+    // node lists: used only when a row's levels are split over several launches (never by the
+    // wide kernel, whose lists live in LDS)
+    const size_t kk = pb.kmax > kMaxTopk ? 0 : (size_t)pb.kmax;
+    w.nf = off;   off += align_up(rows * kk * 4, 256);
+    w.nl = off;   off += align_up(rows * kk * 4, 256);
+    w.ns = off;   off += align_up(rows * kk * 4, 256);
     w.ncnt = off; off += align_up(rows * 4, 256);
     // block-level summaries of an explicit mask array
     const size_t bm = pb.mask == STREAM_MASK_ARRAY ? align_up((size_t)pb.NB * block_bitmap_words(pb) * 4, 256) : 0;
@@ -520,9 +474,11 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     // 16-byte vector loads: base pointers and strides must keep rows 16-byte aligned
     if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
     if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
+    const bool wide = pb.kmax > kMaxTopk;       // more than one node per lane: the LDS-list kernel
+    if (wide && (multi || !level_wide_supported(pb))) return STREAM_EUNSUPPORTED;
     int wpr = 1;
-    level_fn fn = pick_level_kernel(pb, multi, wpr);
-    if (!fn) return STREAM_EUNSUPPORTED;
+    level_fn fn = wide ? nullptr : pick_level_kernel(pb, multi, wpr);
+    if (!wide && !fn) return STREAM_EUNSUPPORTED;
     const PruneWorkspace w = prune_layout(pb);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return STREAM_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -555,6 +511,16 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     p.vk_num = vk.num; p.vk_den = vk.den; p.vk_min = vk.kmin;
     p.n_k = multi ? n_k : 1;
     for (int i = 0; i < kMaxSweep; ++i) p.klist[i] = multi && i < n_k ? topk_list[i] : 0;
+    if (wide) {
+        // every row runs all its levels in one launch (levels_per_launch does not apply)
+        void *const *evw = diag ? diag->level_events : nullptr;
+        p.level_begin = 1; p.level_end = pb.max_levels;
+        if (evw && hipEventRecord((hipEvent_t)evw[0], st) != hipSuccess) return STREAM_EDEVICE;
+        rc = launch_level_wide(pb, p, st);
+        if (rc != STREAM_OK) return rc;
+        if (evw && hipEventRecord((hipEvent_t)evw[1], st) != hipSuccess) return STREAM_EDEVICE;
+        return STREAM_OK;
+    }
     const long long rows_per_kv = (long long)pb.NB * pb.g;
     const long long per_kv = wpr == 1 ? (rows_per_kv + 3) / 4 : rows_per_kv;
     if (per_kv * pb.Hkv + 64 > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
