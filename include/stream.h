@@ -143,7 +143,9 @@ size_t stream_prune_workspace_bytes(const stream_shape *shape, int topk_max);
  *   topk          k, the number of key blocks kept per query block (>= 1); k > N_s keeps every
  *                 causal block
  *   topk_per_seq  HOST int[batch] overriding topk per sequence, or NULL
- *   topk_max      row length of idx/score (>= every k in use, <= 64)
+ *   topk_max      row length of idx/score (>= every k in use, <= 512; beyond 64 a second kernel
+ *                 keeps the row's node list in on-chip memory instead of registers: no 128 x 128
+ *                 blocks, no mask array, no levels_per_launch split there)
  *   idx           int32 [heads, NB, topk_max]: retained key-block ids, ascending, padded with -1
  *   cnt           int32 [heads, NB]: number of retained blocks = min(k, valid key blocks of the
  *                 row) (causal: min(k, q+1))
@@ -170,7 +172,8 @@ size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_ma
  * A query that sees none of its row's retained keys (possible under a window or a mask array)
  * gets O_t = 0 and lse = -inf.
  *
- *   idx, cnt      as written by stream_prune (any ascending lists of valid key-block ids work)
+ *   idx, cnt      as written by stream_prune (any ascending lists of valid key-block ids work);
+ *                 topk_max <= 512 (beyond 64 not together with a mask array)
  *   scale         multiplies the dot products (the paper's Eq. (2) has scale = 1; models use
  *                 1/sqrt(head_dim))
  *   O             [heads, T, head_dim] in the input dtype
@@ -194,8 +197,8 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
  *
  * Result i (i < n_k) is exactly what stream_prune returns for topk = topk_list[i] (every
  * sequence of a ragged batch uses that same k):
- *   topk_list  HOST int[n_k], each in [1, topk_max]; n_k <= 32; any order (largest first reuses
- *              the most)
+ *   topk_list  HOST int[n_k], each in [1, topk_max]; n_k <= 32, topk_max <= 64; any order
+ *              (largest first reuses the most)
  *   idx        int32 [heads, n_k, NB, topk_max]
  *   cnt        int32 [heads, n_k, NB]
  *   score      float [heads, n_k, NB, topk_max] or NULL
@@ -223,7 +226,7 @@ stream_status stream_prune_multi(const void *Q, const void *K, const stream_shap
  * where valid(row) is the number of key blocks the mask C leaves to the row (q + 1 for the
  * causal mask).  Every row then runs Algorithm 2 as printed with its own k (and its own number
  * of levels).  Outputs as stream_prune: idx/score rows have topk_max entries, cnt = min(k(row),
- * valid(row)).  1 <= keep_num <= keep_den, 1 <= topk_min <= topk_max <= 64.  Workspace:
+ * valid(row)).  1 <= keep_num <= keep_den, 1 <= topk_min <= topk_max <= 512.  Workspace:
  * stream_prune_workspace_bytes(shape, topk_max).  diag->trace has stream_prune_levels(shape,
  * topk_min, NULL) levels.
  */

@@ -11,14 +11,12 @@
 // Pass 2 (only when the received mass is requested) recomputes S = Q K^T, where a lane owns one
 // key column, turns it into probabilities with the final row normalisers and adds the column
 // sums to mass[] with atomics.
-#include "stream_common.h"
+#include "stream_mfma.h"
 
 #include <math.h>
 
 namespace stream {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------------------------------------
 // V packing.  Per 32-key group and per 32-feature block db, fragment vf holds for lane
@@ -187,7 +185,9 @@ __device__ __forceinline__ void static_for(F &f)
 // separate launch with two wavefronts per SIMD so that one's exponentials overlap the other's MFMAs.
 // ARB: the mask C is an explicit bit array (STREAM_MASK_ARRAY): every sub-tile of a block that is
 // not wholly visible takes the token-level test against the array, in the plain order.
-template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC, bool ARB = false>
+// WIDE: block lists of more than 64 entries (up to kMaxTopkWide): the list sits in LDS instead of
+// one register, and the sub-tiles are taken in the plain order.
+template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC, bool ARB = false, bool WIDE = false>
 __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -261,15 +261,26 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     const unsigned lane_off = lane * 16;
     // the row's block list lives in one register (lane j holds entry j; lists have <= 64 entries)
     // and is read with a scalar lane select: no memory access inside the tile loops
-    const int my_blk = lane < n_blk ? my_idx[lane] : 0;
+    const int my_blk = !WIDE && lane < n_blk ? my_idx[lane] : 0;
+    __shared__ int s_blk[WIDE ? 4 : 1][WIDE ? kMaxTopkWide : 1];
+    if constexpr (WIDE) {
+        for (int i = lane; i < n_blk; i += 64) s_blk[wave][i] = my_idx[i];
+        wave_sync();
+    }
+    auto list_entry = [&](int i) -> int {        // i is wave-uniform
+        if constexpr (WIDE)
+            return __builtin_amdgcn_readfirstlane(s_blk[wave][i]);
+        else
+            return __builtin_amdgcn_readlane(my_blk, i);
+    };
     auto tile_off = [&](int t) -> unsigned {
         const int ts = __builtin_amdgcn_readfirstlane(t);
-        const int r = __builtin_amdgcn_readlane(my_blk, ts / KSUB);
+        const int r = list_entry(ts / KSUB);
         return (unsigned)r * (unsigned)TILE_BYTES + (unsigned)(ts % KSUB) * NK * GROUP_BYTES;
     };
     auto tile_ktok0 = [&](int t) -> int {
         const int ts = __builtin_amdgcn_readfirstlane(t);
-        const int r = __builtin_amdgcn_readlane(my_blk, ts / KSUB);
+        const int r = list_entry(ts / KSUB);
         return r * BK + (ts % KSUB) * KT;
     };
     // does the mask C (or the end of the sequence) cut through the sub-tile that starts at key k0?
@@ -294,7 +305,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     float lr_run[NQ];
     const float c2 = p.scale_log2e;
     // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
-    constexpr bool PIPE = !ARB && NK == 1 && (BF16 || D == 64);
+    constexpr bool PIPE = !ARB && !WIDE && NK == 1 && (BF16 || D == 64);
     // The pipelined loop reads the Q fragments from the accumulation registers (an MFMA takes
     // its B operand from either file), which leaves the vector registers to the scores.
     u32x4_t qacc[NQ][FR];
@@ -829,8 +840,13 @@ typedef void (*attn_fn)(const AttnParams);
 // group in flight the scores, the K/V fragments and the Q tile fit the 256 architectural VGPRs
 // and the output accumulators live in the accumulation registers.
 template <int PASS, int OCC, bool BF16, int D, int NQ, int BQ>
-static attn_fn pick_attn_kernel_bk(int bk, bool arb)
+static attn_fn pick_attn_kernel_bk(int bk, bool arb, bool wide)
 {
+    if (wide) {
+        if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC, false, true>;
+        if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC, false, true>;
+        return attn_kernel<BF16, D, NQ, 1, BQ, 128, PASS, OCC, false, true>;
+    }
     if (arb) {
         if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC, true>;
         if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC, true>;
@@ -842,12 +858,12 @@ static attn_fn pick_attn_kernel_bk(int bk, bool arb)
 }
 
 template <int PASS, int OCC, bool BF16, int D>
-static attn_fn pick_attn_kernel_d(int bq, int bk, bool arb)
+static attn_fn pick_attn_kernel_d(int bq, int bk, bool arb, bool wide)
 {
     constexpr int OCC2 = (BF16 || D == 64) ? OCC : 1;
-    if (bq == 32) return pick_attn_kernel_bk<PASS, OCC, BF16, D, 1, 32>(bk, arb);
-    if (bq == 64) return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 64>(bk, arb);
-    return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 128>(bk, arb);
+    if (bq == 32) return pick_attn_kernel_bk<PASS, OCC, BF16, D, 1, 32>(bk, arb, wide);
+    if (bq == 64) return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 64>(bk, arb, wide);
+    return pick_attn_kernel_bk<PASS, OCC2, BF16, D, 2, 128>(bk, arb, wide);
 }
 
 template <int PASS, int OCC>
@@ -855,11 +871,13 @@ static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
 {
     qsub = pb.b == 128 ? 2 : 1;
     const bool arb = pb.mask == STREAM_MASK_ARRAY;
+    const bool wide = pb.kmax > kMaxTopk;              // lists longer than one register of entries
+    if (wide && arb) return nullptr;                   // not built together
     if (pb.dtype == STREAM_BF16)
-        return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, true, 128>(pb.b, pb.bk, arb)
-                           : pick_attn_kernel_d<PASS, OCC, true, 64>(pb.b, pb.bk, arb);
-    return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, false, 128>(pb.b, pb.bk, arb)
-                       : pick_attn_kernel_d<PASS, OCC, false, 64>(pb.b, pb.bk, arb);
+        return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, true, 128>(pb.b, pb.bk, arb, wide)
+                           : pick_attn_kernel_d<PASS, OCC, true, 64>(pb.b, pb.bk, arb, wide);
+    return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, false, 128>(pb.b, pb.bk, arb, wide)
+                       : pick_attn_kernel_d<PASS, OCC, false, 64>(pb.b, pb.bk, arb, wide);
 }
 
 struct AttnWorkspace {
@@ -914,6 +932,11 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
     stream_status rc = make_problem(shape, 0, nullptr, 0, &pb);
     if (rc != STREAM_OK) return rc;
     pb.kmax = topk_max;
+    if (topk_max > kMaxTopkWide) return STREAM_EUNSUPPORTED;
+    {
+        int qsub_probe = 1;
+        if (!pick_attn_kernel<1, 1>(pb, qsub_probe)) return STREAM_EUNSUPPORTED;   // long lists with a mask array
+    }
     const long long dflt_h = pb.T * pb.d;
     const long long q_sh = shape->q_stride_h ? shape->q_stride_h : dflt_h;
     const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;

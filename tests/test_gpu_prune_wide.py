@@ -121,3 +121,71 @@ def test_wide_limits():
         with pytest.raises(binding.StreamError) as e:
             call()
         assert e.value.code == 2
+
+
+def attn_case(w, bk=0, mask="causal", window=0):
+    print(f"[wide-attn] {w.name} b_q={w.block} b_k={bk or w.block} k={w.topk} {mask}/{window}", flush=True)
+    Q, K, V, _ = wl.make_inputs(w)
+    cu = w.cu_seqlens if w.batch > 1 else None
+    topk = list(w.topk) if w.batch > 1 else w.topk[0]
+    Qf, Kf, Vf = Q.float().numpy(), K.float().numpy(), V.float().numpy()
+    ref_p = so.prune(Qf, Kf, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu, mask=mask, window=window,
+                     block_k=bk or None)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    out = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), w.heads, w.kv_heads, w.block,
+                                     torch.from_numpy(ref_p["idx"]).to(DEV), torch.from_numpy(ref_p["cnt"]).to(DEV),
+                                     scale, cu_seqlens=cu, want_lse=True, want_mass=True, mask=mask, window=window,
+                                     block_k=bk)
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Qf, Kf, Vf, w.heads, w.kv_heads, w.block, ref_p["idx"], ref_p["cnt"], scale,
+                         cu_seqlens=cu, mask=mask, window=window, block_k=bk or None)
+    glse, gO = out["lse"].cpu().numpy(), out["O"].float().cpu().numpy()
+    empty = np.isneginf(ref["lse"])
+    assert np.isneginf(glse[empty]).all() and (gO[empty] == 0).all()
+    err = np.abs(gO - ref["O"]).max()
+    lerr = np.abs(np.where(empty, 0.0, glse - np.where(empty, 0.0, ref["lse"]))).max()
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    merr = (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max()
+    print(f"[wide-attn] max|dO|={err:.3e} max|dlse|={lerr:.3e} mass rel err={merr:.3e}", flush=True)
+    assert err <= (2e-2 if w.dtype == "bf16" else 1e-4) and lerr <= 1e-3 and merr <= 1e-3
+    np.testing.assert_allclose(mass.sum(axis=1), w.T - empty.sum(axis=1), rtol=1e-4)
+    return out, ref_p
+
+
+@pytest.mark.parametrize("bq,bk,dtype,d,T,k,mask,window", [
+    (32, 0, "bf16", 128, 32 * 200 + 7, 65, "causal", 0), (32, 0, "bf16", 128, 32 * 200 + 7, 150, "causal", 0),
+    (64, 0, "bf16", 128, 64 * 120 + 9, 100, "causal", 0), (32, 0, "f32", 64, 32 * 150 + 3, 90, "sliding", 2000),
+    (128, 32, "bf16", 64, 5000, 140, "causal", 0), (32, 128, "bf16", 128, 9000, 66, "full", 0),
+    (64, 0, "f32", 128, 64 * 80 + 1, 72, "causal", 0), (128, 0, "bf16", 128, 128 * 90 + 5, 80, "causal", 0)])
+def test_wide_attention(bq, bk, dtype, d, T, k, mask, window):
+    w = wl.scaled(wl.config(2), (T,), topk=k, heads=2, kv_heads=1, block=bq, dtype=dtype, head_dim=d,
+                  needles_per_kv_head=2)
+    attn_case(w, bk, mask, window)
+
+
+def test_dense_attention_through_long_lists():
+    """k >= N keeps every causal block: Eq. (2) is then plain causal attention (torch's fused kernel)."""
+    T, H, d, b = 32 * 160, 4, 128, 32
+    w = wl.scaled(wl.config(2), (T,), topk=160, heads=H, kv_heads=H, block=b, needles_per_kv_head=1)
+    Q, K, V, _ = wl.make_inputs(w)
+    Qd, Kd, Vd = Q.to(DEV), K.to(DEV), V.to(DEV)
+    p = binding.stream_prune(Qd, Kd, H, H, b, 160)
+    a = binding.stream_sparse_attn(Qd, Kd, Vd, H, H, b, p["idx"], p["cnt"], 1.0 / math.sqrt(d))
+    ref = torch.nn.functional.scaled_dot_product_attention(Qd[None].float(), Kd[None].float(), Vd[None].float(),
+                                                           is_causal=True)[0]
+    torch.cuda.synchronize()
+    assert bool((p["cnt"][0] == torch.arange(1, 161, device=DEV)).all())
+    assert (a["O"].float() - ref).abs().max().item() <= 2e-2
+
+
+def test_wide_attention_ragged_and_limits():
+    w = wl.scaled(wl.config(5), (5000, 64 * 7, 1, 7000 + 13), topk=(70, 2, 1, 100), heads=7, kv_heads=1, block=32,
+                  anchors_per_seq=3)
+    attn_case(w)
+    w2 = wl.scaled(wl.config(2), (2048,), topk=8, heads=2, kv_heads=1, needles_per_kv_head=1)
+    Q, K, V, _ = wl.make_inputs(w2)
+    idx = torch.full((2, 32, 513), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((2, 32), dtype=torch.int32, device=DEV)
+    with pytest.raises(binding.StreamError) as e:
+        binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), 2, 1, 64, idx, cnt, 0.1)
+    assert e.value.code == 2
