@@ -197,8 +197,9 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
  *
  * Result i (i < n_k) is exactly what stream_prune returns for topk = topk_list[i] (every
  * sequence of a ragged batch uses that same k):
- *   topk_list  HOST int[n_k], each in [1, topk_max]; n_k <= 32, topk_max <= 64; any order
- *              (largest first reuses the most)
+ *   topk_list  HOST int[n_k], each in [1, topk_max]; n_k <= 32; any order (largest first reuses
+ *              the most).  topk_max <= 512; beyond 64 every value runs as a launch of its own
+ *              of the wide kernel (K still packed once, no reuse of scores between values)
  *   idx        int32 [heads, n_k, NB, topk_max]
  *   cnt        int32 [heads, n_k, NB]
  *   score      float [heads, n_k, NB, topk_max] or NULL

@@ -37,6 +37,7 @@ struct PruneParams {
     int vk_num, vk_den, vk_min;  // variable k (vk_den > 0): k(row) = clamp(ceil(valid * num / den), min, kmax)
     int n_k;                     // k sweep (MULTI kernels): values of k, outputs [H, n_k, NB, ...]
     int klist[kMaxSweep];
+    int wide_ki;                 // wide kernel in a sweep: which value of the list this launch runs
 };
 
 // max(1, ceil(log2(ceil(N / k)))): the levels after which every node is a single block

@@ -475,7 +475,7 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
     if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
     const bool wide = pb.kmax > kMaxTopk;       // more than one node per lane: the LDS-list kernel
-    if (wide && (multi || !level_wide_supported(pb))) return STREAM_EUNSUPPORTED;
+    if (wide && !level_wide_supported(pb)) return STREAM_EUNSUPPORTED;
     int wpr = 1;
     level_fn fn = wide ? nullptr : pick_level_kernel(pb, multi, wpr);
     if (!wide && !fn) return STREAM_EUNSUPPORTED;
@@ -511,13 +511,25 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     p.vk_num = vk.num; p.vk_den = vk.den; p.vk_min = vk.kmin;
     p.n_k = multi ? n_k : 1;
     for (int i = 0; i < kMaxSweep; ++i) p.klist[i] = multi && i < n_k ? topk_list[i] : 0;
+    p.wide_ki = 0;
     if (wide) {
-        // every row runs all its levels in one launch (levels_per_launch does not apply)
+        // every row runs all its levels in one launch (levels_per_launch does not apply); a sweep
+        // runs one launch per value of k, every sequence with that k
         void *const *evw = diag ? diag->level_events : nullptr;
-        p.level_begin = 1; p.level_end = pb.max_levels;
+        p.level_begin = 1;
         if (evw && hipEventRecord((hipEvent_t)evw[0], st) != hipSuccess) return STREAM_EDEVICE;
-        rc = launch_level_wide(pb, p, st);
-        if (rc != STREAM_OK) return rc;
+        for (int ki = 0; ki < p.n_k; ++ki) {
+            p.wide_ki = ki;
+            if (multi)
+                for (int sidx = 0; sidx < p.seqs.n; ++sidx) {
+                    SeqDesc &sd = p.seqs.d[sidx];
+                    sd.k = topk_list[ki];
+                    sd.levels = levels_for((int)((long long)sd.nblk * pb.b / pb.bk), sd.k);
+                }
+            p.level_end = pb.max_levels;
+            rc = launch_level_wide(pb, p, st);
+            if (rc != STREAM_OK) return rc;
+        }
         if (evw && hipEventRecord((hipEvent_t)evw[1], st) != hipSuccess) return STREAM_EDEVICE;
         return STREAM_OK;
     }

@@ -6,7 +6,7 @@
 // here in chunks of 64 nodes (split, list of blocks to score) or 64 branch positions (scores,
 // threshold search, compaction).  The tile loop is the narrow kernel's.  Large k means few levels
 // and hundreds of tiles per level, so the chunked bookkeeping is a small part of a row.
-// Mask rules only (no mask array), no sweep over k.
+// Mask rules only (no mask array).  A sweep over k runs one launch per value (no score cache).
 #include "stream_prune.h"
 
 namespace stream {
@@ -88,7 +88,7 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
     const int edge_num = q * BQ + BQ - 1 - p.window;
     const int edge_hi = p.mask == STREAM_MASK_SLIDING && edge_num >= 0 ? edge_num / BK : -1;
     const unsigned long long lt = (1ull << lane) - 1ull;
-    const long long row = (long long)h * p.NB + gb;
+    const long long row = ((long long)h * p.n_k + p.wide_ki) * p.NB + gb;   // n_k > 1: one launch per k of a sweep
     const long long o = row * p.kmax;
 
     // ---- node init line of Alg. 2: the non-empty ranges of the equal split, in order
@@ -263,7 +263,7 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
         float *nso = nsb[nxt_buf];
         int out_base = 0, eq_seen = 0;
         const bool last = level == levels;
-        int *tr = p.trace ? p.trace + (((long long)(level - 1) * p.H * p.NB + row) * p.kmax) * 2 : nullptr;
+        int *tr = p.trace ? p.trace + (((long long)(level - 1) * p.H * p.n_k * p.NB + row) * p.kmax) * 2 : nullptr;
         for (int c0 = 0; c0 < npos; c0 += 64) {
             const int pp = c0 + lane;
             const unsigned key = pp < npos ? s_key[pp] : 0u;
@@ -308,7 +308,7 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
         // rows that finish before the deepest one: their node list stays as it is
         if (last && p.trace)
             for (int lv = level + 1; lv <= p.max_levels; ++lv) {
-                int *t2 = p.trace + (((long long)(lv - 1) * p.H * p.NB + row) * p.kmax) * 2;
+                int *t2 = p.trace + (((long long)(lv - 1) * p.H * p.n_k * p.NB + row) * p.kmax) * 2;
                 for (int j = lane; j < p.kmax; j += 64) {
                     const bool lv_live = j < cnt;
                     t2[2 * j] = lv_live ? nfb[nxt_buf][j] : -1;

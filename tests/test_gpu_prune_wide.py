@@ -111,12 +111,45 @@ def test_wide_and_narrow_kernels_agree():
     assert torch.equal(a["score"], score[:, :, :64]) and bool((idx[:, :, 64] == -1).all())
 
 
+def test_wide_sweep_equals_single_calls():
+    """A sweep whose longest list has more than 64 blocks: result i is the single call with k_i
+    (rows of length max k, one launch of the wide kernel per value)."""
+    for w in (wl.scaled(wl.config(2), (32 * 500 + 7,), topk=8, heads=4, kv_heads=2, block=32, needles_per_kv_head=2),
+              wl.scaled(wl.config(5), (3000, 64 * 5, 1, 4000 + 13), topk=(8, 8, 8, 8), heads=3, kv_heads=1, block=64)):
+        Q, K, _, _ = wl.make_inputs(w, with_v=False)
+        Qd, Kd = Q.to(DEV), K.to(DEV)
+        cu = w.cu_seqlens if w.batch > 1 else None
+        ks = [100, 65, 8, 200, 1]
+        print(f"[wide-sweep] {w.name} b={w.block} ks={ks}", flush=True)
+        m = binding.stream_prune_multi(Qd, Kd, w.heads, w.kv_heads, w.block, ks, cu_seqlens=cu, want_score=True,
+                                       want_tiles=True)
+        torch.cuda.synchronize()
+        tiles = 0
+        for i, k in enumerate(ks):
+            a = binding.stream_prune(Qd, Kd, w.heads, w.kv_heads, w.block, k, cu_seqlens=cu, want_score=True,
+                                     want_tiles=True)
+            torch.cuda.synchronize()
+            tiles += int(a["tiles"].item())
+            assert torch.equal(m["cnt"][:, i], a["cnt"]), k
+            assert torch.equal(m["idx"][:, i, :, :k], a["idx"]), k
+            live = a["idx"] >= 0
+            assert torch.equal(m["score"][:, i, :, :k][live], a["score"][live]), k
+            assert bool((m["idx"][:, i, :, k:] == -1).all()), k
+        assert int(m["tiles"].item()) == tiles
+    # against the oracle directly, for one of the values
+    ref = so.prune(Q.float().numpy(), K.float().numpy(), w.heads, w.kv_heads, w.block, [100] * w.batch, cu_seqlens=cu)
+    np.testing.assert_array_equal(m["cnt"][:, 0].cpu().numpy(), ref["cnt"])
+    differ = int((m["idx"][:, 0, :, :100].cpu().numpy() != ref["idx"]).any(axis=2).sum())
+    print(f"[wide-sweep] k=100: {differ} rows differ from the oracle", flush=True)
+    assert differ <= 2
+
+
 def test_wide_limits():
     w = wl.scaled(wl.config(2), (4096,), topk=8, heads=2, kv_heads=1, needles_per_kv_head=1)
     Q, K, _, _ = wl.make_inputs(w, with_v=False)
     Qd, Kd = Q.to(DEV), K.to(DEV)
     for call in (lambda: binding.stream_prune(Qd, Kd, 2, 1, 64, 513),
-                 lambda: binding.stream_prune_multi(Qd, Kd, 2, 1, 64, [65, 8]),
+                 lambda: binding.stream_prune_multi(Qd, Kd, 2, 1, 128, [65, 8]),
                  lambda: binding.stream_prune(Qd, Kd, 2, 1, 128, 65)):        # 128 x 128 rows: narrow kernel only
         with pytest.raises(binding.StreamError) as e:
             call()
