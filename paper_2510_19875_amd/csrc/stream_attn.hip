@@ -186,7 +186,7 @@ __device__ __forceinline__ void static_for(F &f)
 // ARB: the mask C is an explicit bit array (STREAM_MASK_ARRAY): every sub-tile of a block that is
 // not wholly visible takes the token-level test against the array, in the plain order.
 // WIDE: block lists of more than 64 entries (up to kMaxTopkWide): the list sits in LDS instead of
-// one register, and the sub-tiles are taken in the plain order.
+// one register (a scalar read of LDS per sub-tile in place of a lane select); the loops are the same.
 template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC, bool ARB = false, bool WIDE = false>
 __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 {
@@ -305,7 +305,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     float lr_run[NQ];
     const float c2 = p.scale_log2e;
     // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
-    constexpr bool PIPE = !ARB && !WIDE && NK == 1 && (BF16 || D == 64);
+    constexpr bool PIPE = !ARB && NK == 1 && (BF16 || D == 64);
     // The pipelined loop reads the Q fragments from the accumulation registers (an MFMA takes
     // its B operand from either file), which leaves the vector registers to the scores.
     u32x4_t qacc[NQ][FR];
