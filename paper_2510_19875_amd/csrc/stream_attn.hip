@@ -184,7 +184,8 @@ __device__ __forceinline__ void static_for(F &f)
 // PASS 1: outputs O, lse (and the base-2 normalisers for pass 2).  PASS 2: received mass, a
 // separate launch with two wavefronts per SIMD so that one's exponentials overlap the other's MFMAs.
 // ARB: the mask C is an explicit bit array (STREAM_MASK_ARRAY): every sub-tile of a block that is
-// not wholly visible takes the token-level test against the array, in the plain order.
+// not wholly visible takes the token-level test against the array, in the plain order; the
+// pipelined loop takes the longest run of wholly visible sub-tiles of the list.
 // WIDE: block lists of more than 64 entries (up to kMaxTopkWide): the list sits in LDS instead of
 // one register (a scalar read of LDS per sub-tile in place of a lane select); the loops are the same.
 template <bool BF16, int D, int NQ, int NK, int BQ, int BK, int PASS, int OCC, bool ARB = false, bool WIDE = false>
@@ -284,16 +285,24 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         return r * BK + (ts % KSUB) * KT;
     };
     // does the mask C (or the end of the sequence) cut through the sub-tile that starts at key k0?
-    const unsigned *allrow = ARB ? p.call + (long long)gb * p.cw : nullptr;
     auto needs_mask = [&](int k0) -> bool {
-        if constexpr (ARB) {
-            const int r = k0 / BK;
-            return !((allrow[r >> 5] >> (r & 31)) & 1u);
-        }
         bool m = k0 + KT > L;
         if (p.mask != STREAM_MASK_FULL) m = m || (k0 + KT - 1 > qtok0);                       // keys after a query
         if (p.mask == STREAM_MASK_SLIDING) m = m || (k0 <= qtok0 + QT - 1 - p.window);         // keys before a window
         return m;
+    };
+    // ARB: bit j = list entry j is wholly visible to this query block (every pair real and set in
+    // C); one lane per entry looks it up once, the loops then test a scalar bit per sub-tile
+    unsigned long long allmask = 0;
+    if constexpr (ARB) {
+        const unsigned *allrow = p.call + (long long)gb * p.cw;
+        allmask = __ballot(lane < n_blk && ((allrow[my_blk >> 5] >> (my_blk & 31)) & 1u));
+    }
+    auto tile_masked = [&](int t) -> bool {      // t is wave-uniform
+        if constexpr (ARB)
+            return !((allmask >> (__builtin_amdgcn_readfirstlane(t) / KSUB)) & 1ull);
+        else
+            return needs_mask(tile_ktok0(t));
     };
 
     if constexpr (PASS == 1) {
@@ -305,7 +314,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     float lr_run[NQ];
     const float c2 = p.scale_log2e;
     // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
-    constexpr bool PIPE = !ARB && NK == 1 && (BF16 || D == 64);
+    constexpr bool PIPE = NK == 1 && (BF16 || D == 64);
     // The pipelined loop reads the Q fragments from the accumulation registers (an MFMA takes
     // its B operand from either file), which leaves the vector registers to the scores.
     u32x4_t qacc[NQ][FR];
@@ -337,9 +346,23 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     int tb = 0, t_end = 0;
     if constexpr (PIPE) {
         t_end = n_tiles;
-        while (t_end > 0 && needs_mask(tile_ktok0(t_end - 1))) --t_end;
+        while (t_end > 0 && tile_masked(t_end - 1)) --t_end;
         if (p.mask == STREAM_MASK_SLIDING)
-            while (tb < t_end && needs_mask(tile_ktok0(tb))) ++tb;
+            while (tb < t_end && tile_masked(tb)) ++tb;
+        if constexpr (ARB) {
+            // an array can cut any entry of the list: the pipeline takes the longest run of
+            // wholly visible sub-tiles (after the first sub-tile), the plain order the rest
+            int run_b = -1;
+            tb = t_end = n_tiles;
+            for (int t = 1; t <= n_tiles; ++t) {
+                const bool m = t == n_tiles || tile_masked(t);
+                if (!m && run_b < 0) run_b = t;
+                if (m && run_b >= 0) {
+                    if (t - run_b > t_end - tb) { tb = run_b; t_end = t; }
+                    run_b = -1;
+                }
+            }
+        }
         // the pipelined loop keeps the softmax reference fixed (see below): the sub-tile before
         // it always goes through the plain order, which sets the reference
         tb = tb < 1 ? 1 : tb;
@@ -380,7 +403,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 __builtin_amdgcn_sched_barrier(0);
             }
         // mask (raw scores): the rule C inside the tile, padded keys
-        if (needs_mask(ktok0)) {
+        if (tile_masked(t)) {
 #pragma unroll
             for (int rb = 0; rb < NK; ++rb)
 #pragma unroll
@@ -789,7 +812,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 kreg[ck][fr] = load_frag(krs, lane_off, knext, ck * FR + fr);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        const bool need_mask = needs_mask(ktok0) || (qtok0 + QT > L);
+        const bool need_mask = tile_masked(t) || (qtok0 + QT > L);
 #pragma unroll
         for (int ck = 0; ck < NK; ++ck) {
             const int tk = ktok0 + ck * 32 + col;

@@ -168,3 +168,49 @@ def test_attention_with_mask_array(name, bq, bk, dtype, d, T):
         torch.cuda.synchronize()
         np.testing.assert_allclose(rule["lse"].cpu().numpy(), out["lse"].cpu().numpy(), atol=1e-4)
         assert (rule["O"].float() - out["O"].float()).abs().max().item() <= TOL[dtype]
+
+
+@pytest.mark.parametrize("bq,dtype,d", [(64, "bf16", 128), (64, "bf16", 64), (32, "f32", 64), (128, "bf16", 128)])
+def test_attention_array_runs_between_cut_blocks(bq, dtype, d):
+    """Lists in which blocks the array cuts sit between runs of wholly visible ones, the longest
+    run at a different place per row (the pipelined loop takes one run, the plain order the
+    rest): every row lists all blocks up to its own, under a causal array with key stripes hidden."""
+    NBq = 40
+    T = bq * NBq - 11
+    t = np.arange(T)
+    C = t[None, :] <= t[:, None]
+    for blk, a, e in ((3, 5, 20), (9, 0, bq), (20, bq - 4, bq), (27, 1, 2)):
+        C[:, blk * bq + a: blk * bq + e] = False
+    C[t, t] = True
+    w = wl.scaled(wl.config(2), (T,), topk=NBq, heads=4, kv_heads=2, block=bq, dtype=dtype, head_dim=d,
+                  needles_per_kv_head=2)
+    Q, K, V, _ = wl.make_inputs(w)
+    idx = np.full((4, NBq, NBq), -1, dtype=np.int32)
+    cnt = np.zeros((4, NBq), dtype=np.int32)
+    for q in range(NBq):
+        idx[:, q, :q + 1] = np.arange(q + 1)
+        cnt[:, q] = q + 1
+    idx[1, :, :] = -1                                     # one head skips every third block
+    for q in range(NBq):
+        keep = [r for r in range(q + 1) if r % 3 != 1 or r == q]
+        idx[1, q, :len(keep)] = keep
+        cnt[1, q] = len(keep)
+    scale = 1.0 / math.sqrt(d)
+    print(f"[array-runs] b={bq} {dtype} d={d} T={T}", flush=True)
+    out = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), 4, 2, bq, torch.from_numpy(idx).to(DEV),
+                                     torch.from_numpy(cnt).to(DEV), scale, want_lse=True, want_mass=True,
+                                     mask_bits=pack_bits(C))
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Q.float().numpy(), K.float().numpy(), V.float().numpy(), 4, 2, bq, idx, cnt, scale,
+                         C=C.astype(np.uint8))
+    err = np.abs(out["O"].float().cpu().numpy() - ref["O"]).max()
+    lerr = np.abs(out["lse"].cpu().numpy() - ref["lse"]).max()
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    merr = (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max()
+    print(f"[array-runs] max|dO|={err:.3e} max|dlse|={lerr:.3e} mass rel err={merr:.3e}", flush=True)
+    assert err <= TOL[dtype] and lerr <= 1e-3 and merr <= 1e-3
+    # head 0 lists every block: that is dense attention under C
+    S = scale * (Q[0].double() @ K[0].double().T)
+    S = S.masked_fill(~torch.from_numpy(C), float("-inf"))
+    dense = torch.softmax(S, dim=1) @ V[0].double()
+    assert (out["O"][0].double().cpu() - dense).abs().max().item() <= TOL[dtype]
