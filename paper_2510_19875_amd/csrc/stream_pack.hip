@@ -168,11 +168,12 @@ struct BitmapParams {
 };
 
 template <int WPB>   // 32-bit words of a row per key block: b_k / 32
-__global__ void __launch_bounds__(64) block_bitmap_kernel(BitmapParams p)
+__global__ void __launch_bounds__(256) block_bitmap_kernel(BitmapParams p)
 {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     const int q = blockIdx.y;
-    const int r = blockIdx.x * 64 + lane;
+    const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);        // a wavefront per 64 key blocks: the
+    const int r = chunk * 64 + lane;                              // workgroup reads 256 adjacent ones
     bool any = false, all = false;
     if (r < p.nk && (long long)r * p.bk < p.T && (long long)q * p.bq < p.T) {
         const int t0 = q * p.bq, u0 = r * p.bk;
@@ -184,12 +185,18 @@ __global__ void __launch_bounds__(64) block_bitmap_kernel(BitmapParams p)
             const int ub = u0 + w * 32;                           // first key of this word
             keep[w] = ub >= p.T ? 0u : (ub + 32 > p.T ? (1u << (p.T - ub)) - 1u : ~0u);
         }
-        const unsigned *src = p.cbits + (long long)t0 * p.cpitch + (u0 >> 5);
-#pragma unroll 8
+        // (a word wholly past the end of the rows is not read: its lane reads the last real word
+        // in its place and masks it away, so that every load is unconditional and many are in flight)
+        const int lastw = (p.T - 1) >> 5;
+        int wofs[WPB];
+#pragma unroll
+        for (int w = 0; w < WPB; ++w) wofs[w] = (u0 >> 5) + w < lastw ? (u0 >> 5) + w : lastw;
+        const unsigned *src = p.cbits + (long long)t0 * p.cpitch;
+#pragma unroll 16
         for (int t = t0; t < t1; ++t, src += p.cpitch)
 #pragma unroll
             for (int w = 0; w < WPB; ++w) {
-                const unsigned x = keep[w] ? src[w] & keep[w] : 0u;   // (words wholly past the end are not read)
+                const unsigned x = src[wofs[w]] & keep[w];
                 acc_or |= x;
                 acc_and &= x;
             }
@@ -198,7 +205,7 @@ __global__ void __launch_bounds__(64) block_bitmap_kernel(BitmapParams p)
     }
     const unsigned long long ba = __ballot(any), bl = __ballot(all);
     if (lane == 0 || lane == 32) {
-        const int w = blockIdx.x * 2 + (lane >> 5);
+        const int w = chunk * 2 + (lane >> 5);
         if (w < p.words) {
             p.any_bits[(long long)q * p.words + w] = (unsigned)(ba >> lane);
             p.all_bits[(long long)q * p.words + w] = (unsigned)(bl >> lane);
@@ -221,10 +228,10 @@ stream_status launch_block_bitmaps(const Problem &pb, unsigned *any_bits, unsign
     p.nq = pb.NB; p.nk = (int)((long long)pb.NB * pb.b / pb.bk);
     p.words = block_bitmap_words(pb);
     if (pb.NB > 65535) return STREAM_EUNSUPPORTED;                 // grid.y
-    const dim3 grid((unsigned)((p.nk + 63) / 64), (unsigned)pb.NB);
-    if (pb.bk == 32) hipLaunchKernelGGL(block_bitmap_kernel<1>, grid, dim3(64), 0, st, p);
-    else if (pb.bk == 64) hipLaunchKernelGGL(block_bitmap_kernel<2>, grid, dim3(64), 0, st, p);
-    else hipLaunchKernelGGL(block_bitmap_kernel<4>, grid, dim3(64), 0, st, p);
+    const dim3 grid((unsigned)((p.nk + 255) / 256), (unsigned)pb.NB);
+    if (pb.bk == 32) hipLaunchKernelGGL(block_bitmap_kernel<1>, grid, dim3(256), 0, st, p);
+    else if (pb.bk == 64) hipLaunchKernelGGL(block_bitmap_kernel<2>, grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(block_bitmap_kernel<4>, grid, dim3(256), 0, st, p);
     return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
 }
 
