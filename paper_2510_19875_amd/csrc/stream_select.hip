@@ -52,6 +52,68 @@ __device__ __forceinline__ SelectRow<NB> select_load(const SelectParams &p, long
     return r;
 }
 
+// The selection of select_topk_wave with the search state kept in vector registers.  With many
+// wavefronts per SIMD (this pass has no matrix work to hide behind) what limits the search is the
+// scalar unit: it issues one instruction per wavefront turn and the scalar form of a step is seven
+// of them against one vector compare.  Here a step is: candidate = threshold | bit (vector),
+// compare (vector), count of the lane mask (scalar), count >= k and the conditional move
+// (vector), and the scalar test for the early exit: three scalar and four vector instructions.
+// The values are wave-uniform all the same; the empty asm below only hides that from the
+// compiler, which would otherwise move them back to the scalar unit.  Same result bit for bit.
+template <int NB>
+__device__ __forceinline__ void select_topk_wave_v(const float (&s)[NB], const bool (&v)[NB], int k, int lane,
+                                                   bool (&keep)[NB])
+{
+    unsigned u[NB];
+    int n_valid = 0;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const unsigned b = sortable_bits(s[i]);
+        u[i] = v[i] ? (b ? b : 1u) : 0u;
+        n_valid += __popcll(__ballot(v[i]));
+    }
+    if (n_valid <= k) {                           // wave-uniform
+#pragma unroll
+        for (int i = 0; i < NB; ++i) keep[i] = v[i];
+        return;
+    }
+    unsigned thr = 0;
+    int kv = k;
+    asm volatile("" : "+v"(thr), "+v"(kv));       // (a vector register each; see above)
+#pragma unroll
+    for (int bit = 31; bit >= 0; --bit) {
+        const unsigned t = thr | (1u << bit);
+        int ge = 0;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) ge += __popcll(__ballot(u[i] >= t));
+        thr = ge >= kv ? t : thr;
+        if (ge == k) break;
+    }
+    int n_ge = 0;                                 // (counted again: cheaper than a flag set in every step)
+#pragma unroll
+    for (int i = 0; i < NB; ++i) n_ge += __popcll(__ballot(u[i] >= thr));
+    if (n_ge == k) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) keep[i] = u[i] >= thr;
+        return;
+    }
+    // ties at the threshold
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int n_gt = 0;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) n_gt += __popcll(__ballot(u[i] > thr));
+    const int need = k - n_gt;
+    int before = 0;                               // equal branches at lower positions
+#pragma unroll
+    for (int i = 0; i < NB; ++i) before += __popcll(__ballot(u[i] == thr) & lt);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const bool eq = u[i] == thr;
+        keep[i] = u[i] > thr || (eq && before < need);
+        before += eq ? 1 : 0;                     // this lane's own lower position
+    }
+}
+
 template <int NB>
 __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
 {
@@ -81,7 +143,7 @@ __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
             v[0] = live && (right || m > f) && cur.s[0] > -INFINITY;
             first[0] = right ? m : f; last[0] = right ? l : m - 1;
         }
-        select_topk_wave<NB>(cur.s, v, p.k, lane, keep);
+        select_topk_wave_v<NB>(cur.s, v, p.k, lane, keep);
         // update: survivors overwrite the row's node list in positional order
         const unsigned long long lt = (1ull << lane) - 1ull;
         unsigned long long kb[NB];
