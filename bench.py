@@ -239,6 +239,9 @@ def main():
         result["variable_k"] = variable_k(w, layers[0])
         result["receiver_stats"] = receiver_stats(w, layers[0], scale)
         result["block_shapes"] = block_shapes(w, layers[0], scale)
+        result["wide_lists"] = wide_lists(w, layers[0], scale)
+        if w.T <= 262144:                                   # (T^2 / 8 bytes of mask)
+            result["mask_array"] = mask_array(w, layers[0], scale)
     if args.dense_reference and w.batch == 1:
         result["dense_reference"] = dense_reference(w, layers[0])
     if not args.no_cpu_baseline:
@@ -353,6 +356,96 @@ def mask_rules(w, layer, scale, reps=3):
             res[key] = e0.elapsed_time(e1) / reps
         res["retained_blocks"] = int(st["op"]["cnt"].sum().item())
         out[name] = res
+    return out
+
+
+def _timed_pair(prune, attn, reps):
+    import torch
+
+    res = {}
+    for key, fn in (("prune_ms", prune), ("attn_ms", attn)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[key] = e0.elapsed_time(e1) / reps
+    return res
+
+
+def wide_lists(w, layer, scale, reps=3):
+    """More than 64 blocks kept per row (the kernels that keep the row's lists in LDS), next to
+    k = 64 through the one-node-per-lane kernels: milliseconds per call and MFMA rates."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, V = layer
+    out = {}
+    for k in (64, 65, 128):
+        st = {}
+
+        def prune():
+            r = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, k, workspace=st.get("wp"),
+                                     out=st.get("op"), want_tiles=True)
+            st["wp"], st["op"], st["tiles"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}, r["tiles"]
+
+        def attn():
+            r = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, w.block, st["op"]["idx"], st["op"]["cnt"],
+                                           scale, want_lse=True, want_mass=True, workspace=st.get("wa"),
+                                           out=st.get("oa"))
+            st["wa"], st["oa"] = r["workspace"], {"O": r["O"], "lse": r["lse"], "mass": r["mass"]}
+
+        res = _timed_pair(prune, attn, reps)
+        tile_flop = 2.0 * w.block * w.block * w.head_dim
+        retained = int(st["op"]["cnt"].sum().item())
+        res["retained_blocks"] = retained
+        res["prune_tflops"] = int(st["tiles"].item()) * tile_flop / (res["prune_ms"] * 1e-3) / 1e12
+        res["attn_tflops"] = retained * 3 * tile_flop / (res["attn_ms"] * 1e-3) / 1e12
+        out[f"k{k}"] = res
+    return out
+
+
+def mask_array(w, layer, scale, reps=3):
+    """The mask C as an explicit T x T bit array (here: the causal mask written out) against the
+    causal rule: milliseconds per call, and whether the lists come out identical."""
+    import torch
+
+    from paper_2510_19875_amd import binding
+
+    Q, K, V = layer
+    T = w.T
+    W = (T + 31) // 32
+    bits = torch.empty((T, W), dtype=torch.int32, device=Q.device)
+    wd = torch.arange(W, device=Q.device)[None, :]
+    for t0 in range(0, T, 8192):
+        t = torch.arange(t0, min(T, t0 + 8192), device=Q.device)[:, None]
+        part = (torch.ones_like(t) << ((t % 32) + 1)) - 1               # bits 0 .. t % 32 (int64)
+        rows = torch.where(wd < t // 32, torch.full_like(part, 0xFFFFFFFF),
+                           torch.where(wd == t // 32, part, torch.zeros_like(part)))
+        bits[t0:t0 + rows.shape[0]] = ((rows + (1 << 31)) % (1 << 32) - (1 << 31)).to(torch.int32)
+    out = {"array_bytes": int(bits.numel() * 4)}
+    lists = {}
+    for name, kw in (("rule", {}), ("array", {"mask_bits": bits})):
+        st = {}
+
+        def prune():
+            r = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, w.topk[0], workspace=st.get("wp"),
+                                     out=st.get("op"), **kw)
+            st["wp"], st["op"] = r["workspace"], {"idx": r["idx"], "cnt": r["cnt"]}
+
+        def attn():
+            r = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, w.block, st["op"]["idx"], st["op"]["cnt"],
+                                           scale, want_lse=True, want_mass=True, workspace=st.get("wa"),
+                                           out=st.get("oa"), **kw)
+            st["wa"], st["oa"] = r["workspace"], {"O": r["O"], "lse": r["lse"], "mass": r["mass"]}
+
+        out[name] = _timed_pair(prune, attn, reps)
+        lists[name] = st["op"]["idx"].clone()
+    out["lists_identical"] = bool(torch.equal(lists["rule"], lists["array"]))
     return out
 
 
