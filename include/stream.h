@@ -145,7 +145,7 @@ size_t stream_prune_workspace_bytes(const stream_shape *shape, int topk_max);
  *   topk_per_seq  HOST int[batch] overriding topk per sequence, or NULL
  *   topk_max      row length of idx/score (>= every k in use, <= 512; beyond 64 a second kernel
  *                 keeps the row's node list in on-chip memory instead of registers: no 128 x 128
- *                 blocks, no mask array, no levels_per_launch split there)
+ *                 blocks and no levels_per_launch split there)
  *   idx           int32 [heads, NB, topk_max]: retained key-block ids, ascending, padded with -1
  *   cnt           int32 [heads, NB]: number of retained blocks = min(k, valid key blocks of the
  *                 row) (causal: min(k, q+1))
@@ -173,7 +173,7 @@ size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_ma
  * gets O_t = 0 and lse = -inf.
  *
  *   idx, cnt      as written by stream_prune (any ascending lists of valid key-block ids work);
- *                 topk_max <= 512 (beyond 64 not together with a mask array)
+ *                 topk_max <= 512
  *   scale         multiplies the dot products (the paper's Eq. (2) has scale = 1; models use
  *                 1/sqrt(head_dim))
  *   O             [heads, T, head_dim] in the input dtype

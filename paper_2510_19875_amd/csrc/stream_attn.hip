@@ -264,13 +264,23 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // and is read with a scalar lane select: no memory access inside the tile loops
     const int my_blk = !WIDE && lane < n_blk ? my_idx[lane] : 0;
     __shared__ int s_blk[WIDE ? 4 : 1][WIDE ? kMaxTopkWide : 1];
+    // ARB: "every pair of this query block and that key block is real and set in C", per key block
+    const unsigned *allrow = ARB ? p.call + (long long)gb * p.cw : nullptr;
+    auto all_bit = [&](int r) -> bool {          // (an entry outside the block range reads as "cut")
+        return (unsigned)r < (unsigned)p.cw * 32u && ((allrow[r >> 5] >> (r & 31)) & 1u);
+    };
     if constexpr (WIDE) {
-        for (int i = lane; i < n_blk; i += 64) s_blk[wave][i] = my_idx[i];
+        for (int i = lane; i < n_blk; i += 64) {
+            int v = my_idx[i];
+            // (with a mask array the top bit of an entry says that C cuts through the block)
+            if constexpr (ARB) v |= all_bit(v) ? 0 : (int)0x80000000;
+            s_blk[wave][i] = v;
+        }
         wave_sync();
     }
     auto list_entry = [&](int i) -> int {        // i is wave-uniform
         if constexpr (WIDE)
-            return __builtin_amdgcn_readfirstlane(s_blk[wave][i]);
+            return __builtin_amdgcn_readfirstlane(s_blk[wave][i]) & 0x7fffffff;
         else
             return __builtin_amdgcn_readlane(my_blk, i);
     };
@@ -294,12 +304,12 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // ARB: bit j = list entry j is wholly visible to this query block (every pair real and set in
     // C); one lane per entry looks it up once, the loops then test a scalar bit per sub-tile
     unsigned long long allmask = 0;
-    if constexpr (ARB) {
-        const unsigned *allrow = p.call + (long long)gb * p.cw;
-        allmask = __ballot(lane < n_blk && ((allrow[my_blk >> 5] >> (my_blk & 31)) & 1u));
-    }
+    if constexpr (ARB && !WIDE)
+        allmask = __ballot(lane < n_blk && all_bit(my_blk));
     auto tile_masked = [&](int t) -> bool {      // t is wave-uniform
-        if constexpr (ARB)
+        if constexpr (ARB && WIDE)
+            return __builtin_amdgcn_readfirstlane(s_blk[wave][__builtin_amdgcn_readfirstlane(t) / KSUB]) < 0;
+        else if constexpr (ARB)
             return !((allmask >> (__builtin_amdgcn_readfirstlane(t) / KSUB)) & 1ull);
         else
             return needs_mask(tile_ktok0(t));
@@ -417,7 +427,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         bool visible = tk < L;
                         if constexpr (ARB) {
                             // the word of this lane's query row that holds keys ktok0 + rb*32 .. +31
-                            const unsigned cwd = tq < L ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + rb)] : 0u;
+                            // (a word wholly past the end of the row is not read)
+                            const unsigned cwd = (tq < L) & ((unsigned)(ktok0 + rb * 32) < (unsigned)L) ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + rb)] : 0u;
                             visible = visible & ((cwd >> ((i >> 2) * 8 + gh * 4 + (i & 3))) & 1u);
                         } else {
                             visible = visible & mask_token(p.mask, p.window, tq, tk);
@@ -832,7 +843,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                 unsigned rowword = 0u;
                 if constexpr (ARB) {
                     const int tqr = qtok0 + lane;
-                    if (lane < QT && tqr < L) rowword = p.cbits[(long long)tqr * p.cpitch + ((ktok0 >> 5) + ck)];
+                    if (lane < QT && tqr < L && (unsigned)(ktok0 + ck * 32) < (unsigned)L)     // (no read of a word wholly past the end of the row)
+                        rowword = p.cbits[(long long)tqr * p.cpitch + ((ktok0 >> 5) + ck)];
                 }
 #pragma unroll
                 for (int rq = 0; rq < NQ; ++rq)
@@ -865,6 +877,11 @@ typedef void (*attn_fn)(const AttnParams);
 template <int PASS, int OCC, bool BF16, int D, int NQ, int BQ>
 static attn_fn pick_attn_kernel_bk(int bk, bool arb, bool wide)
 {
+    if (wide && arb) {
+        if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC, true, true>;
+        if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC, true, true>;
+        return attn_kernel<BF16, D, NQ, 1, BQ, 128, PASS, OCC, true, true>;
+    }
     if (wide) {
         if (bk == 32) return attn_kernel<BF16, D, NQ, 1, BQ, 32, PASS, OCC, false, true>;
         if (bk == 64) return attn_kernel<BF16, D, NQ, 1, BQ, 64, PASS, OCC, false, true>;
@@ -895,7 +912,6 @@ static attn_fn pick_attn_kernel(const Problem &pb, int &qsub)
     qsub = pb.b == 128 ? 2 : 1;
     const bool arb = pb.mask == STREAM_MASK_ARRAY;
     const bool wide = pb.kmax > kMaxTopk;              // lists longer than one register of entries
-    if (wide && arb) return nullptr;                   // not built together
     if (pb.dtype == STREAM_BF16)
         return pb.d == 128 ? pick_attn_kernel_d<PASS, OCC, true, 128>(pb.b, pb.bk, arb, wide)
                            : pick_attn_kernel_d<PASS, OCC, true, 64>(pb.b, pb.bk, arb, wide);

@@ -59,7 +59,7 @@ __host__ __device__ __forceinline__ int variable_k(int valid, int num, int den, 
 
 constexpr int kWideTopk = 512;       // blocks kept per row by the wide kernel (node lists in LDS)
 
-// Runs every row's levels in one launch of the wide kernel (rule masks; no sweep, no mask array).
+// Runs every row's levels in one launch of the wide kernel (p.wide_ki selects the k of a sweep).
 bool level_wide_supported(const Problem &pb);
 stream_status launch_level_wide(const Problem &pb, const PruneParams &p, hipStream_t st);
 

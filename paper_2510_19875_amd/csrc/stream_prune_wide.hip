@@ -6,7 +6,9 @@
 // here in chunks of 64 nodes (split, list of blocks to score) or 64 branch positions (scores,
 // threshold search, compaction).  The tile loop is the narrow kernel's.  Large k means few levels
 // and hundreds of tiles per level, so the chunked bookkeeping is a small part of a row.
-// Mask rules only (no mask array).  A sweep over k runs one launch per value (no score cache).
+// ARB: the mask C is an explicit bit array, handled as in the narrow kernel (representatives from
+// the block-level summary, token-level test against the array where a block is not wholly
+// visible).  A sweep over k runs one launch per value (no score cache).
 #include "stream_prune.h"
 
 namespace stream {
@@ -22,7 +24,7 @@ __device__ __forceinline__ float key_to_score(unsigned u)
     return __builtin_bit_cast(float, (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
 }
 
-template <bool BF16, int D, int MB, int NG, int OCC>
+template <bool BF16, int D, int MB, int NG, int OCC, bool ARB>
 __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -46,10 +48,29 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
     const int KM = p.kmax;
     int k = sd.k, levels = sd.levels;
     const int rmin = mask_rmin(p.mask, p.window, q, BQ, BK), rmax = mask_rmax(p.mask, q, BQ, BK, L);
+    // ARB: the block-level summaries of this query block (any pair visible / every pair visible)
+    const unsigned *anyrow = ARB ? p.cany + (long long)gb * p.cw : nullptr;
+    const unsigned *allrow = ARB ? p.call + (long long)gb * p.cw : nullptr;
     if (p.vk_den > 0) {
-        k = variable_k(rmax - rmin + 1, p.vk_num, p.vk_den, p.vk_min, p.kmax);
+        int valid = rmax - rmin + 1;
+        if constexpr (ARB) {
+            valid = 0;
+            for (int w = 0; w < p.cw; ++w) valid += __popc(anyrow[w]);
+        }
+        k = variable_k(valid, p.vk_num, p.vk_den, p.vk_min, p.kmax);
         levels = levels_for(N, k);
     }
+    // ARB: first key block of [a, b] that C^blk leaves to this row, or -1
+    auto first_valid = [&](int a, int b) -> int {
+        if (a > b) return -1;
+        for (int w = a >> 5; w <= (b >> 5); ++w) {
+            unsigned x = anyrow[w];
+            if (w == (a >> 5)) x &= ~0u << (a & 31);
+            if (w == (b >> 5) && (b & 31) != 31) x &= (1u << ((b & 31) + 1)) - 1u;
+            if (x) return w * 32 + __builtin_ctz(x);
+        }
+        return -1;
+    };
 
     // this wavefront's LDS arrays
     int *base = smem + wave * (kWideWordsPerK * KM);
@@ -121,11 +142,18 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
             const bool live = j < cnt;
             const int f = live ? nf[j] : 0, l = live ? nl[j] : -1;
             const int m = (f + l + 1) >> 1;
-            const int rep_p = f > rmin ? f : rmin;
-            const int rep0 = rep_p;
-            const int rep1 = m > rmin ? m : rmin;
-            const bool v0 = live && m > f && rep0 <= (m - 1 < rmax ? m - 1 : rmax);
-            const bool v1 = live && rep1 <= (l < rmax ? l : rmax);
+            int rep_p = f > rmin ? f : rmin;
+            int rep0 = rep_p;
+            int rep1 = m > rmin ? m : rmin;
+            bool v0 = live && m > f && rep0 <= (m - 1 < rmax ? m - 1 : rmax);
+            bool v1 = live && rep1 <= (l < rmax ? l : rmax);
+            if constexpr (ARB) {
+                rep0 = live ? first_valid(f, m - 1) : -1;
+                rep1 = live ? first_valid(m, l) : -1;
+                v0 = rep0 >= 0;
+                v1 = rep1 >= 0;
+                rep_p = v0 ? rep0 : rep1;                     // the node's first valid block
+            }
             const bool need0 = v0 && first;
             const bool need1 = v1 && (first || rep1 != rep_p);
             const unsigned long long b0 = __ballot(need0), b1 = __ballot(need1);
@@ -178,8 +206,9 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                 }
             }
             float mx = -INFINITY;
-            const bool cut = tail_row || (p.mask != STREAM_MASK_FULL && (r + 1) * BK - 1 > q * BQ) ||
-                             r <= edge_hi || (r + 1) * BK > L;
+            bool cut = tail_row || (p.mask != STREAM_MASK_FULL && (r + 1) * BK - 1 > q * BQ) ||
+                       r <= edge_hi || (r + 1) * BK > L;
+            if constexpr (ARB) cut = !((allrow[r >> 5] >> (r & 31)) & 1u);
             if (!cut) {
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
@@ -189,6 +218,21 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
             } else {
                 const int ktok0 = r * BK;
+                // ARB: lane j fetches the mask words of query row j (and j + 64) of this tile, one per
+                // 32-key group; an element then takes its row's word from the lane that fetched it
+                constexpr int RS = (32 * MB + 63) / 64;
+                unsigned rowword[RS][NG];
+                if constexpr (ARB) {
+#pragma unroll
+                    for (int sl = 0; sl < RS; ++sl) {
+                        const int tq = qtok0 + sl * 64 + lane;
+                        const bool ok = (sl * 64 + lane < 32 * MB) & (tq < L);
+#pragma unroll
+                        for (int cb = 0; cb < NG; ++cb)
+                            rowword[sl][cb] = ok & (ktok0 + cb * 32 < L)         // (not a word wholly past the end of the row)
+                                                  ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + cb)] : 0u;
+                    }
+                }
 #pragma unroll
                 for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
@@ -197,7 +241,14 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                         for (int i = 0; i < 16; ++i) {
                             const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
                             const int tk = ktok0 + cb * 32 + (lane & 31);
-                            const bool visible = (tq < L) & (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                            bool visible = (tq < L) & (tk < L);
+                            if constexpr (ARB) {
+                                const int src = (rb & 1) * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                                const unsigned cwd = (unsigned)__shfl((int)rowword[rb >> 1][cb], src);
+                                visible = visible & ((cwd >> (lane & 31)) & 1u);
+                            } else {
+                                visible = visible & mask_token(p.mask, p.window, tq, tk);
+                            }
                             mx = visible ? fmaxf(mx, acc[rb][cb][i]) : mx;
                         }
             }
@@ -321,31 +372,37 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
 
 typedef void (*wide_fn)(const PruneParams);
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool ARB>
 static wide_fn pick_wide(int bq, int bk)
 {
     constexpr int OCC2 = (BF16 || D == 64) ? 2 : 1;
     constexpr bool BIG = BF16 || D == 64;
     const int mb = bq / 32, ng = bk / 32;
-    if (mb == 1 && ng == 1) return level_wide_kernel<BF16, D, 1, 1, 2>;
-    if (mb == 2 && ng == 2) return level_wide_kernel<BF16, D, 2, 2, OCC2>;
-    if (mb == 1 && ng == 2) return level_wide_kernel<BF16, D, 1, 2, OCC2>;
-    if (mb == 2 && ng == 1) return level_wide_kernel<BF16, D, 2, 1, OCC2>;
-    if (mb == 1 && ng == 4) return level_wide_kernel<BF16, D, 1, 4, 1>;
-    if (mb == 4 && ng == 1) return level_wide_kernel<BF16, D, 4, 1, 1>;
+    if (mb == 1 && ng == 1) return level_wide_kernel<BF16, D, 1, 1, 2, ARB>;
+    if (mb == 2 && ng == 2) return level_wide_kernel<BF16, D, 2, 2, OCC2, ARB>;
+    if (mb == 1 && ng == 2) return level_wide_kernel<BF16, D, 1, 2, OCC2, ARB>;
+    if (mb == 2 && ng == 1) return level_wide_kernel<BF16, D, 2, 1, OCC2, ARB>;
+    if (mb == 1 && ng == 4) return level_wide_kernel<BF16, D, 1, 4, 1, ARB>;
+    if (mb == 4 && ng == 1) return level_wide_kernel<BF16, D, 4, 1, 1, ARB>;
     if constexpr (BIG) {
-        if (mb == 2 && ng == 4) return level_wide_kernel<BF16, D, 2, 4, 1>;
-        if (mb == 4 && ng == 2) return level_wide_kernel<BF16, D, 4, 2, 1>;
+        if (mb == 2 && ng == 4) return level_wide_kernel<BF16, D, 2, 4, 1, ARB>;
+        if (mb == 4 && ng == 2) return level_wide_kernel<BF16, D, 4, 2, 1, ARB>;
     }
     return nullptr;     // 128 x 128 rows take four wavefronts: narrow kernel only
 }
 
+template <bool ARB>
+static wide_fn pick_wide_mask(const Problem &pb)
+{
+    return pb.dtype == STREAM_BF16
+               ? (pb.d == 128 ? pick_wide<true, 128, ARB>(pb.b, pb.bk) : pick_wide<true, 64, ARB>(pb.b, pb.bk))
+               : (pb.d == 128 ? pick_wide<false, 128, ARB>(pb.b, pb.bk) : pick_wide<false, 64, ARB>(pb.b, pb.bk));
+}
+
 static wide_fn pick_wide_kernel(const Problem &pb)
 {
-    if (pb.kmax > kWideTopk || pb.mask == STREAM_MASK_ARRAY) return nullptr;
-    return pb.dtype == STREAM_BF16
-               ? (pb.d == 128 ? pick_wide<true, 128>(pb.b, pb.bk) : pick_wide<true, 64>(pb.b, pb.bk))
-               : (pb.d == 128 ? pick_wide<false, 128>(pb.b, pb.bk) : pick_wide<false, 64>(pb.b, pb.bk));
+    if (pb.kmax > kWideTopk) return nullptr;
+    return pb.mask == STREAM_MASK_ARRAY ? pick_wide_mask<true>(pb) : pick_wide_mask<false>(pb);
 }
 
 bool level_wide_supported(const Problem &pb) { return pick_wide_kernel(pb) != nullptr; }

@@ -214,3 +214,49 @@ def test_attention_array_runs_between_cut_blocks(bq, dtype, d):
     S = S.masked_fill(~torch.from_numpy(C), float("-inf"))
     dense = torch.softmax(S, dim=1) @ V[0].double()
     assert (out["O"][0].double().cpu() - dense).abs().max().item() <= TOL[dtype]
+
+
+@pytest.mark.parametrize("name", ["causal", "sliding", "random", "documents", "blank_rows"])
+@pytest.mark.parametrize("bq,bk,dtype,d,T,k", [(32, 0, "bf16", 128, 32 * 150 + 9, 70), (64, 0, "bf16", 128, 64 * 110 + 3, 100),
+                                                (32, 128, "f32", 64, 5000, 66), (128, 32, "bf16", 64, 4000, 90),
+                                                (64, 32, "f32", 128, 3000, 65)])
+def test_long_lists_with_mask_array(name, bq, bk, dtype, d, T, k):
+    """More than 64 blocks kept per row under an explicit array: Alg. 2 and Eq. (2) against the oracle
+    (the kernels that keep the row's lists in LDS)."""
+    w = wl.scaled(wl.config(2), (T,), topk=k, heads=2, kv_heads=1, block=bq, dtype=dtype, head_dim=d,
+                  needles_per_kv_head=2)
+    C = masks(T, 11)[name]
+    print(f"[array-wide] {name} b_q={bq} b_k={bk or bq} {dtype} T={T} k={k}", flush=True)
+    prune_case(w, C, bk)
+    attn_case(w, C, bk)
+
+
+def test_long_lists_with_cut_blocks_between_runs():
+    """Dense causal attention under an array with hidden key stripes through lists of 100 blocks."""
+    bq, d, NBq = 32, 128, 100
+    T = bq * NBq - 5
+    t = np.arange(T)
+    C = t[None, :] <= t[:, None]
+    for blk, a, e in ((3, 5, 20), (9, 0, bq), (40, bq - 4, bq), (77, 1, 2), (78, 0, 1)):
+        C[:, blk * bq + a: blk * bq + e] = False
+    C[t, t] = True
+    w = wl.scaled(wl.config(2), (T,), topk=NBq, heads=2, kv_heads=1, block=bq, head_dim=d, needles_per_kv_head=2)
+    Q, K, V, _ = wl.make_inputs(w)
+    idx = np.full((2, NBq, NBq), -1, dtype=np.int32)
+    cnt = np.zeros((2, NBq), dtype=np.int32)
+    for q in range(NBq):
+        idx[:, q, :q + 1] = np.arange(q + 1)
+        cnt[:, q] = q + 1
+    scale = 1.0 / math.sqrt(d)
+    out = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), 2, 1, bq, torch.from_numpy(idx).to(DEV),
+                                     torch.from_numpy(cnt).to(DEV), scale, want_lse=True, want_mass=True,
+                                     mask_bits=pack_bits(C))
+    torch.cuda.synchronize()
+    ref = so.sparse_attn(Q.float().numpy(), K.float().numpy(), V.float().numpy(), 2, 1, bq, idx, cnt, scale,
+                         C=C.astype(np.uint8))
+    err = np.abs(out["O"].float().cpu().numpy() - ref["O"]).max()
+    lerr = np.abs(out["lse"].cpu().numpy() - ref["lse"]).max()
+    mass = out["mass"].cpu().numpy().astype(np.float64)
+    merr = (np.abs(mass - ref["mass"]) / np.maximum(ref["mass"], 1.0)).max()
+    print(f"[array-wide-runs] max|dO|={err:.3e} max|dlse|={lerr:.3e} mass rel err={merr:.3e}", flush=True)
+    assert err <= TOL["bf16"] and lerr <= 1e-3 and merr <= 1e-3
