@@ -144,8 +144,8 @@ size_t stream_prune_workspace_bytes(const stream_shape *shape, int topk_max);
  *                 causal block
  *   topk_per_seq  HOST int[batch] overriding topk per sequence, or NULL
  *   topk_max      row length of idx/score (>= every k in use, <= 512; beyond 64 a second kernel
- *                 keeps the row's node list in on-chip memory instead of registers: no 128 x 128
- *                 blocks and no levels_per_launch split there)
+ *                 keeps the row's node list in on-chip memory instead of registers: no
+ *                 levels_per_launch split there, and no F32 with head_dim 128 in 128 x 128 blocks)
  *   idx           int32 [heads, NB, topk_max]: retained key-block ids, ascending, padded with -1
  *   cnt           int32 [heads, NB]: number of retained blocks = min(k, valid key blocks of the
  *                 row) (causal: min(k, q+1))

@@ -24,12 +24,15 @@ __device__ __forceinline__ float key_to_score(unsigned u)
     return __builtin_bit_cast(float, (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
 }
 
-template <bool BF16, int D, int MB, int NG, int OCC, bool ARB>
+// KH: a key block is scored in KH pieces of 32 * NG keys each (128 x 128 blocks: two pieces of 64
+// keys, the accumulators of a 128 x 128 tile do not fit one wavefront), the block's score being the
+// maximum over the pieces.
+template <bool BF16, int D, int MB, int NG, int KH, int OCC, bool ARB>
 __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int FR = D * ES / 32;
-    constexpr int BQ = 32 * MB, BK = 32 * NG;
+    constexpr int BQ = 32 * MB, BK = 32 * NG * KH;
     constexpr long long TILE_BYTES = (long long)BK * D * ES;
     extern __shared__ __align__(16) int smem[];
 
@@ -182,10 +185,13 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
-        for (int t = 0; t < nt; ++t) {
+        float mx_block = -INFINITY;
+        for (int u = 0; u < nt * KH; ++u) {
+            const int t = u / KH, piece = u % KH;
             const int r = __builtin_amdgcn_readfirstlane(s_rep[t]);
-            const int tn = t + 1 < nt ? t + 1 : t;
-            const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[tn]) * (unsigned)TILE_BYTES;
+            const int un = u + 1 < nt * KH ? u + 1 : u;
+            const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[un / KH]) * (unsigned)TILE_BYTES;
+            const int nxt_frag = (un % KH) * NG * FR;
             floatx16 acc[MB][NG];
 #pragma unroll
             for (int rb = 0; rb < MB; ++rb)
@@ -201,7 +207,7 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                     for (int rb = 0; rb < MB; ++rb)
                         acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
                     __builtin_amdgcn_sched_barrier(0);
-                    kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * FR + fr);
+                    kf[cb][fr] = load_frag(krs, lane_off, nxt, nxt_frag + cb * FR + fr);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -217,7 +223,7 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
 #pragma unroll
                         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
             } else {
-                const int ktok0 = r * BK;
+                const int ktok0 = r * BK + piece * 32 * NG;
                 // ARB: lane j fetches the mask words of query row j (and j + 64) of this tile, one per
                 // 32-key group; an element then takes its row's word from the lane that fetched it
                 constexpr int RS = (32 * MB + 63) / 64;
@@ -253,7 +259,8 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                         }
             }
             mx = wave_max(mx);
-            if (lane == 0) s_sc[t] = mx;
+            mx_block = piece == 0 ? mx : fmaxf(mx_block, mx);
+            if (lane == 0 && piece == KH - 1) s_sc[t] = mx_block;
         }
         tiles_done += (unsigned long long)nt;
         wave_sync();
@@ -378,17 +385,18 @@ static wide_fn pick_wide(int bq, int bk)
     constexpr int OCC2 = (BF16 || D == 64) ? 2 : 1;
     constexpr bool BIG = BF16 || D == 64;
     const int mb = bq / 32, ng = bk / 32;
-    if (mb == 1 && ng == 1) return level_wide_kernel<BF16, D, 1, 1, 2, ARB>;
-    if (mb == 2 && ng == 2) return level_wide_kernel<BF16, D, 2, 2, OCC2, ARB>;
-    if (mb == 1 && ng == 2) return level_wide_kernel<BF16, D, 1, 2, OCC2, ARB>;
-    if (mb == 2 && ng == 1) return level_wide_kernel<BF16, D, 2, 1, OCC2, ARB>;
-    if (mb == 1 && ng == 4) return level_wide_kernel<BF16, D, 1, 4, 1, ARB>;
-    if (mb == 4 && ng == 1) return level_wide_kernel<BF16, D, 4, 1, 1, ARB>;
+    if (mb == 1 && ng == 1) return level_wide_kernel<BF16, D, 1, 1, 1, 2, ARB>;
+    if (mb == 2 && ng == 2) return level_wide_kernel<BF16, D, 2, 2, 1, OCC2, ARB>;
+    if (mb == 1 && ng == 2) return level_wide_kernel<BF16, D, 1, 2, 1, OCC2, ARB>;
+    if (mb == 2 && ng == 1) return level_wide_kernel<BF16, D, 2, 1, 1, OCC2, ARB>;
+    if (mb == 1 && ng == 4) return level_wide_kernel<BF16, D, 1, 4, 1, 1, ARB>;
+    if (mb == 4 && ng == 1) return level_wide_kernel<BF16, D, 4, 1, 1, 1, ARB>;
     if constexpr (BIG) {
-        if (mb == 2 && ng == 4) return level_wide_kernel<BF16, D, 2, 4, 1, ARB>;
-        if (mb == 4 && ng == 2) return level_wide_kernel<BF16, D, 4, 2, 1, ARB>;
+        if (mb == 2 && ng == 4) return level_wide_kernel<BF16, D, 2, 4, 1, 1, ARB>;
+        if (mb == 4 && ng == 2) return level_wide_kernel<BF16, D, 4, 2, 1, 1, ARB>;
+        if (mb == 4 && ng == 4) return level_wide_kernel<BF16, D, 4, 2, 2, 1, ARB>;   // two pieces of 64 keys
     }
-    return nullptr;     // 128 x 128 rows take four wavefronts: narrow kernel only
+    return nullptr;     // fp32 with d = 128: the 128-row tiles do not fit
 }
 
 template <bool ARB>

@@ -106,7 +106,8 @@ def test_bad_arguments_of_prune(lib):
     assert call(topk=0) == B.STREAM_EINVAL
     assert call(topk=9, kmax=8) == B.STREAM_EINVAL          # k beyond the row length of idx
     assert call(topk=513, kmax=513) == B.STREAM_EUNSUPPORTED  # beyond the LDS node lists of the wide kernel
-    assert call(topk=65, kmax=65, sh=shape(block=128)) == B.STREAM_EUNSUPPORTED  # 128 x 128 rows: 64 at most
+    # fp32 rows of 128 queries at d = 128 fit no single wavefront: 64 blocks per row at most
+    assert call(topk=65, kmax=65, sh=shape(block=128, dtype=B.STREAM_F32)) == B.STREAM_EUNSUPPORTED
     assert call(Q=ctypes.c_void_p(4100)) == B.STREAM_EINVAL  # not 16-byte aligned
     assert call(sh=shape(q_stride_t=100)) == B.STREAM_EINVAL  # rows shorter than head_dim
     assert call(sh=shape(q_stride_t=132)) == B.STREAM_EINVAL  # rows not 16-byte aligned

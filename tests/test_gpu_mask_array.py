@@ -219,7 +219,7 @@ def test_attention_array_runs_between_cut_blocks(bq, dtype, d):
 @pytest.mark.parametrize("name", ["causal", "sliding", "random", "documents", "blank_rows"])
 @pytest.mark.parametrize("bq,bk,dtype,d,T,k", [(32, 0, "bf16", 128, 32 * 150 + 9, 70), (64, 0, "bf16", 128, 64 * 110 + 3, 100),
                                                 (32, 128, "f32", 64, 5000, 66), (128, 32, "bf16", 64, 4000, 90),
-                                                (64, 32, "f32", 128, 3000, 65)])
+                                                (64, 32, "f32", 128, 3000, 65), (128, 0, "bf16", 128, 128 * 80 + 3, 66)])
 def test_long_lists_with_mask_array(name, bq, bk, dtype, d, T, k):
     """More than 64 blocks kept per row under an explicit array: Alg. 2 and Eq. (2) against the oracle
     (the kernels that keep the row's lists in LDS)."""

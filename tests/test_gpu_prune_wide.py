@@ -57,7 +57,8 @@ def case(w, bk=0, mask="causal", window=0, check_trace=True):
     (32, 0, "f32", 64, 32 * 200 + 3, 100), (64, 0, "bf16", 128, 64 * 150 + 9, 80),
     (64, 0, "bf16", 64, 64 * 100, 128), (32, 0, "bf16", 128, 32 * 140, 512),     # k > N: every causal block
     (32, 64, "bf16", 128, 6000, 70), (64, 32, "bf16", 128, 6000, 130), (32, 128, "bf16", 128, 6000, 66),
-    (128, 32, "bf16", 64, 6000, 200), (64, 0, "f32", 128, 64 * 90 + 1, 72)])
+    (128, 32, "bf16", 64, 6000, 200), (64, 0, "f32", 128, 64 * 90 + 1, 72),
+    (128, 0, "bf16", 128, 128 * 100 + 77, 70), (128, 0, "f32", 64, 128 * 90 + 5, 80), (128, 0, "bf16", 64, 128 * 70, 128)])
 def test_wide_causal(bq, bk, dtype, d, T, k):
     w = wl.scaled(wl.config(2), (T,), topk=k, heads=2, kv_heads=1, block=bq, dtype=dtype, head_dim=d,
                   needles_per_kv_head=2)
@@ -70,6 +71,12 @@ def test_wide_mask_rules(mask, window):
     gpu = case(w, 0, mask, window)
     if mask == "full":
         assert (gpu["cnt"] == 90).all()
+
+
+@pytest.mark.parametrize("mask,window", [("sliding", 5000), ("full", 0)])
+def test_wide_mask_rules_128x128(mask, window):
+    w = wl.scaled(wl.config(2), (128 * 95 + 50,), topk=70, heads=2, kv_heads=1, block=128, needles_per_kv_head=2)
+    case(w, 0, mask, window)
 
 
 def test_wide_ragged_batch_and_variable_k():
@@ -148,9 +155,10 @@ def test_wide_limits():
     w = wl.scaled(wl.config(2), (4096,), topk=8, heads=2, kv_heads=1, needles_per_kv_head=1)
     Q, K, _, _ = wl.make_inputs(w, with_v=False)
     Qd, Kd = Q.to(DEV), K.to(DEV)
+    Qf, Kf = Qd.float(), Kd.float()
     for call in (lambda: binding.stream_prune(Qd, Kd, 2, 1, 64, 513),
-                 lambda: binding.stream_prune_multi(Qd, Kd, 2, 1, 128, [65, 8]),
-                 lambda: binding.stream_prune(Qd, Kd, 2, 1, 128, 65)):        # 128 x 128 rows: narrow kernel only
+                 lambda: binding.stream_prune_multi(Qf, Kf, 2, 1, 128, [65, 8]),     # fp32, d = 128, 128 x 128
+                 lambda: binding.stream_prune(Qf, Kf, 2, 1, 128, 65)):
         with pytest.raises(binding.StreamError) as e:
             call()
         assert e.value.code == 2

@@ -35,11 +35,11 @@ def draw(seed):
 
 def draw_wide(seed):
     """The same, with more than 64 blocks kept per row in at least one sequence (the kernels that
-    keep the lists in LDS; they do not take 128 x 128 blocks)."""
+    keep the lists in LDS)."""
     dtype, d, bq, bk, kv, g, lens, mask, window, ks = draw(500 + seed)
     rng = np.random.default_rng(9000 + seed)
-    if bq == 128 and bk == 128:
-        bq = int(rng.choice([32, 64]))
+    if bq == 128 and bk == 128 and dtype == "f32" and d == 128:
+        bq = int(rng.choice([32, 64]))                  # (refused: the tile fits no wavefront)
     if dtype == "f32" and d == 128 and {bq, bk} == {64, 128}:
         bq = 32                                         # the one shape the library refuses
     ks = tuple(int(x) for x in rng.integers(1, 220, size=len(lens)))
