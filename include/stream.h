@@ -254,9 +254,9 @@ stream_status stream_prune_variable(const void *Q, const void *K, const stream_s
  *   node_first    int32 [rows, topk_max], in/out
  *   node_last     int32 [rows, topk_max], in/out
  *   node_count    int32 [rows], in/out; values outside [0, topk_max] are clamped
- *   1 <= topk <= topk_max <= 64; rows >= 0 (0 is a no-op: the pointers are not looked at).
+ *   1 <= topk <= topk_max <= 512; rows >= 0 (0 is a no-op: the pointers are not looked at).
  * Errors: STREAM_EINVAL (null pointer, misaligned scores, bad sizes), STREAM_EUNSUPPORTED
- * (topk_max > 64, more than 2^36 rows), STREAM_EDEVICE.  No workspace, no synchronisation.
+ * (topk_max > 512, too many rows for one launch), STREAM_EDEVICE.  No workspace, no synchronisation.
  */
 stream_status stream_select_update(const float *branch_score, int *node_first, int *node_last,
                                    int *node_count, long long rows, int topk, int topk_max,
@@ -278,9 +278,9 @@ stream_status stream_select_update(const float *branch_score, int *node_first, i
  *   cnt_out        int32 [rows]
  *   weight_out     float [rows, kmax_a] or NULL: score_a of the kept entries, padded with -inf
  *                  (needs score_a)
- *   1 <= kmax_a, kmax_b <= 64; counts outside [0, kmax] are clamped; rows >= 0 (0 is a no-op:
+ *   1 <= kmax_a, kmax_b <= 512; counts outside [0, kmax] are clamped; rows >= 0 (0 is a no-op:
  *   the pointers are not looked at).
- * Errors: STREAM_EINVAL, STREAM_EUNSUPPORTED (kmax > 64), STREAM_EDEVICE.  No workspace.
+ * Errors: STREAM_EINVAL, STREAM_EUNSUPPORTED (kmax > 512), STREAM_EDEVICE.  No workspace.
  */
 stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *score_a, int kmax_a,
                                const int *idx_b, const int *cnt_b, int kmax_b, long long rows,

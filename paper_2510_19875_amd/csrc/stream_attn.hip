@@ -428,7 +428,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         if constexpr (ARB) {
                             // the word of this lane's query row that holds keys ktok0 + rb*32 .. +31
                             // (a word wholly past the end of the row is not read)
-                            const unsigned cwd = (tq < L) & ((unsigned)(ktok0 + rb * 32) < (unsigned)L) ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + rb)] : 0u;
+                            const unsigned cwd = ((tq < L) & ((unsigned)(ktok0 + rb * 32) < (unsigned)L)) ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + rb)] : 0u;
                             visible = visible & ((cwd >> ((i >> 2) * 8 + gh * 4 + (i & 3))) & 1u);
                         } else {
                             visible = visible & mask_token(p.mask, p.window, tq, tk);

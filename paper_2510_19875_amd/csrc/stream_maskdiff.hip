@@ -4,6 +4,7 @@
 // a lane holds one entry of each list and the search reads the other list across lanes.  Lists of
 // at most 32 entries take half a wavefront each.
 #include "stream_common.h"
+#include "stream_mfma.h"
 
 #include <math.h>
 
@@ -95,6 +96,56 @@ __global__ void __launch_bounds__(256) diff_kernel(const DiffParams p)
     }
 }
 
+// Lists of more than 64 entries (up to kMaxTopkWide): a wavefront per row, the row's b list in LDS,
+// the a list taken 64 entries at a time (lower-bound search in LDS, ballot compaction, outputs
+// appended in order).
+__global__ void __launch_bounds__(256) diff_wide_kernel(const DiffParams p)
+{
+    __shared__ int s_b[4][kMaxTopkWide];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long row = (long long)blockIdx.x * 4 + wave;
+    if (row >= p.rows) return;
+    int ca = p.ca[row], cb = p.cb[row];
+    ca = ca < 0 ? 0 : (ca > p.ka ? p.ka : ca);
+    cb = cb < 0 ? 0 : (cb > p.kb ? p.kb : cb);
+    int *b = s_b[wave];
+    for (int i = lane; i < cb; i += 64) b[i] = p.ib[row * p.kb + i];
+    wave_sync();
+    const long long o = row * p.ka;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int n = 0;
+    for (int c0 = 0; c0 < ca; c0 += 64) {
+        const int j = c0 + lane;
+        const bool live = j < ca;
+        const int a = live ? p.ia[o + j] : -1;
+        const float sc = live && p.sa ? p.sa[o + j] : -INFINITY;
+        int lo = 0, hi = cb;                               // first position of b whose entry is >= a
+#pragma unroll
+        for (int step = 0; step < 10; ++step) {            // 2^10 > 512 entries
+            const int mid = (lo + hi) >> 1;
+            const bool open = lo < hi;
+            const int bm = open ? b[mid] : 0;
+            lo = open && bm < a ? mid + 1 : lo;
+            hi = open && !(bm < a) ? mid : hi;
+        }
+        const bool in_b = lo < cb && b[lo < cb ? lo : 0] == a;
+        const bool keep = live && !in_b;
+        const unsigned long long kb = __ballot(keep);
+        const int pos = n + __popcll(kb & lt);
+        if (keep) {
+            p.io[o + pos] = a;
+            if (p.wo) p.wo[o + pos] = sc;
+        }
+        n += __popcll(kb);
+    }
+    for (int j = n + lane; j < p.ka; j += 64) {
+        p.io[o + j] = -1;
+        if (p.wo) p.wo[o + j] = -INFINITY;
+    }
+    if (lane == 0) p.co[row] = n;
+}
+
 }  // namespace stream
 
 using namespace stream;
@@ -104,9 +155,10 @@ extern "C" stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, co
                                           int *idx_out, int *cnt_out, float *weight_out, void *hip_stream)
 {
     if (rows < 0 || kmax_a < 1 || kmax_b < 1) return STREAM_EINVAL;
-    if (kmax_a > kMaxTopk || kmax_b > kMaxTopk) return STREAM_EUNSUPPORTED;
+    if (kmax_a > kMaxTopkWide || kmax_b > kMaxTopkWide) return STREAM_EUNSUPPORTED;
+    const bool wide = kmax_a > kMaxTopk || kmax_b > kMaxTopk;
     const int rpw = (kmax_a <= 32 && kmax_b <= 32) ? 2 : 1;
-    const long long per_wg = 4LL * kDiffRowsPerWave * rpw;
+    const long long per_wg = wide ? 4LL : 4LL * kDiffRowsPerWave * rpw;
     const long long grid = (rows + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
     if (rows == 0) return STREAM_OK;                 // empty tensors may have no address
@@ -118,6 +170,9 @@ extern "C" stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, co
     p.ia = idx_a; p.ca = cnt_a; p.sa = score_a; p.ib = idx_b; p.cb = cnt_b;
     p.io = idx_out; p.co = cnt_out; p.wo = weight_out;
     p.rows = rows; p.ka = kmax_a; p.kb = kmax_b;
-    hipLaunchKernelGGL(rpw == 2 ? diff_kernel<2> : diff_kernel<1>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
+    if (wide)
+        hipLaunchKernelGGL(diff_wide_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
+    else
+        hipLaunchKernelGGL(rpw == 2 ? diff_kernel<2> : diff_kernel<1>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
     return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
 }

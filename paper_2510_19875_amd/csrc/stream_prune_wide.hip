@@ -235,7 +235,7 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                         const bool ok = (sl * 64 + lane < 32 * MB) & (tq < L);
 #pragma unroll
                         for (int cb = 0; cb < NG; ++cb)
-                            rowword[sl][cb] = ok & (ktok0 + cb * 32 < L)         // (not a word wholly past the end of the row)
+                            rowword[sl][cb] = (ok & (ktok0 + cb * 32 < L))       // (not a word wholly past the end of the row)
                                                   ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + cb)] : 0u;
                     }
                 }

@@ -3,6 +3,7 @@
 // chip); this entry point runs it from a score tensor in memory so that the step can be used
 // and measured alone.  A wavefront ranks one row at a time, several rows in a row.
 #include "stream_select.h"
+#include "stream_mfma.h"
 
 #include <math.h>
 
@@ -164,6 +165,91 @@ __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
     }
 }
 
+// Rows of more than 64 nodes (up to kMaxTopkWide): a wavefront per row, the branch keys and the
+// node list in LDS, every step in chunks of 64 branch positions (position 2j + side = child
+// `side` of node j), as the wide refinement kernel does it.
+__global__ void __launch_bounds__(256) select_wide_kernel(const SelectParams p)
+{
+    __shared__ unsigned s_key[4][2 * kMaxTopkWide];
+    __shared__ int s_f[4][kMaxTopkWide], s_l[4][kMaxTopkWide];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long row = (long long)blockIdx.x * 4 + wave;
+    if (row >= p.rows) return;
+    const long long o = row * p.kmax;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int c = p.ncnt[row];
+    c = c < 0 ? 0 : (c > p.kmax ? p.kmax : c);
+    unsigned *key_of = s_key[wave];
+    int *nf = s_f[wave], *nl = s_l[wave];
+    for (int j = lane; j < c; j += 64) { nf[j] = p.nf[o + j]; nl[j] = p.nl[o + j]; }
+    wave_sync();
+    const int npos = 2 * c, k = p.k;
+    int n_valid = 0;
+    for (int c0 = 0; c0 < npos; c0 += 64) {
+        const int pp = c0 + lane;
+        unsigned key = 0;
+        if (pp < npos) {
+            const int f = nf[pp >> 1], l = nl[pp >> 1];
+            const int m = (f + l + 1) >> 1;                 // children [f, m-1] and [m, l]
+            const float sc = p.score[2 * o + pp];
+            if (f <= l && ((pp & 1) || m > f) && sc > -INFINITY) {
+                const unsigned b = sortable_bits(sc);
+                key = b ? b : 1u;
+            }
+            key_of[pp] = key;
+        }
+        n_valid += __popcll(__ballot(key != 0));
+    }
+    wave_sync();
+    unsigned thr = 1;            // n_valid <= k: every candidate is kept (keys are >= 1)
+    int need_eq = 0;
+    bool ties = false;           // keep key > thr plus the first need_eq of the equal ones
+    if (n_valid > k) {
+        thr = 0;
+        bool exact = false;
+        for (int bit = 31; bit >= 0 && !exact; --bit) {
+            const unsigned t = thr | (1u << bit);
+            int ge = 0;
+            for (int c0 = 0; c0 < npos; c0 += 64)
+                ge += __popcll(__ballot(c0 + lane < npos && key_of[c0 + lane] >= t));
+            if (ge >= k) {
+                thr = t;
+                exact = ge == k;
+            }
+        }
+        if (!exact) {
+            int n_gt = 0;
+            for (int c0 = 0; c0 < npos; c0 += 64)
+                n_gt += __popcll(__ballot(c0 + lane < npos && key_of[c0 + lane] > thr));
+            need_eq = k - n_gt;
+            ties = true;
+        }
+    }
+    int out_base = 0, eq_seen = 0;
+    for (int c0 = 0; c0 < npos; c0 += 64) {
+        const int pp = c0 + lane;
+        const unsigned key = pp < npos ? key_of[pp] : 0u;
+        bool keep = key >= thr;
+        if (ties) {
+            const bool eq = key == thr;
+            const unsigned long long be = __ballot(eq);
+            keep = key > thr || (eq && eq_seen + __popcll(be & lt) < need_eq);
+            eq_seen += __popcll(be);
+        }
+        const unsigned long long kb = __ballot(keep);
+        const int out = out_base + __popcll(kb & lt);
+        if (keep) {
+            const int f = nf[pp >> 1], l = nl[pp >> 1];
+            const int m = (f + l + 1) >> 1;
+            p.nf[o + out] = (pp & 1) ? m : f;
+            p.nl[o + out] = (pp & 1) ? l : m - 1;
+        }
+        out_base += __popcll(kb);
+    }
+    if (lane == 0) p.ncnt[row] = out_base;
+}
+
 }  // namespace stream
 
 using namespace stream;
@@ -173,8 +259,10 @@ extern "C" stream_status stream_select_update(const float *branch_score, int *no
                                               void *hip_stream)
 {
     if (rows < 0 || topk < 1 || topk > topk_max) return STREAM_EINVAL;
-    if (topk_max > kMaxTopk) return STREAM_EUNSUPPORTED;
-    const long long grid = (rows + 4 * kSelectRowsPerWave - 1) / (4 * kSelectRowsPerWave);
+    if (topk_max > kMaxTopkWide) return STREAM_EUNSUPPORTED;
+    const bool wide = topk_max > kMaxTopk;
+    const long long per_wg = wide ? 4 : 4 * kSelectRowsPerWave;
+    const long long grid = (rows + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return STREAM_EUNSUPPORTED;
     if (rows == 0) return STREAM_OK;                           // empty tensors may have no address
     if (!branch_score || !node_first || !node_last || !node_count) return STREAM_EINVAL;
@@ -182,6 +270,9 @@ extern "C" stream_status stream_select_update(const float *branch_score, int *no
     SelectParams p;
     p.score = branch_score; p.nf = node_first; p.nl = node_last; p.ncnt = node_count;
     p.rows = rows; p.k = topk; p.kmax = topk_max;
-    hipLaunchKernelGGL(topk_max <= 32 ? select_kernel<1> : select_kernel<2>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
+    if (wide)
+        hipLaunchKernelGGL(select_wide_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
+    else
+        hipLaunchKernelGGL(topk_max <= 32 ? select_kernel<1> : select_kernel<2>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
     return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
 }

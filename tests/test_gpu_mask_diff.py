@@ -33,7 +33,8 @@ def compare(ia, ca, sa, ib, cb):
         assert r["weight"] is None
 
 
-@pytest.mark.parametrize("ka,kb,N", [(1, 1, 3), (6, 3, 32), (8, 8, 10), (32, 16, 2048), (64, 64, 100), (5, 64, 70), (64, 1, 64)])
+@pytest.mark.parametrize("ka,kb,N", [(1, 1, 3), (6, 3, 32), (8, 8, 10), (32, 16, 2048), (64, 64, 100), (5, 64, 70), (64, 1, 64),
+                                      (65, 3, 300), (200, 512, 600), (512, 512, 513), (7, 100, 40), (300, 64, 5000)])
 def test_random_lists(ka, kb, N):
     rng = np.random.default_rng(ka * 1000 + kb)
     rows = 1001

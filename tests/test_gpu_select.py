@@ -48,7 +48,8 @@ def compare(sc, nf, nl, nc, k):
     np.testing.assert_array_equal(gl[~live], nl[~live])
 
 
-@pytest.mark.parametrize("kmax,k", [(1, 1), (2, 1), (5, 3), (8, 8), (16, 7), (32, 32), (33, 20), (64, 64), (64, 1)])
+@pytest.mark.parametrize("kmax,k", [(1, 1), (2, 1), (5, 3), (8, 8), (16, 7), (32, 32), (33, 20), (64, 64), (64, 1),
+                                    (65, 65), (65, 1), (200, 77), (512, 512), (512, 300), (100, 3)])
 @pytest.mark.parametrize("ties", [True, False])
 def test_matches_oracle(kmax, k, ties):
     rows = 1003                                     # not a multiple of the 4 rows per workgroup
