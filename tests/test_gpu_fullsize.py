@@ -120,6 +120,12 @@ def test_config3_sliding_window_sampled():
                mask="sliding", window=4096)
 
 
+def test_config3_long_lists_sampled():
+    """The headline tensors keeping 100 blocks per row: the kernels with the row's lists in LDS at scale."""
+    w = wl.config(3)
+    check_full(wl.scaled(w, w.seq_lens, topk=100, name=w.name + "_k100"), heads_sampled=[7, 25], n_rows=12, seed=15)
+
+
 def test_config4_one_million_tokens_sampled():
     """T = 1,048,576, block 128, k = 64: O(T) memory and the four-wavefront row path at scale."""
     check_full(wl.config(4), heads_sampled=[5, 26], n_rows=14, seed=12)
