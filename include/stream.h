@@ -83,7 +83,7 @@ typedef struct {
     int head_dim;    /* 64 or 128                                                      */
     int block;       /* b_q (and b_k unless block_k is set): 32, 64 or 128             */
     int dtype;       /* stream_dtype of Q, K, V, O                                     */
-    int batch;       /* sequences in the packed batch, >= 1                            */
+    int batch;       /* sequences in the packed batch, 1 .. 64                         */
     long long T;     /* total tokens                                                   */
     const int *cu_seqlens; /* HOST int32[batch+1]; may be NULL when batch == 1         */
     long long q_stride_h, q_stride_t; /* element strides; 0 = contiguous default       */

@@ -99,6 +99,7 @@ struct AttnParams {
     WgMap map;
     SeqTable seqs;
 };
+static_assert(sizeof(AttnParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 typedef float floatx8 __attribute__((ext_vector_type(8)));
 

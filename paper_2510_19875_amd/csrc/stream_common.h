@@ -9,7 +9,7 @@
 
 namespace stream {
 
-constexpr int kMaxBatch = 32;   // sequence descriptors travel as kernel arguments
+constexpr int kMaxBatch = 64;   // sequence descriptors travel as kernel arguments (2 KB of the 4 KB a launch may pass)
 constexpr int kMaxTopk = 64;    // one node per lane of a 64-wide wavefront (narrow kernels)
 constexpr int kMaxTopkWide = 512;   // stream_prune / stream_prune_variable / stream_sparse_attn: lists of up to 512 blocks
 constexpr int kXcds = 8;        // MI355X: 8 XCDs, workgroups are dealt to them round-robin

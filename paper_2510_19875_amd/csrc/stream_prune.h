@@ -40,6 +40,8 @@ struct PruneParams {
     int wide_ki;                 // wide kernel in a sweep: which value of the list this launch runs
 };
 
+static_assert(sizeof(PruneParams) <= 4096, "kernel arguments are limited to 4 KB");
+
 // max(1, ceil(log2(ceil(N / k)))): the levels after which every node is a single block
 __host__ __device__ __forceinline__ int levels_for(int N, int k)
 {

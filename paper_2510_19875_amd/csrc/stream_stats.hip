@@ -30,6 +30,7 @@ struct StatsParams {
     WgMap map;
     SeqTable seqs;
 };
+static_assert(sizeof(StatsParams) <= 4096, "kernel arguments are limited to 4 KB");
 
 // Query blocks (of bq tokens) that can see key block j (of bk tokens) of a sequence of L tokens:
 // imin .. imax, contiguous for all three mask rules (the counterpart of mask_rmin / mask_rmax);

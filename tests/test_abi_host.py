@@ -74,7 +74,7 @@ def test_block_geometry(lib):
     (dict(block=48), B.STREAM_EUNSUPPORTED),
     (dict(block_k=16), B.STREAM_EUNSUPPORTED),
     (dict(block_k=256), B.STREAM_EUNSUPPORTED),
-    (dict(batch=33), B.STREAM_EINVAL),
+    (dict(batch=65), B.STREAM_EINVAL),
 ])
 def test_bad_shapes_are_rejected_on_the_host(lib, kw, code):
     s = shape(**kw)

@@ -50,8 +50,20 @@ def draw_wide(seed):
 @pytest.mark.parametrize("seed", [("narrow", s) for s in range(28)] + [("wide", s) for s in range(10)],
                          ids=lambda x: f"{x[0]}{x[1]}")
 def test_random_configuration(seed):
-    dtype, d, bq, bk, kv, g, lens, mask, window, ks = draw(seed[1]) if seed[0] == "narrow" else draw_wide(seed[1])
-    seed = f"{seed[0]} {seed[1]}"
+    cfg = draw(seed[1]) if seed[0] == "narrow" else draw_wide(seed[1])
+    run_configuration(f"{seed[0]} {seed[1]}", *cfg)
+
+
+def test_batches_of_many_sequences():
+    """50 and 64 (the most a call takes) short sequences in one packed batch, k per sequence."""
+    for n, bq, bk, dtype in ((50, 64, 64, "bf16"), (64, 32, 128, "f32")):
+        rng = np.random.default_rng(n)
+        lens = tuple(int(x) for x in rng.integers(1, 500, size=n))
+        ks = tuple(int(x) for x in rng.integers(1, 9, size=n))
+        run_configuration(f"batch of {n}", dtype, 64, bq, bk, 2, 2, lens, "causal", 0, ks)
+
+
+def run_configuration(seed, dtype, d, bq, bk, kv, g, lens, mask, window, ks):
     H = kv * g
     cfg = 5 if len(lens) > 1 else 2
     kw = {"needles_per_kv_head": 1} if cfg == 2 else {"anchors_per_seq": 2}
