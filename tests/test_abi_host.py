@@ -232,3 +232,16 @@ def test_binding_refuses_cpu_tensors():
         B.stream_prune(Q, Q, 2, 2, 64, 1)
     with pytest.raises(ValueError):
         B.stream_receiver_stats(Q, Q, 2, 2, 64, 0.125)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with no C++ in it."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "t.c"
+    src.write_text('#include "stream.h"\nint main(void) { stream_shape s; (void)s; return (int)STREAM_OK; }\n')
+    subprocess.check_call([cc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
