@@ -14,26 +14,36 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def step(Q, K, V, w, bufs, mask="causal", window=0, block_k=0):
+def step(Q, K, V, w, bufs, mask="causal", window=0, block_k=0, mask_bits=None):
     cu = w.cu_seqlens if w.batch > 1 else None
     topk = list(w.topk) if w.batch > 1 else w.topk[0]
     p = binding.stream_prune(Q, K, w.heads, w.kv_heads, w.block, topk, cu_seqlens=cu, want_score=True,
                              workspace=bufs.get("wp"), out=bufs.get("op"), mask=mask, window=window,
-                             block_k=block_k)
+                             block_k=block_k, mask_bits=mask_bits)
     a = binding.stream_sparse_attn(Q, K, V, w.heads, w.kv_heads, w.block, p["idx"], p["cnt"],
                                    1.0 / math.sqrt(w.head_dim), cu_seqlens=cu, want_lse=True, want_mass=True,
                                    workspace=bufs.get("wa"), out=bufs.get("oa"), mask=mask, window=window,
-                                   block_k=block_k)
+                                   block_k=block_k, mask_bits=mask_bits)
     bufs["wp"], bufs["op"] = p["workspace"], {"idx": p["idx"], "cnt": p["cnt"], "score": p["score"]}
     bufs["wa"], bufs["oa"] = a["workspace"], {"O": a["O"], "lse": a["lse"], "mass": a["mass"]}
     return bufs
 
 
-@pytest.mark.parametrize("case", ["single", "ragged_sliding_rect"])
+@pytest.mark.parametrize("case", ["single", "ragged_sliding_rect", "long_lists", "mask_array"])
 def test_graph_replays_equal_eager(case):
     if case == "single":
         w = wl.scaled(wl.config(2), (64 * 70 + 9,), topk=8, heads=8, kv_heads=2, needles_per_kv_head=2)
         kw = {}
+    elif case == "long_lists":
+        w = wl.scaled(wl.config(2), (32 * 150 + 9,), topk=80, heads=4, kv_heads=2, block=32, needles_per_kv_head=2)
+        kw = {}
+    elif case == "mask_array":
+        T = 64 * 40 + 9
+        w = wl.scaled(wl.config(2), (T,), topk=8, heads=4, kv_heads=2, needles_per_kv_head=2)
+        t = np.arange(T)
+        C = (t[None, :] <= t[:, None]) & ((t[:, None] // 500 == t[None, :] // 500) | (t[None, :] < 70))
+        bits = np.packbits(np.pad(C, ((0, 0), (0, -T % 32))), axis=1, bitorder="little").view(np.int32)
+        kw = {"mask_bits": torch.from_numpy(bits.copy()).to(DEV)}
     else:
         w = wl.scaled(wl.config(5), (900, 64, 1700), topk=(3, 1, 5), heads=7, kv_heads=1, block=32, anchors_per_seq=3)
         kw = {"mask": "sliding", "window": 400, "block_k": 64}
