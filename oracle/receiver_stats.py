@@ -8,7 +8,8 @@ pattern of the attention-patterns figure) and ranks heads by the maximum vertica
 these block means.  Written out here from the definitions, in fp64, with the whole T x T
 probability matrix of one (head, sequence) in memory:
 
-  P        = softmax over visible keys of scale * Q K^T              (the dense pattern, mask C)
+  P        = softmax over visible keys of scale * Q K^T              (the dense pattern, mask C:
+             a rule, or an explicit T x T array; a query that sees no key has a zero row)
   M[i, j]  = sum of P over (queries of block i) x (keys of block j) / (n_q(i) * n_k(j)),
              n_q, n_k the real tokens of the two blocks (a hidden pair counts as probability 0);
              defined where block j is valid for block i (C^blk[i, j] = 1 in the notation of
@@ -48,22 +49,33 @@ def visible(mask: str, window: int, tq: np.ndarray, tk: np.ndarray) -> np.ndarra
     return ok
 
 
+def token_mask(L: int, mask: str = "causal", window: int = 0, C=None) -> np.ndarray:
+    """The mask C [L, L] of one sequence: a rule, or the explicit array given (mask = "array")."""
+    if C is not None:
+        C = np.asarray(C) != 0
+        assert C.shape == (L, L)
+        return C
+    t = np.arange(L)
+    return visible(mask, window, t[:, None], t[None, :])
+
+
 def dense_probabilities(Qh: np.ndarray, Kh: np.ndarray, scale: float, mask: str = "causal",
-                        window: int = 0) -> np.ndarray:
-    """P [L, L] of one head and one sequence, fp64."""
+                        window: int = 0, C=None) -> np.ndarray:
+    """P [L, L] of one head and one sequence, fp64.  A query that sees no key at all (possible
+    only with an explicit array) attends to nothing: its row of P is zero."""
     Qh = np.asarray(Qh, dtype=np.float64)
     Kh = np.asarray(Kh, dtype=np.float64)
     L = Qh.shape[0]
     S = scale * (Qh @ Kh.T)
-    t = np.arange(L)
-    C = visible(mask, window, t[:, None], t[None, :])
-    S = np.where(C, S, -np.inf)
-    S = S - S.max(axis=1, keepdims=True)
-    E = np.exp(S)
-    return E / E.sum(axis=1, keepdims=True)
+    Cm = token_mask(L, mask, window, C)
+    S = np.where(Cm, S, -np.inf)
+    top = S.max(axis=1, keepdims=True)
+    E = np.exp(S - np.where(np.isfinite(top), top, 0.0))
+    den = E.sum(axis=1, keepdims=True)
+    return np.where(den > 0, E / np.where(den > 0, den, 1.0), 0.0)
 
 
-def block_means(P: np.ndarray, block: int, mask: str = "causal", window: int = 0, block_k=None):
+def block_means(P: np.ndarray, block: int, mask: str = "causal", window: int = 0, block_k=None, C=None):
     """(M [T_p / b_q, T_p / b_k], Cblk of the same shape) of one L x L probability matrix:
     spans of b_q = block queries by b_k = block_k keys (default b_k = b_q); T_p is L rounded up
     to a multiple of lcm(b_q, b_k) as in the preamble of Alg. 2."""
@@ -77,8 +89,11 @@ def block_means(P: np.ndarray, block: int, mask: str = "causal", window: int = 0
     nk = np.clip(L - np.arange(Tp // bk) * bk, 0, bk).astype(np.float64)
     t = np.arange(Tp)
     real = t < L
-    C = visible(mask, window, t[:, None], t[None, :]) & real[:, None] & real[None, :]
-    Cblk = C.reshape(Tp // bq, bq, Tp // bk, bk).any(axis=(1, 3))
+    if C is not None:
+        Cp = np.pad(np.asarray(C) != 0, ((0, Tp - L), (0, Tp - L)))
+    else:
+        Cp = visible(mask, window, t[:, None], t[None, :]) & real[:, None] & real[None, :]
+    Cblk = Cp.reshape(Tp // bq, bq, Tp // bk, bk).any(axis=(1, 3))
     M = np.where(Cblk, sums / np.maximum(np.outer(nq, nk), 1.0), 0.0)
     return M, Cblk
 
@@ -120,7 +135,7 @@ def head_stats(col_mean: np.ndarray, col_kurt: np.ndarray, col_n: np.ndarray):
 
 
 def receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: float, cu_seqlens=None,
-                   mask: str = "causal", window: int = 0, want_block_mean: bool = True, block_k=None):
+                   mask: str = "causal", window: int = 0, want_block_mean: bool = True, block_k=None, C=None):
     """Q [heads, T, d], K [kv_heads, T, d].  Returns a dict with
     block_mean [heads, NBq, NBk] (global block ids, zero across sequences; None if not wanted),
     col_mean, col_kurt [heads, NBk], head [heads, batch, 2] = (max_kurt, vert_kurt); NBq / NBk
@@ -142,8 +157,9 @@ def receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: float, cu
     for h in range(heads):
         for s in range(len(tp)):
             a, e = cu[s], cu[s + 1]
-            P = dense_probabilities(Q[h, a:e], K[h // g, a:e], scale, mask, window)
-            M, Cblk = block_means(P, bq, mask, window, bk)
+            assert C is None or len(tp) == 1                 # an explicit array covers one sequence
+            P = dense_probabilities(Q[h, a:e], K[h // g, a:e], scale, mask, window, C)
+            M, Cblk = block_means(P, bq, mask, window, bk, C)
             mean, kurt, n = column_stats(M, Cblk)
             if bm is not None:
                 bm[h, q0[s]:q0[s + 1], k0[s]:k0[s + 1]] = M

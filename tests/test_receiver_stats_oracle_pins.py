@@ -223,3 +223,48 @@ def test_rectangular_spans_are_weighted_means_of_square_ones():
     assert out["block_mean"].shape == (1, 23 * 4 // 4 + 1, 6)        # T_p = 48: 24 x 6
     got = rs.block_mean_entry(Q, K, 2, 1.0, 9, 2, block_k=8)
     assert got == pytest.approx(out["block_mean"][0, 9, 2], rel=1e-12)
+
+
+def test_explicit_array_equals_python_loops_and_the_rules():
+    """The mask as an explicit array: Python loops over the visible pairs (with a query that sees
+    nothing and a key block nobody sees), rectangular spans included; an array that spells out a
+    rule gives what the rule gives."""
+    rng = np.random.default_rng(12)
+    L, d, scale = 13, 3, 0.6
+    Q = rng.standard_normal((L, d))
+    K = rng.standard_normal((L, d))
+    C = rng.random((L, L)) < 0.45
+    C[5, :] = False                      # a query without a key
+    C[:, 8:12] = False                   # keys nobody sees (a whole key block for b_k = 4)
+    for bq, bk in ((4, 4), (2, 4), (4, 2)):
+        ell = bq * bk // math.gcd(bq, bk)
+        Tp = -(-L // ell) * ell
+        Nq, Nk = Tp // bq, Tp // bk
+        want = [[0.0] * Nk for _ in range(Nq)]
+        valid = [[False] * Nk for _ in range(Nq)]
+        for t in range(L):
+            vis = [u for u in range(L) if C[t, u]]
+            s = {u: scale * sum(Q[t, c] * K[u, c] for c in range(d)) for u in vis}
+            z = sum(math.exp(v) for v in s.values())
+            for u in vis:
+                want[t // bq][u // bk] += math.exp(s[u]) / z
+                valid[t // bq][u // bk] = True
+        nq = [max(0, min(bq, L - i * bq)) for i in range(Nq)]
+        nk = [max(0, min(bk, L - j * bk)) for j in range(Nk)]
+        P = rs.dense_probabilities(Q, K, scale, C=C)
+        assert (P[5] == 0).all() and np.allclose(np.delete(P, 5, axis=0).sum(axis=1), 1.0)
+        M, Cb = rs.block_means(P, bq, block_k=bk, C=C)
+        for i in range(Nq):
+            for j in range(Nk):
+                assert bool(Cb[i, j]) == valid[i][j]
+                if valid[i][j]:
+                    assert M[i, j] == pytest.approx(want[i][j] / (nq[i] * nk[j]), rel=1e-12, abs=1e-300)
+                else:
+                    assert M[i, j] == 0.0
+    t = np.arange(L)
+    for mask, window in (("causal", 0), ("sliding", 5), ("full", 0)):
+        arr = rs.visible(mask, window, t[:, None], t[None, :])
+        a = rs.receiver_stats(Q[None], K[None], 1, 1, 4, scale, C=arr)
+        r = rs.receiver_stats(Q[None], K[None], 1, 1, 4, scale, mask=mask, window=window)
+        for key in ("block_mean", "col_mean", "col_kurt", "head"):
+            np.testing.assert_array_equal(a[key], r[key])
