@@ -312,7 +312,9 @@ stream_status stream_mask_diff(const int *idx_a, const int *cnt_a, const float *
  *   workspace   stream_receiver_stats_workspace_bytes(shape) bytes (packed Q and K, one float
  *               per padded token and head), 256-byte aligned
  * The moments are accumulated in fp64 from the fp32 block means.  Errors: as stream_prune;
- * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and b_k = 128, and for STREAM_MASK_ARRAY.
+ * STREAM_EUNSUPPORTED also for dtype F32 with head_dim 128 and b_k = 128.  With STREAM_MASK_ARRAY a
+ * query that sees no key has a zero row of probabilities, and a key block no query block sees is
+ * no column (col_mean = col_kurt = 0, left out of head_stats).
  */
 size_t stream_receiver_stats_workspace_bytes(const stream_shape *shape);
 

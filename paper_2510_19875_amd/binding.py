@@ -399,7 +399,7 @@ def stream_mask_diff(idx_a, cnt_a, score_a, idx_b, cnt_b, want_weight: bool = Tr
 
 def stream_receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: float, cu_seqlens=None,
                           want_block_mean: bool = False, workspace=None, out=None, mask="causal",
-                          window: int = 0, block_k: int = 0):
+                          window: int = 0, block_k: int = 0, mask_bits=None):
     """Block means of the dense attention pattern and their vertical kurtosis (Section 4.1).
 
     Returns dict(block_mean [H, NB, NBk] or None, col_mean [H, NBk], col_kurt [H, NBk],
@@ -410,7 +410,7 @@ def stream_receiver_stats(Q, K, heads: int, kv_heads: int, block: int, scale: fl
     H, T, d = Q.shape
     dev = Q.device
     shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
-                             mask=mask, window=window, block_k=block_k)
+                             mask=mask, window=window, block_k=block_k, mask_bits=mask_bits)
     NB = lib.stream_num_blocks(ctypes.byref(shape))
     NBk = lib.stream_num_key_blocks(ctypes.byref(shape))
     if NB < 0 or NBk < 0:

@@ -27,6 +27,12 @@ struct StatsParams {
     int H, g, NB, b;            // NB query blocks of b = b_q tokens
     int NBk, bk;                // NBk key blocks of b_k tokens (NB * b = NBk * bk padded tokens)
     int mask, window;
+    // STREAM_MASK_ARRAY (ARB kernels): the bit array C, the "some pair visible" summary per (query
+    // block, key block), and the number of query blocks every column is defined on
+    const unsigned *cbits, *cany;
+    long long cpitch;
+    int cw;
+    int *col_n;                 // [heads, NBk]
     WgMap map;
     SeqTable seqs;
 };
@@ -62,7 +68,10 @@ __device__ __forceinline__ int seq_of_key_block(const SeqTable &t, int gk, int b
 // ---------------------------------------------------------------------------------------------
 // rows: log-sum-exp of every query.  NS = 32-query groups per wavefront (1 for block 32).
 // ---------------------------------------------------------------------------------------------
-template <bool BF16, int D, int NS, int OCC>
+// ARB: the mask is an explicit bit array: every 64-key tile of the sequence is visited and every
+// element takes its bit (a lane owns a query: one mask word per 32 keys).  A query that sees no key
+// gets lse = -inf, and with it a zero row of probabilities in the column pass.
+template <bool BF16, int D, int NS, int OCC, bool ARB>
 __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -106,7 +115,7 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
     const int last_q = tq0 + QT - 1 < L - 1 ? tq0 + QT - 1 : L - 1;
     const int hi_tok = p.mask == STREAM_MASK_FULL ? L - 1 : last_q;
     const int lo_tok = p.mask == STREAM_MASK_SLIDING && tq0 - p.window + 1 > 0 ? tq0 - p.window + 1 : 0;
-    const int kt_lo = lo_tok / 64, kt_hi = hi_tok / 64;
+    const int kt_lo = ARB ? 0 : lo_tok / 64, kt_hi = ARB ? (L - 1) / 64 : hi_tok / 64;
 
     float m[NS], l[NS];
 #pragma unroll
@@ -143,13 +152,20 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
             }
         }
         const int tk0 = kt * 64;
-        const bool cut = (tq0 + QT > L) | (tk0 + 64 > L) |
+        const bool cut = ARB | (tq0 + QT > L) | (tk0 + 64 > L) |
                          ((p.mask != STREAM_MASK_FULL) & (tk0 + 63 > tq0)) |
                          ((p.mask == STREAM_MASK_SLIDING) & (tq0 + QT - 1 - tk0 >= p.window));
         // accumulator layout: lane holds query column (lane % 32); element i is key row
         // 8*(i/4) + 4*(lane/32) + (i%4)
 #pragma unroll
         for (int qs = 0; qs < NS; ++qs) {
+            unsigned cwd[2] = {0u, 0u};              // ARB: this lane's query against the tile's two key groups
+            if constexpr (ARB) {
+                const int tq = tq0 + qs * 32 + (lane & 31);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    if (tq < L && tk0 + kb * 32 < L) cwd[kb] = p.cbits[(long long)tq * p.cpitch + (tk0 >> 5) + kb];
+            }
             // m[] is kept on the raw products (c > 0, so the maximum commutes with the scaling):
             // per element one max, one fused multiply-add, one exp2, one add
             float x[2][16];
@@ -162,7 +178,9 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
                     if (cut) {
                         const int tq = tq0 + qs * 32 + (lane & 31);
                         const int tk = tk0 + kb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                        const bool vis = (tq < L) & (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                        bool vis = (tq < L) & (tk < L);
+                        if constexpr (ARB) vis = vis & ((cwd[kb] >> ((i >> 2) * 8 + (lane >> 5) * 4 + (i & 3))) & 1u);
+                        else vis = vis & mask_token(p.mask, p.window, tq, tk);
                         v = vis ? v : -INFINITY;
                     }
                     x[kb][i] = v;
@@ -197,7 +215,10 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
 // columns: block means and the moments of every column.  NG = 32-key groups of a key block,
 // NS = 32-query groups per streamed tile, TPB = streamed tiles per query block.
 // ---------------------------------------------------------------------------------------------
-template <bool BF16, int D, int NG, int NS, int TPB, int OCC>
+// ARB: the query blocks a column is defined on come from the block summary of the array (they need
+// not be contiguous: the tiles between the first and the last are all streamed, spans the array
+// hides from the column are left out of its moments), and every element takes its bit.
+template <bool BF16, int D, int NG, int NS, int TPB, int OCC, bool ARB>
 __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
@@ -237,8 +258,24 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
 
     int imin, imax;
     mask_irange(p.mask, p.window, j, BQ, BK, L, imin, imax);
-    if (imin > imax) {                              // a key block of padding only: no column
-        if (lane == 0) { p.col_mean[(long long)h * p.NBk + gbj] = 0.f; p.col_kurt[(long long)h * p.NBk + gbj] = 0.f; }
+    auto span_valid = [&](int i) -> bool {          // ARB: does query block i see key block j at all?
+        return (p.cany[(long long)(sd.blk0 + i) * p.cw + (gbj >> 5)] >> (gbj & 31)) & 1u;
+    };
+    if constexpr (ARB) {
+        imin = 0x7fffffff; imax = -1;
+        for (int i0 = 0; i0 < sd.nblk; i0 += 64) {
+            const unsigned long long b = __ballot(i0 + lane < sd.nblk && span_valid(i0 + lane));
+            if (b) {
+                if (imax < 0) imin = i0 + __builtin_ctzll(b);
+                imax = i0 + 63 - __builtin_clzll(b);
+            }
+        }
+    }
+    if (imin > imax) {                              // a key block of padding only (or hidden from everyone): no column
+        if (lane == 0) {
+            p.col_mean[(long long)h * p.NBk + gbj] = 0.f; p.col_kurt[(long long)h * p.NBk + gbj] = 0.f;
+            if constexpr (ARB) p.col_n[(long long)h * p.NBk + gbj] = 0;
+        }
         return;
     }
     const int nk = L - tk0 < BK ? L - tk0 : BK;     // real keys of the block
@@ -248,6 +285,7 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
     // diagonal block) so that the central moments formed from them at the end lose nothing that
     // matters: four short independent chains per span instead of a long dependent update
     double x0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0, s4 = 0.0;
+    int n_spans = 0;                                // spans the column is defined on
 
     uint4 qf[NS][FR];
     float lq[NS];
@@ -294,9 +332,19 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
             lcur[qs] = lq[qs];
             lq[qs] = lse_seq[tqn + qs * 32 + (lane & 31)];
         }
-        const bool cut = (tq0 + QT > L) | (tk0 + BK > L) |
+        const bool cut = ARB | (tq0 + QT > L) | (tk0 + BK > L) |
                          ((p.mask != STREAM_MASK_FULL) & (tk0 + BK - 1 > tq0)) |
                          ((p.mask == STREAM_MASK_SLIDING) & (tq0 + QT - 1 - tk0 >= p.window));
+        unsigned cwd[NG][NS];                        // ARB: this lane's queries against the block's key groups
+        if constexpr (ARB) {
+#pragma unroll
+            for (int qs = 0; qs < NS; ++qs) {
+                const int tq = tq0 + qs * 32 + (lane & 31);
+#pragma unroll
+                for (int kg = 0; kg < NG; ++kg)
+                    cwd[kg][qs] = (tq < L && tk0 + kg * 32 < L) ? p.cbits[(long long)tq * p.cpitch + (tk0 >> 5) + kg] : 0u;
+            }
+        }
 #pragma unroll
         for (int kg = 0; kg < NG; ++kg)
 #pragma unroll
@@ -307,7 +355,9 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
                     if (cut) {
                         const int tq = tq0 + qs * 32 + (lane & 31);
                         const int tk = tk0 + kg * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                        const bool vis = (tq < L) & (tk < L) & mask_token(p.mask, p.window, tq, tk);
+                        bool vis = (tq < L) & (tk < L);
+                        if constexpr (ARB) vis = vis & ((cwd[kg][qs] >> ((i >> 2) * 8 + (lane >> 5) * 4 + (i & 3))) & 1u);
+                        else vis = vis & mask_token(p.mask, p.window, tq, tk);
                         pr = vis ? pr : 0.f;
                     }
                     psum += pr;
@@ -318,19 +368,25 @@ __global__ void __launch_bounds__(256, OCC) stats_cols_kernel(const StatsParams 
             const int nq = L - i_blk * BQ < BQ ? L - i_blk * BQ : BQ;
             const float mval = wave_sum(psum) / (float)(nq * nk);
             psum = 0.f;
-            if (bm && lane == 0) bm[(long long)i_blk * p.NBk] = mval;
-            const double x = (double)mval;
-            if (t + 1 == TPB) x0 = x;
-            const double y = x - x0, y2 = y * y;
-            s1 += y;
-            s2 += y2;
-            s3 = fma(y2, y, s3);
-            s4 = fma(y2, y2, s4);
+            bool defined = true;
+            if constexpr (ARB) defined = span_valid(i_blk);
+            if (defined) {
+                if (bm && lane == 0) bm[(long long)i_blk * p.NBk] = mval;
+                const double x = (double)mval;
+                if (n_spans == 0) x0 = x;
+                const double y = x - x0, y2 = y * y;
+                s1 += y;
+                s2 += y2;
+                s3 = fma(y2, y, s3);
+                s4 = fma(y2, y2, s4);
+                ++n_spans;
+            }
         }
     }
     if (lane == 0) {
         const long long o = (long long)h * p.NBk + gbj;
-        const double cn = (double)(imax - imin + 1);
+        if constexpr (ARB) p.col_n[o] = n_spans;
+        const double cn = (double)n_spans;
         const double mu = s1 / cn;                                  // mean of the shifted values
         const double m2 = s2 / cn - mu * mu;
         const double m4 = s4 / cn - 4.0 * mu * (s3 / cn) + 6.0 * mu * mu * (s2 / cn) - 3.0 * mu * mu * mu * mu;
@@ -359,27 +415,35 @@ __global__ void __launch_bounds__(64) stats_heads_kernel(const StatsParams p)
     const long long kblk0 = (long long)sd.blk0 * p.b / p.bk;
     const float *cm = p.col_mean + (long long)h * p.NBk + kblk0;
     const float *ck = p.col_kurt + (long long)h * p.NBk + kblk0;
+    const bool arb = p.mask == STREAM_MASK_ARRAY;
+    const int *cnn = p.col_n + (long long)h * p.NBk + kblk0;     // (read with an array only)
     double s1 = 0.0;
     float mx = -INFINITY;
+    int n_cols = 0;                                 // columns some query block sees
     for (int j = lane; j < N; j += 64) {
-        s1 += (double)cm[j];
         int imin, imax;
         mask_irange(p.mask, p.window, j, p.b, p.bk, L, imin, imax);
-        if (imax - imin + 1 >= 4) mx = fmaxf(mx, ck[j]);
+        const int n = arb ? cnn[j] : imax - imin + 1;
+        if (n > 0) { s1 += (double)cm[j]; ++n_cols; }
+        if (n >= 4) mx = fmaxf(mx, ck[j]);
     }
-    const double mean = wave_sum_f64(s1) / (double)N;
+    for (int sft = 32; sft >= 1; sft >>= 1) n_cols += __shfl_xor(n_cols, sft);
+    if (!arb) n_cols = N;
+    const int Ncol = n_cols;
+    const double mean = wave_sum_f64(s1) / (double)(Ncol > 0 ? Ncol : 1);
     double c2 = 0.0, c4 = 0.0;
     for (int j = lane; j < N; j += 64) {
+        if (arb && cnn[j] <= 0) continue;
         const double c = (double)cm[j] - mean;
         c2 += c * c;
         c4 += c * c * c * c;
     }
-    const double m2 = wave_sum_f64(c2) / (double)N, m4 = wave_sum_f64(c4) / (double)N;
+    const double m2 = wave_sum_f64(c2) / (double)(Ncol > 0 ? Ncol : 1), m4 = wave_sum_f64(c4) / (double)(Ncol > 0 ? Ncol : 1);
     mx = wave_max(mx);
     if (lane == 0) {
         float *o = p.head_stats + ((long long)h * p.seqs.n + s) * 2;
         o[0] = mx == -INFINITY ? 0.f : mx;
-        o[1] = (N >= 4 && m2 > 0.0) ? (float)(m4 / (m2 * m2) - 3.0) : 0.f;
+        o[1] = (Ncol >= 4 && m2 > 0.0) ? (float)(m4 / (m2 * m2) - 3.0) : 0.f;
     }
 }
 
@@ -390,7 +454,7 @@ __global__ void __launch_bounds__(256) stats_zero_kernel(float *p, long long n)
 }
 
 struct StatsWorkspace {
-    size_t qp, kp, lse2, total;
+    size_t qp, kp, lse2, cany, call, coln, total;
 };
 
 static StatsWorkspace stats_layout(const Problem &pb)
@@ -400,38 +464,51 @@ static StatsWorkspace stats_layout(const Problem &pb)
     w.qp = off;   off += align_up((size_t)pb.H * pb.NB * pb.b * pb.d * pb.esize, 256);
     w.kp = off;   off += align_up((size_t)pb.Hkv * pb.NB * pb.b * pb.d * pb.esize, 256);
     w.lse2 = off; off += align_up((size_t)pb.H * pb.NB * pb.b * 4, 256);
+    // with a mask array: its block-level summaries and the number of spans of every column
+    const bool arb = pb.mask == STREAM_MASK_ARRAY;
+    const size_t bm = arb ? align_up((size_t)pb.NB * block_bitmap_words(pb) * 4, 256) : 0;
+    w.cany = off; off += bm;
+    w.call = off; off += bm;
+    w.coln = off; off += arb ? align_up((size_t)pb.H * ((size_t)pb.NB * pb.b / pb.bk) * 4, 256) : 0;
     w.total = off;
     return w;
 }
 
 typedef void (*stats_fn)(const StatsParams);
 
-template <bool BF16, int D, int NS, int TPB>
+template <bool BF16, int D, int NS, int TPB, bool ARB>
 static stats_fn pick_stats_cols_bk(int bk)
 {
     constexpr int OCC = (BF16 || D == 64) ? 2 : 1;   // fp32 with d = 128 holds 16 fragments per group
-    if (bk == 32) return stats_cols_kernel<BF16, D, 1, NS, TPB, OCC>;
-    if (bk == 64) return stats_cols_kernel<BF16, D, 2, NS, TPB, OCC>;
+    if (bk == 32) return stats_cols_kernel<BF16, D, 1, NS, TPB, OCC, ARB>;
+    if (bk == 64) return stats_cols_kernel<BF16, D, 2, NS, TPB, OCC, ARB>;
     if constexpr (BF16 || D == 64)
-        return stats_cols_kernel<BF16, D, 4, NS, TPB, 1>;
+        return stats_cols_kernel<BF16, D, 4, NS, TPB, 1, ARB>;
     else
         return nullptr;                              // 128 keys of fp32 x 128 do not fit a wavefront's registers
 }
 
-template <bool BF16, int D>
-static void pick_stats_kernels_t(int bq, int bk, stats_fn &rows, stats_fn &cols)
+template <bool BF16, int D, bool ARB>
+static void pick_stats_kernels_m(int bq, int bk, stats_fn &rows, stats_fn &cols)
 {
     constexpr int OCC = (BF16 || D == 64) ? 2 : 1;
     if (bq == 32) {
-        rows = stats_rows_kernel<BF16, D, 1, OCC>;
-        cols = pick_stats_cols_bk<BF16, D, 1, 1>(bk);
+        rows = stats_rows_kernel<BF16, D, 1, OCC, ARB>;
+        cols = pick_stats_cols_bk<BF16, D, 1, 1, ARB>(bk);
     } else if (bq == 64) {
-        rows = stats_rows_kernel<BF16, D, 2, OCC>;
-        cols = pick_stats_cols_bk<BF16, D, 2, 1>(bk);
+        rows = stats_rows_kernel<BF16, D, 2, OCC, ARB>;
+        cols = pick_stats_cols_bk<BF16, D, 2, 1, ARB>(bk);
     } else {
-        rows = stats_rows_kernel<BF16, D, 2, OCC>;
-        cols = pick_stats_cols_bk<BF16, D, 2, 2>(bk);
+        rows = stats_rows_kernel<BF16, D, 2, OCC, ARB>;
+        cols = pick_stats_cols_bk<BF16, D, 2, 2, ARB>(bk);
     }
+}
+
+template <bool BF16, int D>
+static void pick_stats_kernels_t(int bq, int bk, bool arb, stats_fn &rows, stats_fn &cols)
+{
+    if (arb) pick_stats_kernels_m<BF16, D, true>(bq, bk, rows, cols);
+    else pick_stats_kernels_m<BF16, D, false>(bq, bk, rows, cols);
 }
 
 }  // namespace stream
@@ -457,7 +534,6 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     Problem pb;
     stream_status rc = make_problem(shape, 0, nullptr, 0, &pb);
     if (rc != STREAM_OK) return rc;
-    if (pb.mask == STREAM_MASK_ARRAY) return STREAM_EUNSUPPORTED;   // the statistics take the three rules
     const long long q_sh = shape->q_stride_h ? shape->q_stride_h : pb.T * pb.d;
     const long long q_st = shape->q_stride_t ? shape->q_stride_t : pb.d;
     const long long k_sh = shape->k_stride_h ? shape->k_stride_h : pb.T * pb.d;
@@ -466,12 +542,13 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
     if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
     stats_fn rows = nullptr, cols = nullptr;
+    const bool arb = pb.mask == STREAM_MASK_ARRAY;
     if (pb.dtype == STREAM_BF16) {
-        if (pb.d == 128) pick_stats_kernels_t<true, 128>(pb.b, pb.bk, rows, cols);
-        else pick_stats_kernels_t<true, 64>(pb.b, pb.bk, rows, cols);
+        if (pb.d == 128) pick_stats_kernels_t<true, 128>(pb.b, pb.bk, arb, rows, cols);
+        else pick_stats_kernels_t<true, 64>(pb.b, pb.bk, arb, rows, cols);
     } else {
-        if (pb.d == 128) pick_stats_kernels_t<false, 128>(pb.b, pb.bk, rows, cols);
-        else pick_stats_kernels_t<false, 64>(pb.b, pb.bk, rows, cols);
+        if (pb.d == 128) pick_stats_kernels_t<false, 128>(pb.b, pb.bk, arb, rows, cols);
+        else pick_stats_kernels_t<false, 64>(pb.b, pb.bk, arb, rows, cols);
     }
     if (!rows || !cols) return STREAM_EUNSUPPORTED;
     const StatsWorkspace w = stats_layout(pb);
@@ -497,7 +574,15 @@ stream_status stream_receiver_stats(const void *Q, const void *K, const stream_s
     p.H = pb.H; p.g = pb.g; p.NB = pb.NB; p.b = pb.b;
     p.bk = pb.bk; p.NBk = (int)((long long)pb.NB * pb.b / pb.bk);
     p.mask = pb.mask; p.window = pb.window;
+    p.cbits = pb.cbits; p.cpitch = pb.cpitch;
+    p.cany = (const unsigned *)(ws + w.cany);
+    p.cw = arb ? block_bitmap_words(pb) : 0;
+    p.col_n = (int *)(ws + w.coln);
     p.seqs = pb.seqs;
+    if (arb) {
+        rc = launch_block_bitmaps(pb, (unsigned *)(ws + w.cany), (unsigned *)(ws + w.call), st);
+        if (rc != STREAM_OK) return rc;
+    }
 
     if (block_mean) {
         // entries no kernel writes (blocks the mask hides, pairs of different sequences) are zero

@@ -135,8 +135,10 @@ def test_bad_arguments_of_the_mask_array(lib):
     cu = (ctypes.c_int * 3)(0, 600, 1000)
     two = shape(batch=2, cu_seqlens=ctypes.cast(cu, ctypes.POINTER(ctypes.c_int)), **arr)
     assert prune(two) == B.STREAM_EUNSUPPORTED                                 # single sequence only
-    rc = lib.stream_receiver_stats(fake, fake, ctypes.byref(shape(**arr)), 0.125, None, fake, fake, fake,
-                                   ws, 1 << 40, None)
+    # the statistics take the array too (one sequence): more workspace, the same refusal of a batch
+    assert lib.stream_receiver_stats_workspace_bytes(ctypes.byref(shape(**arr))) > \
+        lib.stream_receiver_stats_workspace_bytes(ctypes.byref(shape()))
+    rc = lib.stream_receiver_stats(fake, fake, ctypes.byref(two), 0.125, None, fake, fake, fake, ws, 1 << 40, None)
     assert rc == B.STREAM_EUNSUPPORTED
 
 

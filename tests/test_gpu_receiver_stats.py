@@ -21,10 +21,10 @@ DEV = "cuda:0"
 RTOL_M = 2e-4
 
 
-def run(Q, K, H, Hkv, b, scale, cu=None, mask="causal", window=0, want_block_mean=True, block_k=0):
+def run(Q, K, H, Hkv, b, scale, cu=None, mask="causal", window=0, want_block_mean=True, block_k=0, mask_bits=None):
     r = binding.stream_receiver_stats(Q.to(DEV), K.to(DEV), H, Hkv, b, scale, cu_seqlens=cu,
                                       want_block_mean=want_block_mean, mask=mask, window=window,
-                                      block_k=block_k)
+                                      block_k=block_k, mask_bits=mask_bits)
     torch.cuda.synchronize()
     return {k: (v.cpu().numpy() if isinstance(v, torch.Tensor) and k != "workspace" else v)
             for k, v in r.items()}
@@ -40,15 +40,19 @@ def seq_blocks(cu, T, b, bk):
     return cu, q0, k0
 
 
-def check(w, mask="causal", window=0, scale=None, bk=None):
+def check(w, mask="causal", window=0, scale=None, bk=None, C=None):
     Q, K, _, _ = wl.make_inputs(w, with_v=False)
     H, Hkv, b, d = w.heads, w.kv_heads, w.block, w.head_dim
     scale = 1.0 / math.sqrt(d) if scale is None else scale
     bk = bk or b
     cu = list(w.cu_seqlens) if len(w.seq_lens) > 1 else None
-    got = run(Q, K, H, Hkv, b, scale, cu, mask, window, block_k=bk)
+    bits = None
+    if C is not None:
+        from tests.test_gpu_mask_array import pack_bits
+        bits = pack_bits(C)
+    got = run(Q, K, H, Hkv, b, scale, cu, mask, window, block_k=bk, mask_bits=bits)
     Qn, Kn = Q.to(torch.float64).numpy(), K.to(torch.float64).numpy()
-    want = rs.receiver_stats(Qn, Kn, H, Hkv, b, scale, cu_seqlens=cu, mask=mask, window=window, block_k=bk)
+    want = rs.receiver_stats(Qn, Kn, H, Hkv, b, scale, cu_seqlens=cu, mask=mask, window=window, block_k=bk, C=C)
     assert got["block_mean"].shape == want["block_mean"].shape
 
     bm = got["block_mean"].astype(np.float64)
@@ -63,7 +67,7 @@ def check(w, mask="causal", window=0, scale=None, bk=None):
         for s in range(len(q0) - 1):
             qlo, qhi, lo, hi = q0[s], q0[s + 1], k0[s], k0[s + 1]
             L = cu_l[s + 1] - cu_l[s]
-            _, Cblk = rs.block_means(np.zeros((L, L)), b, mask, window, bk)
+            _, Cblk = rs.block_means(np.zeros((L, L)), b, mask, window, bk, C)
             mean, kurt, n = rs.column_stats(bm[h, qlo:qhi, lo:hi], Cblk)
             np.testing.assert_allclose(got["col_mean"][h, lo:hi], mean, rtol=1e-6, atol=1e-37)
             np.testing.assert_allclose(got["col_kurt"][h, lo:hi], kurt, rtol=1e-4, atol=1e-4)
@@ -212,3 +216,21 @@ def test_config3_full_size_sampled():
         for (i, j) in pairs:
             want = rs.block_mean_entry(Qh, Kh, b, scale, i, j)
             assert Mh[i, j] == pytest.approx(want, rel=RTOL_M, abs=1e-30), (h, i, j)
+
+
+@pytest.mark.parametrize("name", ["causal", "sliding", "random", "documents", "blank_rows"])
+@pytest.mark.parametrize("b,bk,dtype_cfg,T", [(64, 64, 2, 64 * 14 + 9), (32, 128, 2, 900), (128, 32, 1, 1000)])
+def test_with_mask_array(name, b, bk, dtype_cfg, T):
+    """The statistics of the dense pattern under an explicit array C (queries that see nothing, key
+    blocks nobody sees, columns whose query blocks are not contiguous)."""
+    from tests.test_gpu_mask_array import masks
+    w = wl.scaled(wl.config(dtype_cfg), (T,), heads=2, kv_heads=1, block=b, needles_per_kv_head=2)
+    C = masks(T, 21)[name].copy()
+    if name == "random":
+        lo = -(-300 // bk) * bk
+        C[:, lo:lo + bk * 2] = False                           # two key blocks hidden from everyone
+    got, want = check(w, bk=bk, C=C)
+    if name == "causal":
+        rule = run(*wl.make_inputs(w, with_v=False)[:2], 2, 1, b, 1.0 / math.sqrt(w.head_dim), block_k=bk)
+        np.testing.assert_allclose(got["col_mean"], rule["col_mean"], rtol=1e-5)
+        np.testing.assert_allclose(got["head"], rule["head"], rtol=1e-3, atol=1e-4)
