@@ -115,7 +115,27 @@ __global__ void __launch_bounds__(256, OCC) stats_rows_kernel(const StatsParams 
     const int last_q = tq0 + QT - 1 < L - 1 ? tq0 + QT - 1 : L - 1;
     const int hi_tok = p.mask == STREAM_MASK_FULL ? L - 1 : last_q;
     const int lo_tok = p.mask == STREAM_MASK_SLIDING && tq0 - p.window + 1 > 0 ? tq0 - p.window + 1 : 0;
-    const int kt_lo = ARB ? 0 : lo_tok / 64, kt_hi = ARB ? (L - 1) / 64 : hi_tok / 64;
+    int kt_lo = lo_tok / 64, kt_hi = hi_tok / 64;
+    if constexpr (ARB) {
+        // from the first to the last key block some query of this block sees (the block summary of
+        // the array): a causal or a document mask then costs its triangle, not the square
+        const unsigned *anyrow = p.cany + (long long)gb * p.cw;
+        const int nkb = (int)(((long long)sd.nblk * p.b) / p.bk);      // key blocks of the sequence
+        int r_first = 0x7fffffff, r_last = -1;
+        for (int w0 = 0; w0 * 32 < nkb; w0 += 64) {
+            const int wi = w0 + lane;
+            const unsigned x = wi * 32 < nkb ? anyrow[wi] : 0u;
+            const unsigned long long nz = __ballot(x != 0u);
+            if (nz) {
+                const int wf = w0 + __builtin_ctzll(nz), wl = w0 + 63 - __builtin_clzll(nz);
+                if (r_last < 0) r_first = wf * 32 + __builtin_ctz(__builtin_amdgcn_readlane(x, wf - w0));
+                r_last = wl * 32 + 31 - __builtin_clz(__builtin_amdgcn_readlane(x, wl - w0));
+            }
+        }
+        kt_lo = r_last < 0 ? 1 : (int)((long long)r_first * p.bk / 64);
+        kt_hi = r_last < 0 ? 0 : (int)((((long long)r_last + 1) * p.bk - 1) / 64);
+        if (kt_hi > (L - 1) / 64) kt_hi = (L - 1) / 64;
+    }
 
     float m[NS], l[NS];
 #pragma unroll
