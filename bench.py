@@ -203,6 +203,9 @@ def main():
                    "step": "stream_prune + stream_sparse_attn (O, lse, mass)"},
         "prune_ms": float(np.mean(prune_ms)),
         "attn_ms": float(np.mean(attn_ms)),
+        # one entry per timed step; step i runs the independently seeded layer i % resident_layers
+        "per_layer_prune_ms": [round(float(x), 4) for x in prune_ms],
+        "per_layer_attn_ms": [round(float(x), 4) for x in attn_ms],
         "prune_only_value": tok_heads / (float(np.mean(prune_ms)) * 1e-3),
         "attn_tflops": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12,
         "attn_frac_of_mfma_peak": attn_flop / (float(np.mean(attn_ms)) * 1e-3) / 1e12 / mfma_peak(w.dtype),
@@ -245,7 +248,15 @@ def main():
     if args.dense_reference and w.batch == 1:
         result["dense_reference"] = dense_reference(w, layers[0])
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale)
+        # the step's own outputs for layer 0, taken again after the timed region (with the per-level
+        # trace a differing row is certified from), for the row-by-row comparison with the oracle
+        Q0, K0, V0 = layers[0]
+        gp = binding.stream_prune(Q0, K0, H, Hkv, b, topk, cu_seqlens=cu, want_score=True, want_trace=True,
+                                  workspace=ws_p)
+        ga = binding.stream_sparse_attn(Q0, K0, V0, H, Hkv, b, gp["idx"], gp["cnt"], scale, cu_seqlens=cu,
+                                        want_lse=True, want_mass=True, workspace=ws_a)
+        torch.cuda.synchronize()
+        result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale, gp, ga)
     print(json.dumps(result))
 
 
@@ -625,9 +636,11 @@ def select_standalone(kmax, rows=1 << 21, launches=12):
             "bytes_per_launch": rows * bytes_per_row, "avg_launch_ms": ms, "launches": launches}
 
 
-def cpu_baseline(w, layer, n_rows, scale):
+def cpu_baseline(w, layer, n_rows, scale, gpu_prune=None, gpu_attn=None):
     """The oracle as it stands (fp64, OpenMP over rows), timed on a seeded row sample of the same
-    workload: prune + attention of those rows.  A reported baseline, not a target."""
+    workload: prune + attention of those rows.  A reported baseline, not a target.  The rows it
+    computes are then compared with the library's outputs for the same layer (outside the timing):
+    lists equal, or certified level by level within the 1e-3 tie rule; O and lse of the equal rows."""
     import numpy as np
 
     from oracle import stream_oracle as so
@@ -645,21 +658,52 @@ def cpu_baseline(w, layer, n_rows, scale):
     bseq, bloc = so.block_table(cu, w.block)
     t0 = time.perf_counter()
     tokens = 0
+    done = []
     for h in heads:
         for s in range(w.batch):
-            ql = [int(bloc[gb]) for (hh, gb) in rows if hh == h and bseq[gb] == s]
+            gbs = [gb for (hh, gb) in rows if hh == h and bseq[gb] == s]
+            ql = [int(bloc[gb]) for gb in gbs]
             if not ql:
                 continue
             a, e = cu[s], cu[s + 1]
             p = so.prune_head(Qh[h][a:e], Kh[h // g][a:e], w.block, w.topk[s], qblocks=ql)
-            so.sparse_attn(Qh[h][None, a:e], Kh[h // g][None, a:e], Vh[h // g][None, a:e], 1, 1, w.block,
-                           p["idx"], p["cnt"], scale, rows=[(0, qb) for qb in ql])
+            at = so.sparse_attn(Qh[h][None, a:e], Kh[h // g][None, a:e], Vh[h // g][None, a:e], 1, 1, w.block,
+                                p["idx"], p["cnt"], scale, rows=[(0, qb) for qb in ql])
             tokens += sum(min(w.block, (e - a) - qb * w.block) for qb in ql)
+            done.append((h, s, gbs, ql, p, at))
     dt = time.perf_counter() - t0
-    return {"value": tokens / dt, "unit": "query-tokens*heads/s", "cores": so.threads(),
-            "kind": "oracle", "seconds": dt,
-            "sample": f"{len(rows)} seeded (head, query block) rows of {w.name}: Alg. 2 as printed "
-                      f"(n_it levels, no score reuse) + Eq. (2) on the retained blocks, fp64"}
+    res = {"value": tokens / dt, "unit": "query-tokens*heads/s", "cores": so.threads(),
+           "kind": "oracle", "seconds": dt,
+           "sample": f"{len(rows)} seeded (head, query block) rows of {w.name}: Alg. 2 as printed "
+                     f"(n_it levels, no score reuse) + Eq. (2) on the retained blocks, fp64"}
+    if gpu_prune is not None:
+        from tests import parity
+
+        gi, gc = gpu_prune["idx"].cpu().numpy(), gpu_prune["cnt"].cpu().numpy()
+        gt = gpu_prune["trace"].cpu().numpy()
+        equal = ties = failed = 0
+        worst_o = worst_l = 0.0
+        for (h, s, gbs, ql, p, at) in done:
+            a, e = cu[s], cu[s + 1]
+            k = w.topk[s]
+            O_g = gpu_attn["O"][h, a:e].float().cpu().numpy()
+            l_g = gpu_attn["lse"][h, a:e].cpu().numpy()
+            for i, (gb, q) in enumerate(zip(gbs, ql)):
+                if int(gc[h, gb]) == int(p["cnt"][i]) and np.array_equal(gi[h, gb, :k], p["idx"][i]):
+                    equal += 1
+                    t0_, t1_ = q * w.block, min((q + 1) * w.block, e - a)
+                    worst_o = max(worst_o, float(np.abs(O_g[t0_:t1_] - at["O"][0, t0_:t1_]).max()))
+                    worst_l = max(worst_l, float(np.abs(l_g[t0_:t1_] - at["lse"][0, t0_:t1_]).max()))
+                    continue
+                n_eff = max(1, math.ceil(math.log2(math.ceil(-(-(e - a) // w.block) / k))))
+                ok, _ = parity.certify_row(Qh[h][a:e], Kh[h // g][a:e], w.block, k, q, gt[:n_eff, h, gb, :k])
+                ties += 1 if ok else 0
+                failed += 0 if ok else 1
+        tol = 2e-2 if w.dtype == "bf16" else 1e-4
+        res.update({"parity_rows": len(rows), "parity_equal": equal, "parity_tie_rows": ties,
+                    "parity_failed_rows": failed, "parity_max_abs_dO": worst_o, "parity_max_abs_dlse": worst_l,
+                    "parity_ok": bool(failed == 0 and worst_o <= tol and worst_l <= 1e-3)})
+    return res
 
 
 if __name__ == "__main__":

@@ -270,27 +270,59 @@ def variable_k(valid: int, keep_num: int, keep_den: int, topk_min: int, topk_max
     return min(topk_max, max(topk_min, k))
 
 
-def valid_blocks(q: int, N: int, block: int, mask: str = "causal", window: int = 0) -> int:
-    """Number of key blocks the mask rule leaves to query block q (they are contiguous)."""
+def valid_blocks(q: int, N: int, block: int, mask: str = "causal", window: int = 0,
+                 block_k: Optional[int] = None, L: Optional[int] = None, C=None) -> int:
+    """Number of key blocks the mask C leaves to query block q: blocks with at least one real key
+    that one real query of the block sees (C^blk of the preamble of Alg. 2).
+
+    Square blocks under a rule: N = blocks of the sequence.  With b_q != b_k (block_k) pass the
+    sequence length L; with an explicit [T, T] array C the count is read off the array (L = T)."""
+    bk = int(block_k or block)
+    if C is not None:
+        C = np.asarray(C) != 0
+        T = C.shape[0]
+        Tp = padded_len(T, block, bk)
+        rows = C[q * block:min((q + 1) * block, T)]              # the block's real queries
+        if rows.shape[0] == 0:
+            return 0
+        cols = np.zeros((Tp,), dtype=bool)
+        cols[:T] = rows.any(axis=0)                                # keys some query of the block sees
+        return int(cols.reshape(Tp // bk, bk).any(axis=1).sum())
+    if bk == block and L is None:
+        if mask == "full":
+            return N
+        rmin = 0
+        if mask == "sliding":
+            lo = q * block - window + 1
+            rmin = lo // block if lo > 0 else 0
+        return q - rmin + 1
+    if L is None:
+        raise ValueError("b_q != b_k needs the sequence length L")
+    t_first = q * block
+    if t_first >= L:
+        return 0                                                   # a query block of padding only
+    t_last = min((q + 1) * block, L) - 1
     if mask == "full":
-        return N
-    rmin = 0
-    if mask == "sliding":
-        lo = q * block - window + 1
-        rmin = lo // block if lo > 0 else 0
-    return q - rmin + 1
+        return (L - 1) // bk + 1
+    u_lo = max(0, t_first - window + 1) if mask == "sliding" else 0   # lowest key any query of the block sees
+    return t_last // bk - u_lo // bk + 1
 
 
 def prune_variable(Q, K, heads: int, kv_heads: int, block: int, keep_num: int, keep_den: int,
                    topk_min: int, topk_max: int, cu_seqlens=None,
-                   rows: Optional[Sequence[Sequence[int]]] = None, mask: str = "causal", window: int = 0):
-    """Algorithm 2 run row by row with k(row) = variable_k(valid(row), ...).  Output arrays as
-    prune(): [heads, NB, topk_max] (full) or [len(rows), topk_max]; also "k" per row."""
+                   rows: Optional[Sequence[Sequence[int]]] = None, mask: str = "causal", window: int = 0,
+                   block_k: Optional[int] = None, C=None):
+    """Algorithm 2 run row by row with k(row) = variable_k(valid(row), ...), valid(row) counted
+    under the mask the row is pruned with (rule, rectangular blocks, or an explicit [T, T] array C
+    for a single sequence).  Output arrays as prune(): [heads, NB, topk_max] (full) or
+    [len(rows), topk_max]; also "k" per row."""
     Q, K = _f32(Q), _f32(K)
     H, T, d = Q.shape
     g = heads // kv_heads
     cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
-    bseq, bloc = block_table(cu, block)
+    if C is not None and len(cu) != 2:
+        raise ValueError("an explicit mask is taken for a single sequence only")
+    bseq, bloc = block_table(cu, block, block_k)
     NB = len(bseq)
     full = rows is None
     rows_arr = (np.asarray([(h, gb) for h in range(H) for gb in range(NB)], dtype=np.int64) if full
@@ -300,12 +332,20 @@ def prune_variable(Q, K, heads: int, kv_heads: int, block: int, keep_num: int, k
     cnt = np.zeros((R,), dtype=np.int32)
     score = np.full((R, topk_max), -np.inf, dtype=np.float64)
     ks = np.zeros((R,), dtype=np.int32)
+    valid_of = {}
     for i, (h, gb) in enumerate(rows_arr):
         s, q = int(bseq[gb]), int(bloc[gb])
         L = cu[s + 1] - cu[s]
-        N = -(-L // block)
-        k = variable_k(valid_blocks(q, N, block, mask, window), keep_num, keep_den, topk_min, topk_max)
-        out = prune_head(Q[h, cu[s]:cu[s + 1]], K[h // g, cu[s]:cu[s + 1]], block, k, [q], mask=mask, window=window)
+        if (s, q) not in valid_of:
+            if C is not None:
+                valid_of[(s, q)] = valid_blocks(q, 0, block, block_k=block_k, C=C)
+            elif block_k is not None and block_k != block:
+                valid_of[(s, q)] = valid_blocks(q, 0, block, mask, window, block_k=block_k, L=L)
+            else:
+                valid_of[(s, q)] = valid_blocks(q, -(-L // block), block, mask, window)
+        k = variable_k(valid_of[(s, q)], keep_num, keep_den, topk_min, topk_max)
+        out = prune_head(Q[h, cu[s]:cu[s + 1]], K[h // g, cu[s]:cu[s + 1]], block, k, [q], mask=mask,
+                         window=window, block_k=block_k, C=C)
         idx[i, :k] = out["idx"][0]
         cnt[i] = out["cnt"][0]
         score[i, :k] = out["score"][0]

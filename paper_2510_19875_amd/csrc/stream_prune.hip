@@ -73,13 +73,17 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     uint4 qf[MB][FR];
     {
         const int mrow = lane & 31, gh = lane >> 5;
+        // the resource starts at this wavefront's first query row (64-bit arithmetic) and spans
+        // its real rows only, so per-lane offsets stay below 128 token strides whatever the
+        // length of the sequence and the layout of Q
+        const int qrow0 = q * BQ + qh * 32 * MB;
+        const int qrows = L - qrow0 < 32 * MB ? L - qrow0 : 32 * MB;
         const __amdgpu_buffer_rsrc_t qrs = make_tile_rsrc(
-            p.Q + (long long)h * p.q_sh_b + sd.tok0 * p.q_st_b,
-            (unsigned)((long long)(L - 1) * p.q_st_b + D * ES));
+            p.Q + (long long)h * p.q_sh_b + (sd.tok0 + qrow0) * p.q_st_b,
+            qrows > 0 ? (unsigned)((long long)(qrows - 1) * p.q_st_b + D * ES) : 0u);
 #pragma unroll
         for (int rb = 0; rb < MB; ++rb) {
-            const unsigned tok = (unsigned)(q * BQ + qh * 32 * MB + rb * 32 + mrow);
-            const unsigned voff = tok * (unsigned)p.q_st_b + gh * 16;
+            const unsigned voff = (unsigned)(rb * 32 + mrow) * (unsigned)p.q_st_b + gh * 16;
 #pragma unroll
             for (int fr = 0; fr < FR; ++fr) {
                 const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * 32, 0, 0);
@@ -475,6 +479,8 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     // 16-byte vector loads: base pointers and strides must keep rows 16-byte aligned
     if (((uintptr_t)Q | (uintptr_t)K) & 15) return STREAM_EINVAL;
     if ((q_sh * pb.esize | q_st * pb.esize | k_sh * pb.esize | k_st * pb.esize) & 15) return STREAM_EINVAL;
+    // the kernels address a query block's rows with 32-bit offsets from the block's first row
+    if (q_st * pb.esize * 128 >= (1LL << 31)) return STREAM_EUNSUPPORTED;
     const bool wide = pb.kmax > kMaxTopk;       // more than one node per lane: the LDS-list kernel
     if (wide && !level_wide_supported(pb)) return STREAM_EUNSUPPORTED;
     int wpr = 1;

@@ -89,13 +89,15 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
     uint4 qf[MB][FR];
     {
         const int mrow = lane & 31, gh = lane >> 5;
+        // (resource from the row's first query on, 64-bit base: see the narrow kernel)
+        const int qrow0 = q * BQ;
+        const int qrows = L - qrow0 < 32 * MB ? L - qrow0 : 32 * MB;
         const __amdgpu_buffer_rsrc_t qrs = make_tile_rsrc(
-            p.Q + (long long)h * p.q_sh_b + sd.tok0 * p.q_st_b,
-            (unsigned)((long long)(L - 1) * p.q_st_b + D * ES));
+            p.Q + (long long)h * p.q_sh_b + (sd.tok0 + qrow0) * p.q_st_b,
+            qrows > 0 ? (unsigned)((long long)(qrows - 1) * p.q_st_b + D * ES) : 0u);
 #pragma unroll
         for (int rb = 0; rb < MB; ++rb) {
-            const unsigned tok = (unsigned)(q * BQ + rb * 32 + mrow);
-            const unsigned voff = tok * (unsigned)p.q_st_b + gh * 16;
+            const unsigned voff = (unsigned)(rb * 32 + mrow) * (unsigned)p.q_st_b + gh * 16;
 #pragma unroll
             for (int fr = 0; fr < FR; ++fr) {
                 const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * 32, 0, 0);

@@ -38,14 +38,30 @@ def valid_range(mask, window, q, block, N, block_k=None, L=None):
     return rmin, rmax
 
 
-def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0, block_k=None):
+def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0, block_k=None, C=None):
     """trace_row: int array [levels, k, 2] of (f, l) kept after each GPU level (-1 = dead).
-    Returns (ok, reason)."""
+    C: explicit [T, T] mask (then `mask` / `window` are not looked at).  Returns (ok, reason)."""
     T = Qh.shape[0]
     bk = block_k or block
     N = so.padded_len(T, block, bk) // bk     # key blocks: the nodes range over these
-    rmin, rmax = valid_range(mask, window, q, block, N, block_k, T)
-    rep = lambda f: max(f, rmin)              # a branch's representative: its first valid block
+    if C is None:
+        rmin, rmax = valid_range(mask, window, q, block, N, block_k, T)
+        def rep(f, l):                        # a branch's representative: its first valid block, or None
+            r = max(f, rmin)
+            return r if f <= l and r <= min(l, rmax) else None
+    else:
+        Cb = np.asarray(C) != 0
+        rows = Cb[q * block:min((q + 1) * block, T)]
+        cols = np.zeros((N * bk,), dtype=bool)
+        if rows.shape[0]:
+            cols[:T] = rows.any(axis=0)
+        vblk = cols.reshape(N, bk).any(axis=1)    # C^blk[q, :]
+        def rep(f, l):
+            if f > l:
+                return None
+            hit = np.nonzero(vblk[f:l + 1])[0]
+            return f + int(hit[0]) if len(hit) else None
+    score = lambda r: so.block_score(Qh, Kh, block, q, r, C=C, mask=mask, window=window, block_k=block_k)
     nodes = [((j * N) // k, ((j + 1) * N) // k - 1) for j in range(k)]
     nodes = [(f, l) for (f, l) in nodes if f <= l]
     for lv in range(trace_row.shape[0]):
@@ -53,7 +69,7 @@ def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0, block_k
         for (f, l) in nodes:
             m = (f + l + 1) // 2
             for (cf, cl) in ((f, m - 1), (m, l)):
-                if cf <= cl and rep(cf) <= min(cl, rmax):
+                if rep(cf, cl) is not None:
                     children.append((cf, cl))
         kept = [(int(f), int(l)) for f, l in trace_row[lv] if f >= 0]
         if len(set(kept)) != len(kept) or kept != sorted(kept):
@@ -64,14 +80,53 @@ def certify_row(Qh, Kh, block, k, q, trace_row, mask="causal", window=0, block_k
             return False, f"level {lv}: kept {len(kept)} of {len(children)} valid, k={k}"
         dropped = [c for c in children if c not in set(kept)]
         if dropped:
-            s_keep = min(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window, block_k=block_k) for f, _ in kept)
-            s_drop = max(so.block_score(Qh, Kh, block, q, rep(f), mask=mask, window=window, block_k=block_k) for f, _ in dropped)
+            s_keep = min(score(rep(f, l)) for f, l in kept)
+            s_drop = max(score(rep(f, l)) for f, l in dropped)
             if s_keep < s_drop - TIE_RTOL * max(abs(s_drop), abs(s_keep)):
                 return False, f"level {lv}: dropped {s_drop} > kept {s_keep}"
         nodes = kept
     if any(f != l for f, l in nodes):
         return False, "final nodes are not single blocks"
     return True, ""
+
+
+def compare_variable(gpu, ref, Q, K, heads, kv_heads, block, kmax, cu_seqlens=None, mask="causal",
+                     window=0, block_k=None, C=None):
+    """stream_prune_variable against oracle.prune_variable.  gpu: numpy idx [H, NB, kmax], cnt,
+    score (optional), trace [levels, H, NB, kmax, 2] (needed only if a row differs); ref: the
+    oracle's output (all rows, or the rows it lists).  Counts must be equal, lists equal or
+    certified level by level as in compare_prune.  Returns dict(rows, equal, tie_rows)."""
+    g = heads // kv_heads
+    T = Q.shape[1]
+    cu = [0, T] if cu_seqlens is None else [int(x) for x in cu_seqlens]
+    bseq, bloc = so.block_table(cu, block, block_k)
+    ri = ref["idx"].reshape(-1, kmax)
+    rc = ref["cnt"].reshape(-1)
+    rs = ref["score"].reshape(-1, kmax)
+    rk = ref["k"].reshape(-1)
+    equal = ties = 0
+    for i, (h, gb) in enumerate(ref["rows"]):
+        gi, gc = gpu["idx"][h, gb], int(gpu["cnt"][h, gb])
+        assert gc == int(rc[i]), (h, gb, gc, int(rc[i]))
+        assert (gi[gc:] == -1).all(), (h, gb)
+        if np.array_equal(gi, ri[i]):
+            equal += 1
+            if gpu.get("score") is not None and gc:
+                np.testing.assert_allclose(gpu["score"][h, gb, :gc], rs[i, :gc], rtol=1e-4,
+                                           atol=1e-4 * float(np.abs(rs[i, :gc]).max()))
+            continue
+        assert gpu.get("trace") is not None, f"row {(h, gb)} differs and no trace was taken"
+        s, q = int(bseq[gb]), int(bloc[gb])
+        k = int(rk[i])
+        Qh, Kh = Q[h, cu[s]:cu[s + 1]], K[h // g, cu[s]:cu[s + 1]]
+        n_key = so.padded_len(Qh.shape[0], block, block_k) // (block_k or block)
+        n_eff = max(1, math.ceil(math.log2(math.ceil(n_key / k))))
+        tr = gpu["trace"][:n_eff, h, gb, :k]
+        ok, why = certify_row(Qh, Kh, block, k, q, tr, mask=mask, window=window, block_k=block_k, C=C)
+        assert ok, f"row (h={h}, block={gb}, k={k}): {why}; gpu={gi[:gc]} oracle={ri[i][:gc]}"
+        assert list(tr[-1][:gc, 0]) == list(gi[:gc])
+        ties += 1
+    return {"rows": len(ref["rows"]), "equal": equal, "tie_rows": ties}
 
 
 def compare_prune(gpu, ref, Q, K, heads, kv_heads, block, topk, cu_seqlens=None, rows=None,

@@ -111,6 +111,9 @@ def test_bad_arguments_of_prune(lib):
     assert call(Q=ctypes.c_void_p(4100)) == B.STREAM_EINVAL  # not 16-byte aligned
     assert call(sh=shape(q_stride_t=100)) == B.STREAM_EINVAL  # rows shorter than head_dim
     assert call(sh=shape(q_stride_t=132)) == B.STREAM_EINVAL  # rows not 16-byte aligned
+    # a query block's rows are addressed with 32-bit offsets from the block's first row: token
+    # strides of 16 MiB and more are refused (anything below is fine whatever the sequence length)
+    assert call(sh=shape(q_stride_t=(1 << 23))) == B.STREAM_EUNSUPPORTED
     assert call(wsp=None) == B.STREAM_EWORKSPACE
     assert call(wsp=ctypes.c_void_p(4096 + 64)) == B.STREAM_EWORKSPACE
     assert call(wsz=need - 1) == B.STREAM_EWORKSPACE

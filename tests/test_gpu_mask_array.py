@@ -9,6 +9,7 @@ import torch
 
 from oracle import stream_oracle as so
 from paper_2510_19875_amd import binding, workloads as wl
+from tests import parity
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -99,13 +100,31 @@ def test_variable_k_and_split_levels_with_mask_array():
     torch.cuda.synchronize()
     assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["score"], b["score"])
     # k(row) = ceil(valid / 4) clamped to [1, 8], valid = key blocks C^blk leaves to the row
-    v = binding.stream_prune_variable(Qd, Kd, 4, 2, 64, 1, 4, 1, 8, mask_bits=bits)
+    v = binding.stream_prune_variable(Qd, Kd, 4, 2, 64, 1, 4, 1, 8, want_score=True, want_trace=True, mask_bits=bits)
     torch.cuda.synchronize()
     Tp = -(-T // 64) * 64
     Cp = np.zeros((Tp, Tp), bool); Cp[:T, :T] = C
     valid = Cp.reshape(Tp // 64, 64, Tp // 64, 64).any(axis=(1, 3)).sum(axis=1)
     want = np.minimum(np.clip(-(-valid // 4), 1, 8), valid)
     np.testing.assert_array_equal(v["cnt"].cpu().numpy(), np.broadcast_to(want, (4, Tp // 64)))
+    # the lists, against the oracle run row by row with the k the array leaves the row
+    Qf, Kf = Q.float().numpy(), K.float().numpy()
+    ref = so.prune_variable(Qf, Kf, 4, 2, 64, 1, 4, 1, 8, C=C)
+    gpu = {x: v[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")}
+    res = parity.compare_variable(gpu, ref, Qf, Kf, 4, 2, 64, 8, C=C)
+    print(f"[array] variable k: rows={res['rows']} equal={res['equal']} tie_rows={res['tie_rows']}", flush=True)
+    assert res["tie_rows"] <= 2
+    # rectangular blocks and a variable k under an array no rule expresses
+    Cr = masks(T, 4)["random"]
+    vr = binding.stream_prune_variable(Qd, Kd, 4, 2, 32, 1, 3, 2, 16, want_score=True, want_trace=True,
+                                       mask_bits=pack_bits(Cr), block_k=64)
+    torch.cuda.synchronize()
+    refr = so.prune_variable(Qf, Kf, 4, 2, 32, 1, 3, 2, 16, C=Cr, block_k=64)
+    gpur = {x: vr[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")}
+    resr = parity.compare_variable(gpur, refr, Qf, Kf, 4, 2, 32, 16, block_k=64, C=Cr)
+    print(f"[array] variable k, 32 x 64 blocks, random bits: rows={resr['rows']} equal={resr['equal']} "
+          f"tie_rows={resr['tie_rows']}", flush=True)
+    assert resr["tie_rows"] <= 2
     # the k sweep with the array: result i equals the single call
     ks = [8, 3, 1, 5]
     m = binding.stream_prune_multi(Qd, Kd, 4, 2, 64, ks, want_score=True, mask_bits=bits)

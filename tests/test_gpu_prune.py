@@ -8,6 +8,7 @@ from paper_2510_19875_amd import binding, workloads as wl
 from tests import parity
 
 pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
 
 
 def run_case(w, rows=None, n_rows=None, seed=0, heads_for_sample=None):
@@ -206,3 +207,36 @@ def test_two_streams_with_their_own_workspaces():
     for i in (0, 1):
         assert torch.equal(alone[i][0]["idx"], both[i][0]["idx"]) and torch.equal(alone[i][0]["score"], both[i][0]["score"])
         assert torch.equal(alone[i][1]["O"], both[i][1]["O"]) and torch.equal(alone[i][1]["lse"], both[i][1]["lse"])
+
+
+def test_token_major_q_spanning_more_than_4_gib():
+    """Q as a strided view whose last token lies more than 4 GiB after the first (a fused
+    projection output, or a long sequence laid out token-major): the kernels address a query
+    block from its own first row, so the lists equal those from a contiguous copy, and the last
+    rows equal the oracle's."""
+    T, d, H = 70_001, 128, 2
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    Qc = torch.randn((H, T, d), device=DEV, generator=gen).to(torch.bfloat16)
+    Kc = torch.randn((1, T, d), device=DEV, generator=gen).to(torch.bfloat16)
+    pitch = 32768                                                 # elements per token: 64 KiB
+    big = torch.zeros((T, pitch), dtype=torch.bfloat16, device=DEV)
+    for h in range(H):
+        big[:, h * d:(h + 1) * d] = Qc[h]
+    Qv = big.as_strided((H, T, d), (d, pitch, 1))
+    assert (T - 1) * pitch * 2 > (1 << 32)
+    a = binding.stream_prune(Qc, Kc, H, 1, 64, 8, want_score=True)
+    b = binding.stream_prune(Qv, Kc, H, 1, 64, 8, want_score=True)
+    k100 = binding.stream_prune(Qv, Kc, H, 1, 64, 100)           # the kernel with the lists in LDS
+    k100c = binding.stream_prune(Qc, Kc, H, 1, 64, 100)
+    torch.cuda.synchronize()
+    assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["score"], b["score"])
+    assert torch.equal(k100["idx"], k100c["idx"])
+    NB = a["idx"].shape[1]
+    rows = [(h, q) for h in range(H) for q in (NB - 1, NB - 2, NB - 300, NB // 2 + 11)]
+    Qf, Kf = Qc.float().cpu().numpy(), Kc.float().cpu().numpy()
+    ref = so.prune(Qf, Kf, H, 1, 64, 8, rows=rows)
+    gi = b["idx"].cpu().numpy()
+    same = sum(int(np.array_equal(gi[h, q], ref["idx"][i])) for i, (h, q) in enumerate(rows))
+    print(f"[prune] strided Q beyond 4 GiB: {same} of {len(rows)} sampled rows equal the oracle", flush=True)
+    assert same >= len(rows) - 1

@@ -85,14 +85,15 @@ def test_wide_ragged_batch_and_variable_k():
     # k(row) = ceil(valid / 3) clamped to [1, 200]: rows with k <= 64 and rows with k > 64 in one call
     w2 = wl.scaled(wl.config(2), (32 * 400 + 5,), topk=8, heads=2, kv_heads=1, block=32, needles_per_kv_head=2)
     Q, K, _, _ = wl.make_inputs(w2, with_v=False)
-    v = binding.stream_prune_variable(Q.to(DEV), K.to(DEV), 2, 1, 32, 1, 3, 1, 200, want_score=True)
+    v = binding.stream_prune_variable(Q.to(DEV), K.to(DEV), 2, 1, 32, 1, 3, 1, 200, want_score=True, want_trace=True)
     torch.cuda.synchronize()
-    ref = so.prune_variable(Q.float().numpy(), K.float().numpy(), 2, 1, 32, 1, 3, 1, 200)
-    np.testing.assert_array_equal(v["cnt"].cpu().numpy(), ref["cnt"])
-    gi = v["idx"].cpu().numpy()
-    differ = int((gi != ref["idx"]).any(axis=2).sum())
-    print(f"[wide] variable k: {differ} of {gi.shape[0] * gi.shape[1]} rows differ from the oracle", flush=True)
-    assert differ <= 4                                            # (near-ties only)
+    Qf, Kf = Q.float().numpy(), K.float().numpy()
+    ref = so.prune_variable(Qf, Kf, 2, 1, 32, 1, 3, 1, 200)
+    gpu = {x: v[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")}
+    # every row equal to the oracle's, or certified level by level along the kernel's own trace
+    res = parity.compare_variable(gpu, ref, Qf, Kf, 2, 1, 32, 200)
+    print(f"[wide] variable k: rows={res['rows']} equal={res['equal']} tie_rows={res['tie_rows']}", flush=True)
+    assert res["tie_rows"] <= max(2, res["rows"] // 100)
 
 
 def test_wide_and_narrow_kernels_agree():

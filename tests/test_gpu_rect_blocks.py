@@ -92,7 +92,7 @@ def test_prune_ragged_batch_per_sequence_k_and_sweep():
         torch.cuda.synchronize()
         np.testing.assert_array_equal(m["idx"][:, i, :, :k].cpu().numpy(), one["idx"].cpu().numpy())
         np.testing.assert_array_equal(m["score"][:, i, :, :k].cpu().numpy(), one["score"].cpu().numpy())
-    v = binding.stream_prune_variable(Qd, Kd, 4, 2, 64, 1, 8, 1, 8, block_k=32)
+    v = binding.stream_prune_variable(Qd, Kd, 4, 2, 64, 1, 8, 1, 8, block_k=32, want_score=True, want_trace=True)
     torch.cuda.synchronize()
     cnt = v["cnt"].cpu().numpy()
     N = cnt.shape[1]
@@ -100,6 +100,21 @@ def test_prune_ragged_batch_per_sequence_k_and_sweep():
     valid = valid // 32 + 1
     want_k = np.clip(-(-valid // 8), 1, 8)
     np.testing.assert_array_equal(cnt, np.broadcast_to(np.minimum(want_k, valid), cnt.shape))
+    # the lists, against the oracle run row by row with the row's own k
+    Qf, Kf = Q.float().numpy(), K.float().numpy()
+    gpu = {x: v[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")}
+    for (bq, bk, mask, window, share) in ((64, 32, "causal", 0, (1, 8)), (32, 128, "sliding", 700, (1, 2)),
+                                          (128, 64, "full", 0, (1, 16))):
+        if (bq, bk) != (64, 32):
+            vv = binding.stream_prune_variable(Qd, Kd, 4, 2, bq, share[0], share[1], 1, 8, block_k=bk, mask=mask,
+                                               window=window, want_score=True, want_trace=True)
+            torch.cuda.synchronize()
+            gpu = {x: vv[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")}
+        ref = so.prune_variable(Qf, Kf, 4, 2, bq, share[0], share[1], 1, 8, mask=mask, window=window, block_k=bk)
+        res = parity.compare_variable(gpu, ref, Qf, Kf, 4, 2, bq, 8, mask=mask, window=window, block_k=bk)
+        print(f"[rect] variable k {bq}x{bk} {mask}: rows={res['rows']} equal={res['equal']} "
+              f"tie_rows={res['tie_rows']}", flush=True)
+        assert res["tie_rows"] <= 2
 
 
 def attn_case(w, bk, mask="causal", window=0):

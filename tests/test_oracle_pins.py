@@ -330,3 +330,82 @@ def test_received_mass_invariants():
             kept[p["idx"][h, q, :p["cnt"][h, q]]] = True
         never = np.repeat(~kept, b)[:T]
         assert np.all(o["mass"][h, never] == 0)
+
+
+def test_level_certificate_accepts_the_oracle_trace_and_rejects_planted_mistakes():
+    """The checker that replays a differing GPU row level by level (tests/parity.py) is itself
+    checked here on the CPU: it accepts the oracle's own per-level trace under a rule, with
+    rectangular blocks and with an explicit array, and rejects a trace in which one kept branch is
+    swapped for a clearly worse sibling, one with a branch too few, and one that keeps a branch
+    the mask hides."""
+    from tests import parity
+
+    rng = np.random.default_rng(31)
+    T, d = 4 * 37 + 2, 8
+    Qh = rng.standard_normal((T, d)).astype(np.float32)
+    Kh = rng.standard_normal((T, d)).astype(np.float32)
+    t = np.arange(T)[:, None]
+    u = np.arange(T)[None, :]
+    docs = (u <= t) & ((t // 50) == (u // 50))                 # three packed documents
+    cases = [dict(block=4, k=3), dict(block=4, k=3, mask="sliding", window=40),
+             dict(block=4, k=2, block_k=8), dict(block=8, k=5, block_k=4, mask="full"),
+             dict(block=4, k=3, C=docs), dict(block=4, k=2, block_k=8, C=docs)]
+    for kw in cases:
+        block, k = kw["block"], kw["k"]
+        extra = {x: kw[x] for x in ("mask", "window", "block_k", "C") if x in kw}
+        nq = so.padded_len(T, block, kw.get("block_k")) // block
+        rejected = 0
+        for q in (nq - 1, nq // 2, 1):
+            r = so.prune_head(Qh, Kh, block, k, [q], want_trace=True, **extra)
+            n_key = so.padded_len(T, block, kw.get("block_k")) // kw.get("block_k", block)
+            n_eff = max(1, int(np.ceil(np.log2(np.ceil(n_key / k)))))
+            tr = r["trace"][0][:n_eff]
+            ok, why = parity.certify_row(Qh, Kh, block, k, q, tr, **extra)
+            assert ok, (kw.keys(), q, why)
+            # a branch too few at the first level that prunes
+            for lv in range(n_eff):
+                live = int((tr[lv][:, 0] >= 0).sum())
+                if live >= 2:
+                    bad = tr.copy()
+                    bad[lv][live - 1] = -1
+                    ok, _ = parity.certify_row(Qh, Kh, block, k, q, bad, **extra)
+                    assert not ok
+                    rejected += 1
+                    break
+            # the last level's best block swapped for the worst valid sibling the level dropped
+            last = [(int(f), int(l)) for f, l in tr[-1] if f >= 0]
+            prev = [(int(f), int(l)) for f, l in (tr[-2] if n_eff > 1 else [])]
+            cands = []
+            for (f, l) in prev:
+                m = (f + l + 1) // 2
+                for c in ((f, m - 1), (m, l)):
+                    if c[0] <= c[1] and c not in last:
+                        cands.append(c)
+            scored = []
+            for c in cands:
+                rp = [x for x in range(c[0], c[1] + 1)]
+                sc = [so.block_score(Qh, Kh, block, q, x, **extra) for x in rp]
+                fin = [v for v in sc if np.isfinite(v)]
+                if fin:
+                    scored.append((sc[[i for i, v in enumerate(sc) if np.isfinite(v)][0]], c))
+            if scored and last:
+                kept_scores = [so.block_score(Qh, Kh, block, q, f, **extra) for f, _ in last]
+                worst = min(scored)
+                best_i = int(np.argmax(kept_scores))
+                if worst[0] < kept_scores[best_i] - 0.5:
+                    bad = tr.copy()
+                    row = [c for i, c in enumerate(last) if i != best_i] + [worst[1]]
+                    row.sort()
+                    bad[-1][:] = -1
+                    for i, c in enumerate(row):
+                        bad[-1][i] = c
+                    ok, _ = parity.certify_row(Qh, Kh, block, k, q, bad, **extra)
+                    assert not ok
+                    rejected += 1
+        assert rejected >= 2, kw.keys()
+    # a kept branch the mask hides (future blocks under the causal rule)
+    r = so.prune_head(Qh, Kh, 4, 3, [5], want_trace=True)
+    tr = r["trace"][0][:4].copy()
+    tr[0][0] = (20, 24)
+    ok, _ = parity.certify_row(Qh, Kh, 4, 3, 5, tr)
+    assert not ok

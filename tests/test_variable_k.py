@@ -57,6 +57,75 @@ def test_keeps_the_same_share_of_every_row():
     assert c["cnt"][0, N - 1] / N < 0.07 < 0.25 <= v["cnt"][0, N - 1] / N
 
 
+def dense_rule_mask(T, mask, window):
+    t = np.arange(T)[:, None]
+    u = np.arange(T)[None, :]
+    if mask == "full":
+        return np.ones((T, T), bool)
+    c = u <= t
+    return c & (t - u < window) if mask == "sliding" else c
+
+
+@pytest.mark.parametrize("bq,bk", [(4, 4), (4, 8), (8, 4), (2, 8), (8, 2)])
+def test_valid_blocks_equal_the_dense_block_mask(bq, bk):
+    """The closed-form counts (rules, square and rectangular blocks) and the count read off an
+    explicit array both equal C^blk of the preamble of Alg. 2 written out densely: pad C with zero
+    rows and columns to T_p, take the maximum over every b_q x b_k span, count the ones of a row."""
+    for T in (1, 7, 8, 29, 64, 67):
+        Tp = so.padded_len(T, bq, bk)
+        for mask, window in (("causal", 0), ("full", 0), ("sliding", 1), ("sliding", 5), ("sliding", 13), ("sliding", 1000)):
+            C = dense_rule_mask(T, mask, window)
+            Cp = np.zeros((Tp, Tp), bool)
+            Cp[:T, :T] = C
+            dense = Cp.reshape(Tp // bq, bq, Tp // bk, bk).any(axis=(1, 3)).sum(axis=1)
+            for q in range(Tp // bq):
+                if bq == bk:
+                    assert so.valid_blocks(q, Tp // bq, bq, mask, window) == dense[q], (T, mask, window, q)
+                assert so.valid_blocks(q, 0, bq, mask, window, block_k=bk, L=T) == dense[q], (T, mask, window, q)
+                assert so.valid_blocks(q, 0, bq, block_k=bk, C=C) == dense[q], (T, mask, window, q)
+    # an array no rule expresses: random bits
+    rng = np.random.default_rng(9)
+    T = 45
+    C = rng.random((T, T)) < 0.03
+    Tp = so.padded_len(T, bq, bk)
+    Cp = np.zeros((Tp, Tp), bool)
+    Cp[:T, :T] = C
+    dense = Cp.reshape(Tp // bq, bq, Tp // bk, bk).any(axis=(1, 3)).sum(axis=1)
+    assert [so.valid_blocks(q, 0, bq, block_k=bk, C=C) for q in range(Tp // bq)] == list(dense)
+
+
+@pytest.mark.parametrize("bq,bk", [(4, 4), (4, 8), (8, 4)])
+def test_variable_k_with_rectangular_blocks_and_arrays(bq, bk):
+    """prune_variable under b_q != b_k and under an explicit array: a rule written out as an array
+    gives the rule's result; every row is Alg. 2 with the k the row's valid count gives; with an
+    arbitrary array the kept blocks are valid ones, as many as min(k(row), valid(row))."""
+    rng = np.random.default_rng(12)
+    T = 8 * 11 + 3
+    Q, K = gauss(rng, T, 6)[None], gauss(rng, T, 6)[None]
+    for mask, window in (("causal", 0), ("sliding", 21), ("full", 0)):
+        rule = so.prune_variable(Q, K, 1, 1, bq, 1, 3, 1, 6, mask=mask, window=window, block_k=bk)
+        arr = so.prune_variable(Q, K, 1, 1, bq, 1, 3, 1, 6, block_k=bk, C=dense_rule_mask(T, mask, window))
+        for key in ("idx", "cnt", "k"):
+            np.testing.assert_array_equal(rule[key], arr[key])
+        for q in range(rule["idx"].shape[1]):
+            k = int(rule["k"][0, q])
+            one = so.prune_head(Q[0], K[0], bq, k, [q], mask=mask, window=window, block_k=bk)
+            np.testing.assert_array_equal(rule["idx"][0, q, :k], one["idx"][0])
+            assert (rule["idx"][0, q, k:] == -1).all()
+    C = rng.random((T, T)) < 0.02
+    v = so.prune_variable(Q, K, 1, 1, bq, 1, 2, 1, 6, block_k=bk, C=C)
+    Tp = so.padded_len(T, bq, bk)
+    Cp = np.zeros((Tp, Tp), bool)
+    Cp[:T, :T] = C
+    Cblk = Cp.reshape(Tp // bq, bq, Tp // bk, bk).any(axis=(1, 3))
+    for q in range(Tp // bq):
+        valid = int(Cblk[q].sum())
+        k = min(6, max(1, -(-valid // 2)))
+        assert v["k"][0, q] == k and v["cnt"][0, q] == min(k, valid)
+        kept = v["idx"][0, q, :v["cnt"][0, q]]
+        assert all(Cblk[q, r] for r in kept) and list(kept) == sorted(set(kept))
+
+
 # ------------------------------------------------------------------ GPU parity
 def run_gpu_case(w, keep, kmin, kmax, mask="causal", window=0, n_rows=None):
     import torch
@@ -71,34 +140,15 @@ def run_gpu_case(w, keep, kmin, kmax, mask="causal", window=0, n_rows=None):
                                         kmin, kmax, cu_seqlens=cu, want_score=True, want_trace=True,
                                         mask=mask, window=window)
     torch.cuda.synchronize()
-    gi, gc, gs, gt = (out[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace"))
+    gpu = {x: out[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")}
     Qf, Kf = Q.float().numpy(), K.float().numpy()
     rows = parity.sample_rows(w, n_rows, seed=3) if n_rows is not None else None
     ref = so.prune_variable(Qf, Kf, w.heads, w.kv_heads, w.block, keep[0], keep[1], kmin, kmax,
                             cu_seqlens=cu, rows=rows, mask=mask, window=window)
-    g = w.heads // w.kv_heads
-    cul = w.cu_seqlens
-    bseq, bloc = so.block_table(cul, w.block)
-    ri = ref["idx"].reshape(-1, kmax); rc = ref["cnt"].reshape(-1); rs = ref["score"].reshape(-1, kmax)
-    rk = ref["k"].reshape(-1)
-    equal = ties = 0
-    for i, (h, gb) in enumerate(ref["rows"]):
-        assert gc[h, gb] == rc[i]
-        c = int(rc[i])
-        assert (gi[h, gb, c:] == -1).all()
-        if np.array_equal(gi[h, gb], ri[i]):
-            equal += 1
-            np.testing.assert_allclose(gs[h, gb, :c], rs[i, :c], rtol=1e-4, atol=1e-4 * float(np.abs(rs[i, :c]).max()))
-        else:
-            s, q = int(bseq[gb]), int(bloc[gb])
-            k = int(rk[i])
-            Qh, Kh = Qf[h, cul[s]:cul[s + 1]], Kf[h // g, cul[s]:cul[s + 1]]
-            n_eff = max(1, math.ceil(math.log2(math.ceil((-(-Qh.shape[0] // w.block)) / k))))
-            ok, why = parity.certify_row(Qh, Kh, w.block, k, q, gt[:n_eff, h, gb, :k], mask=mask, window=window)
-            assert ok, (h, gb, why)
-            ties += 1
-    print(f"[vark] rows={len(ref['rows'])} equal={equal} ties={ties}", flush=True)
-    assert ties <= max(2, len(ref["rows"]) // 100)
+    res = parity.compare_variable(gpu, ref, Qf, Kf, w.heads, w.kv_heads, w.block, kmax, cu_seqlens=cu,
+                                  mask=mask, window=window)
+    print(f"[vark] rows={res['rows']} equal={res['equal']} ties={res['tie_rows']}", flush=True)
+    assert res["tie_rows"] <= max(2, res["rows"] // 100)
 
 
 @pytest.mark.gpu
