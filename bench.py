@@ -232,6 +232,8 @@ def main():
                                             else float(Q_BYTES + K_BYTES * 0.25 + H * NB * (24 * kmax + 4)),
         },
     }
+    if w.batch == 1 and H * NB * NB <= (1 << 31):
+        result["list_sharing"] = list_sharing(out_p["idx"], out_p["cnt"], Hkv)
     if not args.no_select:
         result["select_roofline"] = select_standalone(kmax)
     if not args.no_select:
@@ -258,6 +260,29 @@ def main():
         torch.cuda.synchronize()
         result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale, gp, ga)
     print(json.dumps(result))
+
+
+def list_sharing(idx, cnt, kv_heads):
+    """How much the retained lists overlap where the attention kernel could share K/V tiles:
+    between the query heads of one key/value head at the same query block, and between adjacent
+    query blocks of one head.  Fractions of all list entries."""
+    import torch
+
+    H, NB, kmax = idx.shape
+    g = H // kv_heads
+    live = torch.arange(kmax, device=idx.device)[None, None, :] < cnt[:, :, None]
+    pres = torch.zeros((H, NB, NB + 1), dtype=torch.bool, device=idx.device)
+    pres.scatter_(2, torch.where(live, idx, torch.full_like(idx, NB)).long(), True)
+    pres = pres[:, :, :NB]
+    total = float(cnt.sum().item())
+    union = float(pres.view(kv_heads, g, NB, NB).any(dim=1).sum().item())
+    adjacent = float((pres[:, 1:] & pres[:, :-1]).sum().item())
+    pairs = float(((pres[:, 0::2][:, :NB // 2]) | (pres[:, 1::2][:, :NB // 2])).sum().item())
+    return {"entries": total,
+            "distinct_per_kv_head_and_query_block": union,
+            "saved_by_sharing_within_gqa_group": 1.0 - union / total,
+            "entries_also_in_previous_query_block": adjacent / total,
+            "saved_by_sharing_between_two_adjacent_query_blocks": 1.0 - pairs / total}
 
 
 def dense_reference(w, layer):
