@@ -162,6 +162,32 @@ stream_status stream_prune(const void *Q, const void *K, const stream_shape *sha
                            int *idx, int *cnt, float *score, const stream_prune_diag *diag,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * stream_prune for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs and errors as stream_prune without `workspace`; the scratch (packed K
+ * tiles, node lists, block summaries of a mask array) is a device array of
+ * STREAM_STATIC_SCRATCH_BYTES that belongs to the library: every GPU the library is used on holds
+ * it from the moment the library is loaded there until the process ends.  The call allocates and
+ * frees nothing (no hipMalloc / hipFree, no allocating library routine) and never synchronises.
+ *
+ *   - Problems whose stream_prune_workspace_bytes(shape, topk_max) exceeds
+ *     STREAM_STATIC_SCRATCH_BYTES return STREAM_EWORKSPACE before anything is launched (80 MiB
+ *     covers e.g. 32,768 tokens x 8 KV heads x head_dim 128 in bf16 with k = 16, or 10 sequences
+ *     of 8 K tokens at 28/4 heads).
+ *   - The first call on a device looks up the array's address there (one hipGetSymbolAddress, no
+ *     allocation); make that call outside a graph capture.
+ *   - All calls on one GPU share that GPU's array, which keeps whatever the last call left in it
+ *     (nothing in it has to start at zero).  Calls that overlap in time on one GPU - different
+ *     streams, or different host threads - race on it: serialise them.
+ */
+#define STREAM_STATIC_SCRATCH_BYTES (80 * 1024 * 1024)
+
+stream_status stream_prune_static(const void *Q, const void *K, const stream_shape *shape,
+                                  int topk, const int *topk_per_seq, int topk_max,
+                                  int *idx, int *cnt, float *score, const stream_prune_diag *diag,
+                                  void *hip_stream);
+
 size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_max);
 
 /*

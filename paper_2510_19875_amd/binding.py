@@ -19,7 +19,7 @@ STREAM_OK, STREAM_EINVAL, STREAM_EUNSUPPORTED, STREAM_EWORKSPACE, STREAM_EDEVICE
 STREAM_F32, STREAM_BF16 = 0, 1
 
 EXPORTS = ["stream_num_blocks", "stream_num_key_blocks", "stream_prune_levels", "stream_prune_workspace_bytes",
-           "stream_prune", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
+           "stream_prune", "stream_prune_static", "stream_sparse_attn_workspace_bytes", "stream_sparse_attn",
            "stream_prune_multi_workspace_bytes", "stream_prune_multi", "stream_prune_variable",
            "stream_select_update", "stream_mask_diff", "stream_receiver_stats_workspace_bytes",
            "stream_receiver_stats", "stream_status_str"]
@@ -74,6 +74,9 @@ def load():
     lib.stream_prune.restype = ctypes.c_int
     lib.stream_prune.argtypes = [vp, vp, sp, ctypes.c_int, ip, ctypes.c_int, vp, vp, vp,
                                  ctypes.POINTER(StreamPruneDiag), vp, ctypes.c_size_t, vp]
+    lib.stream_prune_static.restype = ctypes.c_int
+    lib.stream_prune_static.argtypes = [vp, vp, sp, ctypes.c_int, ip, ctypes.c_int, vp, vp, vp,
+                                        ctypes.POINTER(StreamPruneDiag), vp]
     lib.stream_sparse_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.stream_sparse_attn_workspace_bytes.argtypes = [sp, ctypes.c_int]
     lib.stream_sparse_attn.restype = ctypes.c_int
@@ -216,6 +219,37 @@ def stream_prune(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, bl
         raise StreamError(rc, "stream_prune")
     return {"idx": idx, "cnt": cnt, "score": score, "trace": trace, "tiles": tiles,
             "levels": levels, "workspace": workspace, "_keep": keep}
+
+
+STATIC_SCRATCH_BYTES = 80 * 1024 * 1024   # STREAM_STATIC_SCRATCH_BYTES of include/stream.h
+
+
+def stream_prune_static(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,
+                        topk, out, cu_seqlens: Optional[Sequence[int]] = None, mask="causal",
+                        window: int = 0, block_k: int = 0, mask_bits=None):
+    """stream_prune through the entry point that allocates nothing: the scratch is the library's
+    own device array, the outputs out["idx"] [H, NB, kmax], out["cnt"] [H, NB] and (optional)
+    out["score"] come from the caller.  Raises StreamError(STREAM_EWORKSPACE) beyond the limit."""
+    lib = load()
+    if not (Q.is_cuda and K.is_cuda):
+        raise ValueError("Q and K must be device tensors (the library has no CPU path)")
+    H, T, d = Q.shape
+    shape, keep = make_shape(heads, kv_heads, d, block, _dtype_code(Q), T, cu_seqlens, Q=Q, K=K,
+                             mask=mask, window=window, block_k=block_k, mask_bits=mask_bits)
+    if isinstance(topk, int):
+        ks, kmax, k_arr = None, int(topk), None
+    else:
+        ks = [int(x) for x in topk]
+        kmax = max(ks)
+        k_arr = (ctypes.c_int * shape.batch)(*ks)
+    idx, cnt, score = out["idx"], out["cnt"], out.get("score")
+    rc = lib.stream_prune_static(Q.data_ptr(), K.data_ptr(), ctypes.byref(shape),
+                                 kmax if ks is None else 0, k_arr, idx.shape[-1],
+                                 idx.data_ptr(), cnt.data_ptr(), score.data_ptr() if score is not None else None,
+                                 None, _stream_ptr())
+    if rc != STREAM_OK:
+        raise StreamError(rc, "stream_prune_static")
+    return {"idx": idx, "cnt": cnt, "score": score, "_keep": keep}
 
 
 def stream_prune_multi(Q: torch.Tensor, K: torch.Tensor, heads: int, kv_heads: int, block: int,

@@ -14,6 +14,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 namespace stream {
 
 // Template parameters: element type, head dim, 32-row groups of Q per wavefront (MB), 32-key
@@ -461,6 +463,33 @@ static level_fn pick_level_kernel(const Problem &pb, bool multi, int &wpr)
 
 using namespace stream;
 
+// ---------------------------------------------------------------------------------------------
+// Scratch of stream_prune_static: the workspace of stream_prune (packed K tiles, node lists,
+// block bitmaps of a mask array) in a device array that belongs to the library, for callers that
+// cannot allocate.  Every GPU the library runs on holds its own copy at its own address; host
+// code never uses the array's name as an address, only the pointer hipGetSymbolAddress returns
+// for the device that is current.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[STREAM_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];      // per device, set on the first call there
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr.
+static void *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 // Packs K and runs the refinement kernel: once per group of levels, or (topk_list != nullptr)
 // once for a whole sweep over k, every row then running all its levels for every k in turn.
 struct VariableK { int num, den, kmin; };   // den == 0: off
@@ -582,6 +611,25 @@ stream_status stream_prune(const void *Q, const void *K, const stream_shape *sha
     if (rc != STREAM_OK) return rc;
     return run_prune(Q, K, shape, pb, nullptr, 0, VariableK{0, 0, 0}, idx, cnt, score, diag, workspace,
                      workspace_bytes, hip_stream);
+}
+
+stream_status stream_prune_static(const void *Q, const void *K, const stream_shape *shape,
+                                  int topk, const int *topk_per_seq, int topk_max,
+                                  int *idx, int *cnt, float *score, const stream_prune_diag *diag,
+                                  void *hip_stream)
+{
+    if (!Q || !K || !shape || !idx || !cnt) return STREAM_EINVAL;
+    if (topk_max < 1) return STREAM_EINVAL;
+    Problem pb;
+    stream_status rc = make_problem(shape, topk, topk_per_seq, topk_max, &pb);
+    if (rc != STREAM_OK) return rc;
+    if (prune_layout(pb).total > (size_t)STREAM_STATIC_SCRATCH_BYTES) return STREAM_EWORKSPACE;
+    void *ws = scratch_of_current_device();
+    if (!ws) return STREAM_EDEVICE;
+    // (nothing in the scratch has to start at zero: the packer rewrites every tile the kernels
+    // read, node lists and bitmaps are written before they are read)
+    return run_prune(Q, K, shape, pb, nullptr, 0, VariableK{0, 0, 0}, idx, cnt, score, diag, ws,
+                     (size_t)STREAM_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 size_t stream_prune_multi_workspace_bytes(const stream_shape *shape, int n_k, int topk_max)
