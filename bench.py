@@ -32,12 +32,36 @@ PEAK_FP32_MFMA_TFLOPS = 157.3    # MI355X fp32 (the contraction of the fp32 work
 def mfma_peak(dtype: str) -> float:
     return PEAK_BF16_MFMA_TFLOPS if dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per level-kernel launch at the headline workload, from the
-# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/cfg3_pmc_counters.txt, per
-# launch of the level kernel in its default form (all levels of a row in one launch):
-# FETCH_SIZE 4.576e6 x 2.0 (the factor a plain 268 MB copy shows for this counter) + WRITE_SIZE
-# 1.716e4 x 1.0, in KiB.  Only meaningful for that workload and launch form.
-LEVEL_KERNEL_HBM_BYTES = {"cfg3_T131072_gqa32x8_d128_bf16": (4.576e6 * 2.0 + 1.716e4) * 1024.0}
+# HBM-side bytes per launch of the dominant kernel come from the rocprofv3 --pmc summary under
+# profiles/ (FETCH_SIZE and WRITE_SIZE runs, scaled by what the same counters read for a plain copy
+# of known size).  The summary records the hash of the kernel sources it was taken with; when the
+# sources on disk differ, the figure is not that of the binary being timed and `traffic` is null.
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "cfg3_pmc_counters.txt")
+LEVEL_KERNEL_SOURCES = ["stream_prune.hip", "stream_prune.h", "stream_select.h", "stream_mfma.h", "stream_common.h"]
+
+
+def kernel_source_hash(files=LEVEL_KERNEL_SOURCES) -> str:
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in files:
+        with open(os.path.join(ROOT, "paper_2510_19875_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def level_kernel_traffic(workload: str):
+    """Bytes per launch from the line `traffic level_kernel <workload> <bytes> sources <hash>` of the
+    counter summary, or None when there is no such line for these sources."""
+    try:
+        with open(PMC_SUMMARY) as fh:
+            for line in fh:
+                t = line.split()
+                if len(t) >= 6 and t[0] == "traffic" and t[1] == "level_kernel" and t[2] == workload:
+                    return float(t[3]) if t[5] == kernel_source_hash() else None
+    except OSError:
+        pass
+    return None
 
 
 class HipEvents:
@@ -227,7 +251,7 @@ def main():
             "flop_per_launch": float(flops_per_step.sum() / launches),
             "avg_launch_ms": float(level_ms.sum() / launches),
             "launches": launches,
-            "traffic": LEVEL_KERNEL_HBM_BYTES.get(w.name) if n_launch == 1 else None,
+            "traffic": level_kernel_traffic(w.name) if n_launch == 1 else None,
             "algorithmic_bytes_per_launch": float(Q_BYTES + K_BYTES + H * NB * (8 * kmax + 4)) if n_launch == 1
                                             else float(Q_BYTES + K_BYTES * 0.25 + H * NB * (24 * kmax + 4)),
         },

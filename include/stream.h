@@ -198,8 +198,12 @@ size_t stream_sparse_attn_workspace_bytes(const stream_shape *shape, int topk_ma
  * A query that sees none of its row's retained keys (possible under a window or a mask array)
  * gets O_t = 0 and lse = -inf.
  *
- *   idx, cnt      as written by stream_prune (any ascending lists of valid key-block ids work);
- *                 topk_max <= 512
+ *   idx, cnt      as written by stream_prune: strictly ascending ids of key blocks of the
+ *                 sequence (any such lists work); topk_max <= 512.  Other lists are handled safely
+ *                 rather than fast: a row whose list is not strictly ascending or holds an id
+ *                 outside [0, key blocks of the sequence) takes the token-level mask on every
+ *                 tile, so a key after its query or outside the sequence never counts; ids outside
+ *                 the range contribute nothing, an id listed twice counts twice
  *   scale         multiplies the dot products (the paper's Eq. (2) has scale = 1; models use
  *                 1/sqrt(head_dim))
  *   O             [heads, T, head_dim] in the input dtype

@@ -228,17 +228,9 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
 
     // key sub-tiles to visit: all of every listed block, except that under a causal rule the
     // sub-tiles of the diagonal block lying entirely after this wavefront's queries are dropped
-    // (lists are ascending, so the diagonal block, if present, is the last one)
+    // (lists are ascending, so the diagonal block, if present, is the last one); the count is
+    // fixed further down, once the list has been looked at
     int n_tiles = n_blk * KSUB;
-    if (!ARB && n_blk > 0 && p.mask != STREAM_MASK_FULL) {
-        const int last_r = my_idx[n_blk - 1];
-        if (last_r * BK + (KSUB - 1) * KT > qtok0 + QT - 1) {
-            int vis = (qtok0 + QT - 1 - last_r * BK) / KT + 1;
-            vis = vis < 0 ? 0 : (vis > KSUB ? KSUB : vis);
-            n_tiles = (n_blk - 1) * KSUB + vis;
-        }
-    }
-    n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
 
     // Q fragments (usable as A or B operand): lane (col, gh), fragment fr -> chunk 2*fr+gh of row col
     uint4 qf[NQ][FR];
@@ -270,15 +262,37 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     auto all_bit = [&](int r) -> bool {          // (an entry outside the block range reads as "cut")
         return (unsigned)r < (unsigned)p.cw * 32u && ((allrow[r >> 5] >> (r & 31)) & 1u);
     };
+    // The loops below assume what stream_prune writes: strictly ascending ids of key blocks of the
+    // sequence.  A list that is anything else (not ascending, a repeated id, an id outside the
+    // sequence) is still handled safely: `plain_list` sends every sub-tile through the plain order
+    // with the token-level mask (so no key after a query, and no key outside the sequence, ever
+    // counts), and the trimming of the last block is skipped.
+    const int nkb = (int)((long long)sd.nblk * BQ / BK);          // key blocks of the sequence
+    bool entry_bad = false;
     if constexpr (WIDE) {
         for (int i = lane; i < n_blk; i += 64) {
             int v = my_idx[i];
+            const int before = i > 0 ? my_idx[i - 1] : -1;
+            entry_bad = entry_bad | ((unsigned)v >= (unsigned)nkb) | (v <= before);
             // (with a mask array the top bit of an entry says that C cuts through the block)
             if constexpr (ARB) v |= all_bit(v) ? 0 : (int)0x80000000;
             s_blk[wave][i] = v;
         }
         wave_sync();
+    } else {
+        const int before = __shfl_up(my_blk, 1);
+        entry_bad = (lane < n_blk) & (((unsigned)my_blk >= (unsigned)nkb) | ((lane > 0) & (my_blk <= before)));
     }
+    const bool plain_list = __ballot(entry_bad) != 0ull;          // wave-uniform
+    if (!ARB && !plain_list && n_blk > 0 && p.mask != STREAM_MASK_FULL) {
+        const int last_r = my_idx[n_blk - 1];
+        if (last_r * BK + (KSUB - 1) * KT > qtok0 + QT - 1) {
+            int vis = (qtok0 + QT - 1 - last_r * BK) / KT + 1;
+            vis = vis < 0 ? 0 : (vis > KSUB ? KSUB : vis);
+            n_tiles = (n_blk - 1) * KSUB + vis;
+        }
+    }
+    n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
     auto list_entry = [&](int i) -> int {        // i is wave-uniform
         if constexpr (WIDE)
             return __builtin_amdgcn_readfirstlane(s_blk[wave][i]) & 0x7fffffff;
@@ -308,6 +322,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     if constexpr (ARB && !WIDE)
         allmask = __ballot(lane < n_blk && all_bit(my_blk));
     auto tile_masked = [&](int t) -> bool {      // t is wave-uniform
+        if (plain_list) return true;
         if constexpr (ARB && WIDE)
             return __builtin_amdgcn_readfirstlane(s_blk[wave][__builtin_amdgcn_readfirstlane(t) / KSUB]) < 0;
         else if constexpr (ARB)
@@ -425,7 +440,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         const int tq = qtok0 + cq * 32 + col;
                         // (a select, not a conditional store: `if (!visible) acc_s[..][i] = -inf` on a
                         // vector element was dropped by this compiler inside the lambda)
-                        bool visible = tk < L;
+                        bool visible = (unsigned)tk < (unsigned)L;
                         if constexpr (ARB) {
                             // the word of this lane's query row that holds keys ktok0 + rb*32 .. +31
                             // (a word wholly past the end of the row is not read)
@@ -864,7 +879,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                     }
             }
             colsum += __shfl_xor(colsum, 32);
-            if (gh == 0 && tk < L && colsum != 0.f) atomicAdd(mass_h + tk, colsum);
+            if (gh == 0 && (unsigned)tk < (unsigned)L && colsum != 0.f) atomicAdd(mass_h + tk, colsum);
         }
     }
     }

@@ -200,3 +200,24 @@ def sample_rows(w, n, seed=0, heads=None):
     while len(rows) < n:
         rows.add((heads[int(rng.integers(len(heads)))], int(rng.integers(NB))))
     return sorted(rows)
+
+
+def kurtosis_gradient(x):
+    """d kurt / d x_i of the excess kurtosis m4 / m2^2 - 3 (biased central moments) of the values
+    x: (4 / n) * ((c_i^3 - m3) / m2^2 - m4 * c_i / m2^3), c = x - mean.  Used to turn the error of
+    the block means into the error their column kurtosis may show (first order)."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.size
+    c = x - x.mean()
+    m2, m3, m4 = np.mean(c * c), np.mean(c ** 3), np.mean(c ** 4)
+    return (4.0 / n) * ((c ** 3 - m3) / (m2 * m2) - m4 * c / (m2 ** 3))
+
+
+def kurtosis_tolerance(x_ref, x_got, kurt_ref):
+    """How far the kurtosis of x_got may lie from that of x_ref given how far the values
+    themselves lie apart: twice the first-order bound sum_i |d kurt / d x_i| * |x_got_i - x_ref_i|
+    (the factor covers the second-order terms while the deviations stay small) plus the rounding of
+    an fp32 result."""
+    g = kurtosis_gradient(x_ref)
+    return 2.0 * float(np.sum(np.abs(g) * np.abs(np.asarray(x_got, np.float64) - np.asarray(x_ref, np.float64)))) + \
+        2e-5 * (1.0 + abs(kurt_ref))

@@ -10,6 +10,7 @@ from paper_2510_19875_amd import binding, workloads as wl
 from tests import parity
 
 pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
 
 TOL = {"bf16": 2e-2, "f32": 1e-4}
 
@@ -161,3 +162,60 @@ def test_strided_inputs_and_output():
     rb = binding.stream_receiver_stats(Qs, Ks, w.heads, w.kv_heads, w.block, scale)
     torch.cuda.synchronize()
     assert torch.equal(ra["col_mean"], rb["col_mean"]) and torch.equal(ra["head"], rb["head"])
+
+
+@pytest.mark.parametrize("kmax,block", [(12, 64), (80, 32)])
+def test_lists_not_ascending_or_out_of_range_never_leak_future_keys(kmax, block):
+    """Lists the pruning never writes: shuffled entries, blocks after the query block, ids past the
+    end of the sequence and below zero.  The kernels then mask every tile at token level: the
+    result is Eq. (2) over the listed blocks' visible keys (the oracle takes a list in any
+    order), ids outside the sequence add nothing, no key after a query ever counts."""
+    w = wl.scaled(wl.config(2), (block * 41 + 7,), topk=4, heads=4, kv_heads=2, block=block, needles_per_kv_head=2)
+    Q, K, V, _ = wl.make_inputs(w)
+    N = w.blocks_per_seq[0]
+    rng = np.random.default_rng(5)
+    idx = np.full((w.heads, N, kmax), -1, dtype=np.int32)
+    cnt = np.zeros((w.heads, N), dtype=np.int32)
+    for h in range(w.heads):
+        for q in range(N):
+            c = int(rng.integers(1, kmax + 1))
+            pool = np.arange(N + 3)                               # incl. future blocks and ids >= N
+            ent = rng.choice(pool, size=min(c, len(pool)), replace=False)
+            kind = (h + q) % 4
+            if kind == 0:
+                ent = np.sort(ent[ent <= q])                      # a list as the pruning writes it
+            elif kind == 1:
+                ent = np.sort(ent)                                # ascending, but with future / outside ids
+            cnt[h, q] = len(ent)                                  # kinds 2, 3: shuffled as drawn
+            idx[h, q, :len(ent)] = ent
+    scale = 1.0 / math.sqrt(w.head_dim)
+    ref = so.sparse_attn(Q.float().numpy(), K.float().numpy(), V.float().numpy(), w.heads, w.kv_heads, block,
+                         idx, cnt, scale)
+    it, ct = torch.from_numpy(idx).to(DEV), torch.from_numpy(cnt).to(DEV)
+    a = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), w.heads, w.kv_heads, block, it, ct, scale,
+                                   want_lse=True, want_mass=True)
+    torch.cuda.synchronize()
+    O, lse, mass = a["O"].float().cpu().numpy(), a["lse"].cpu().numpy(), a["mass"].cpu().numpy()
+    seen = np.isfinite(ref["lse"])                                # queries with at least one visible listed key
+    assert (np.isneginf(lse) == ~seen).all()
+    np.testing.assert_allclose(lse[seen], ref["lse"][seen], atol=1e-3)
+    assert np.abs(O - ref["O"]).max() <= TOL[w.dtype]
+    np.testing.assert_allclose(mass, ref["mass"], rtol=1e-3, atol=1e-5)
+    # ids below zero: the same result as the list without them
+    idx2 = idx.copy()
+    idx2[:, :, 0] = np.where(cnt > 1, -1 - (idx[:, :, 0] % 3), idx[:, :, 0])
+    idx3 = idx.copy()
+    cnt3 = cnt.copy()
+    for h in range(w.heads):
+        for q in range(N):
+            if cnt[h, q] > 1:
+                idx3[h, q, :cnt[h, q] - 1] = idx[h, q, 1:cnt[h, q]]
+                idx3[h, q, cnt[h, q] - 1] = -1
+                cnt3[h, q] -= 1
+    ref3 = so.sparse_attn(Q.float().numpy(), K.float().numpy(), V.float().numpy(), w.heads, w.kv_heads, block,
+                          idx3, cnt3, scale)
+    b = binding.stream_sparse_attn(Q.to(DEV), K.to(DEV), V.to(DEV), w.heads, w.kv_heads, block,
+                                   torch.from_numpy(idx2).to(DEV), ct, scale, want_lse=True, want_mass=True)
+    torch.cuda.synchronize()
+    assert np.abs(b["O"].float().cpu().numpy() - ref3["O"]).max() <= TOL[w.dtype]
+    np.testing.assert_allclose(b["mass"].cpu().numpy(), ref3["mass"], rtol=1e-3, atol=1e-5)

@@ -268,3 +268,27 @@ def test_explicit_array_equals_python_loops_and_the_rules():
         r = rs.receiver_stats(Q[None], K[None], 1, 1, 4, scale, mask=mask, window=window)
         for key in ("block_mean", "col_mean", "col_kurt", "head"):
             np.testing.assert_array_equal(a[key], r[key])
+
+
+def test_kurtosis_gradient_of_the_parity_checker_matches_finite_differences():
+    """tests/parity.py derives the tolerance of a column kurtosis from the error of the block
+    means through the gradient of the moment formula; the gradient is checked here against central
+    differences of the oracle's excess_kurtosis, and the tolerance against actual perturbations."""
+    from tests import parity
+
+    rng = np.random.default_rng(8)
+    for n, spread in ((4, 1.0), (9, 0.01), (40, 1.0), (200, 1e-3)):
+        x = 1.0 + spread * rng.standard_normal(n)
+        x[rng.integers(n)] += 6 * spread                      # a heavy tail, as a receiver block gives
+        g = parity.kurtosis_gradient(x)
+        for i in range(n):
+            h = 1e-6 * spread
+            xp, xm = x.copy(), x.copy()
+            xp[i] += h
+            xm[i] -= h
+            fd = (rs.excess_kurtosis(xp) - rs.excess_kurtosis(xm)) / (2 * h)
+            assert abs(fd - g[i]) <= 1e-5 * (1 + abs(g).max()), (n, i, fd, g[i])
+        k0 = rs.excess_kurtosis(x)
+        for rel in (1e-6, 1e-5, 2e-4):
+            y = x * (1 + rel * rng.uniform(-1, 1, n))
+            assert abs(rs.excess_kurtosis(y) - k0) <= parity.kurtosis_tolerance(x, y, k0)
