@@ -99,11 +99,18 @@ def main():
     ap.add_argument("--levels-per-launch", type=int, default=0,
                     help="refinement levels per kernel launch (0 = library default: all in one)")
     ap.add_argument("--cpu-rows", type=int, default=1536)
+    ap.add_argument("--probes", action="store_true",
+                    help="run only the micro-benchmarks behind the roofline statements (MFMA-only rate, "
+                         "shader clock under matrix load, tile-gather bandwidth) and print them as JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding code); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.probes:
+        print(json.dumps(probes()))
+        return
 
     import numpy as np
     import torch
@@ -284,6 +291,33 @@ def main():
         torch.cuda.synchronize()
         result["cpu_baseline"] = cpu_baseline(w, layers[0], args.cpu_rows, scale, gp, ga)
     print(json.dumps(result))
+
+
+def probes():
+    """Micro-benchmarks of csrc/stream_probe.hip (libstream_probe.so): what the matrix cores and
+    the vector-memory path deliver on their own, for the tile shapes the level kernel uses."""
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2510_19875_amd", "libstream_probe.so"))
+    lib.stream_probe_run.restype = ctypes.c_int
+    lib.stream_probe_run.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int]
+    out = (ctypes.c_double * 18)()
+    rc = lib.stream_probe_run(out, 18)
+    if rc != 0:
+        raise RuntimeError(f"stream_probe_run -> {rc}")
+    v = list(out)
+    res = {"what": "micro-benchmarks: 64x64x128 bf16 tile products on register operands (mfma), shader clock "
+                   "during them (shader-clock counter / 100 MHz counter), random 16 KiB tile gathers (gather)",
+           "mfma": {}, "gather": []}
+    for i, name in enumerate(("2_waves_per_simd_short", "2_waves_per_simd_long", "1_wave_per_simd_short",
+                              "1_wave_per_simd_long")):
+        res["mfma"][name] = {"tflops": v[2 * i], "frac_of_2500": v[2 * i] / PEAK_BF16_MFMA_TFLOPS,
+                             "shader_clock_mhz": v[2 * i + 1]}
+    for i in range(5):
+        tbs, ws = v[8 + 2 * i], v[9 + 2 * i]
+        clk = res["mfma"]["2_waves_per_simd_long"]["shader_clock_mhz"] * 1e6
+        res["gather"].append({"working_set_mib": ws / 2 ** 20, "tb_per_s": tbs,
+                              "bytes_per_clk_per_cu_at_2400mhz": tbs * 1e12 / 256 / 2.4e9,
+                              "bytes_per_clk_per_cu_at_sustained_clock": tbs * 1e12 / 256 / clk if clk else None})
+    return res
 
 
 def list_sharing(idx, cnt, kv_heads):

@@ -105,8 +105,8 @@ __global__ void __launch_bounds__(256, 2) gather_probe(const char *base, unsigne
 
 struct Timer {
     hipEvent_t e0, e1;
-    Timer() { hipEventCreate(&e0); hipEventCreate(&e1); }
-    ~Timer() { hipEventDestroy(e0); hipEventDestroy(e1); }
+    Timer() { (void)hipEventCreate(&e0); (void)hipEventCreate(&e1); }
+    ~Timer() { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); }
 };
 
 template <int OCC>
@@ -119,9 +119,9 @@ int run_mfma(int ntiles, uint4 *in, float *out, long long *clk, double *tflops, 
         if (hipEventRecord(tm.e0) != hipSuccess) return 1;
         hipLaunchKernelGGL(mfma_probe<OCC>, dim3(wgs), dim3(256), 0, 0, in, out, ntiles, clk);
         if (hipGetLastError() != hipSuccess) return 1;
-        hipEventRecord(tm.e1);
+        (void)hipEventRecord(tm.e1);
         if (hipEventSynchronize(tm.e1) != hipSuccess) return 1;
-        hipEventElapsedTime(&ms, tm.e0, tm.e1);
+        (void)hipEventElapsedTime(&ms, tm.e0, tm.e1);
     }
     *tflops = (double)wgs * 4 * ntiles * 32 * 32768.0 / (ms * 1e-3) / 1e12;
     // shader clock = sum of shader clocks / sum of 100 MHz ticks over all wavefronts
@@ -141,7 +141,7 @@ extern "C" {
 
 // out[0..7]: MFMA-only TFLOP/s and shader clock (MHz) for {2 waves/SIMD short run, 2 waves/SIMD long
 // run, 1 wave/SIMD short, 1 wave/SIMD long}; out[8 + 2i], out[9 + 2i]: tile-gather TB/s and bytes
-// per launch for working sets of 2 MiB, 16 MiB, 64 MiB, 192 MiB, 1 GiB.  Allocates its own buffers
+// per launch for working sets of 2 MiB, 16 MiB, 64 MiB, 128 MiB, 1 GiB.  Allocates its own buffers
 // (1 GiB) and synchronises.  Returns 0 on success.
 int stream_probe_run(double *out, int n)
 {
@@ -158,33 +158,33 @@ int stream_probe_run(double *out, int n)
     if (hipMalloc(&clk, sizeof(long long) * 2 * 256 * 8 * 4) != hipSuccess) return 2;
     if (hipMalloc(&big, region) != hipSuccess) return 2;
     if (hipMalloc(&flag, 4) != hipSuccess) return 2;
-    hipMemset(in, 0, 1 << 20);
-    hipMemset(big, 1, region);
+    (void)hipMemset(in, 0, 1 << 20);
+    (void)hipMemset(big, 1, region);
     int rc = 0;
     // ~2 ms and ~60 ms of MFMA-only work
     rc |= run_mfma<2>(256, in, o, clk, &out[0], &out[1]);
     rc |= run_mfma<2>(8192, in, o, clk, &out[2], &out[3]);
     rc |= run_mfma<1>(512, in, o, clk, &out[4], &out[5]);
     rc |= run_mfma<1>(16384, in, o, clk, &out[6], &out[7]);
-    const unsigned masks[5] = {127u, 1023u, 4095u, 12287u, 65535u};   // tiles of 16 KiB (12287: sampled below 192 MiB by the mask 16383 and a fold)
+    const unsigned masks[5] = {127u, 1023u, 4095u, 8191u, 65535u};   // working sets in tiles of 16 KiB, minus one
     Timer tm;
     for (int i = 0; i < 5 && rc == 0; ++i) {
         const int wgs = 256 * 2 * 8, ntw = 256;
-        const unsigned m = masks[i] == 12287u ? 8191u : masks[i];      // powers of two only: 192 MiB is probed as 128 MiB
+        const unsigned m = masks[i];
         float ms = 0.f;
         for (int rep = 0; rep < 2; ++rep) {
-            hipEventRecord(tm.e0);
+            (void)hipEventRecord(tm.e0);
             hipLaunchKernelGGL(gather_probe, dim3(wgs), dim3(256), 0, 0, big, (unsigned)region, ntw, m, flag);
             if (hipGetLastError() != hipSuccess) rc = 3;
-            hipEventRecord(tm.e1);
+            (void)hipEventRecord(tm.e1);
             if (hipEventSynchronize(tm.e1) != hipSuccess) rc = 3;
-            hipEventElapsedTime(&ms, tm.e0, tm.e1);
+            (void)hipEventElapsedTime(&ms, tm.e0, tm.e1);
         }
         const double bytes = (double)wgs * 4 * ntw * 16384.0;
         out[8 + 2 * i] = bytes / (ms * 1e-3) / 1e12;
         out[9 + 2 * i] = (double)(m + 1) * 16384.0;
     }
-    hipFree(in); hipFree(o); hipFree(clk); hipFree(big); hipFree(flag);
+    (void)hipFree(in); (void)hipFree(o); (void)hipFree(clk); (void)hipFree(big); (void)hipFree(flag);
     return rc;
 }
 
