@@ -2,8 +2,8 @@
 // library: built as libstream_probe.so and called by `bench.py --probes`).
 //
 //   mfma    the level kernel's tile product alone: 32 x (32x32x16 bf16 MFMA) per 64 x 64 x 128 tile
-//           on register-resident operands, one or two wavefronts per SIMD, for a short and a long
-//           run (the part lowers its clock under sustained matrix load);
+//           on register-resident operands holding random values, one or two wavefronts per SIMD,
+//           for a short and a long run (the part lowers its clock under sustained matrix load);
 //   clock   the shader clock during that long run: shader-clock counter against the constant
 //           100 MHz real-time counter, read inside the kernel;
 //   gather  the level kernel's K-tile fetch alone: 16 KiB tiles read as sixteen 1 KiB wave-wide
@@ -141,11 +141,12 @@ extern "C" {
 
 // out[0..7]: MFMA-only TFLOP/s and shader clock (MHz) for {2 waves/SIMD short run, 2 waves/SIMD long
 // run, 1 wave/SIMD short, 1 wave/SIMD long}; out[8 + 2i], out[9 + 2i]: tile-gather TB/s and bytes
-// per launch for working sets of 2 MiB, 16 MiB, 64 MiB, 128 MiB, 1 GiB.  Allocates its own buffers
+// per launch for working sets of 2 MiB, 16 MiB, 64 MiB, 128 MiB, 1 GiB; out[18], out[19]: the long
+// 2 waves/SIMD MFMA run again with all-zero operands.  Allocates its own buffers
 // (1 GiB) and synchronises.  Returns 0 on success.
 int stream_probe_run(double *out, int n)
 {
-    if (!out || n < 18) return 1;
+    if (!out || n < 20) return 1;
     memset(out, 0, sizeof(double) * n);
     uint4 *in = nullptr;
     float *o = nullptr;
@@ -158,7 +159,21 @@ int stream_probe_run(double *out, int n)
     if (hipMalloc(&clk, sizeof(long long) * 2 * 256 * 8 * 4) != hipSuccess) return 2;
     if (hipMalloc(&big, region) != hipSuccess) return 2;
     if (hipMalloc(&flag, 4) != hipSuccess) return 2;
-    (void)hipMemset(in, 0, 1 << 20);
+    // operands: random bf16 values of both signs with magnitudes between 2^-7 and 2 (the power an
+    // MFMA draws, and with it the clock the part sustains, depends on the data: zeros are cheap)
+    {
+        const size_t n16 = (1 << 20) / 2;
+        unsigned short *h = new unsigned short[n16];
+        unsigned long long st = 0x9E3779B97F4A7C15ull;
+        for (size_t i = 0; i < n16; ++i) {
+            st = st * 6364136223846793005ull + 1442695040888963407ull;
+            const unsigned r = (unsigned)(st >> 33);
+            h[i] = (unsigned short)(((r & 1u) << 15) | ((120u + ((r >> 1) & 7u)) << 7) | ((r >> 4) & 0x7fu));
+        }
+        const hipError_t e = hipMemcpy(in, h, n16 * 2, hipMemcpyHostToDevice);
+        delete[] h;
+        if (e != hipSuccess) return 2;
+    }
     (void)hipMemset(big, 1, region);
     int rc = 0;
     // ~2 ms and ~60 ms of MFMA-only work
@@ -166,6 +181,9 @@ int stream_probe_run(double *out, int n)
     rc |= run_mfma<2>(8192, in, o, clk, &out[2], &out[3]);
     rc |= run_mfma<1>(512, in, o, clk, &out[4], &out[5]);
     rc |= run_mfma<1>(16384, in, o, clk, &out[6], &out[7]);
+    // the same long run on all-zero operands: multipliers that do not toggle draw far less power
+    if (hipMemset(in, 0, 1 << 20) != hipSuccess) return 2;
+    rc |= run_mfma<2>(8192, in, o, clk, &out[18], &out[19]);
     const unsigned masks[5] = {127u, 1023u, 4095u, 8191u, 65535u};   // working sets in tiles of 16 KiB, minus one
     Timer tm;
     for (int i = 0; i < 5 && rc == 0; ++i) {
