@@ -280,6 +280,11 @@ def main():
             result["mask_array"] = mask_array(w, layers[0], scale)
     if args.dense_reference and w.batch == 1:
         result["dense_reference"] = dense_reference(w, layers[0])
+    try:
+        # what the matrix cores and the memory path deliver on their own on this very box
+        result["probes"] = probes()
+    except (OSError, RuntimeError) as e:
+        result["probes"] = {"error": str(e)}
     if not args.no_cpu_baseline:
         # the step's own outputs for layer 0, taken again after the timed region (with the per-level
         # trace a differing row is certified from), for the row-by-row comparison with the oracle

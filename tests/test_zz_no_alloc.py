@@ -78,3 +78,37 @@ def test_sizes_beyond_the_scratch_are_refused_before_any_launch():
     rc = lib.stream_prune_static(fake, fake, ctypes.byref(s), 32, None, 32, fake, fake, None, None, None)
     assert rc == binding.STREAM_EWORKSPACE
     assert lib.stream_prune_static(None, fake, ctypes.byref(s), 32, None, 32, fake, fake, None, None, None) == binding.STREAM_EINVAL
+
+
+def test_under_graph_capture():
+    """What the entry point is for: recorded into a HIP graph (after one call outside the capture,
+    which looks up the scratch on this device) and replayed with new inputs written into the
+    captured buffers and eager work in between; every replay equals stream_prune run eagerly."""
+    w = wl.scaled(wl.config(2), (64 * 50 + 9,), topk=8, heads=8, kv_heads=2, needles_per_kv_head=2)
+    inputs = [wl.make_inputs(w.with_layer(l), with_v=False) for l in range(3)]
+    Qs, Ks = (torch.empty_like(t, device=DEV) for t in inputs[0][:2])
+    eager = []
+    for (Q, K, _, _) in inputs:
+        r = binding.stream_prune(Q.to(DEV), K.to(DEV), w.heads, w.kv_heads, w.block, w.topk[0], want_score=True)
+        torch.cuda.synchronize()
+        eager.append({k: r[k].clone() for k in ("idx", "cnt", "score")})
+    out = {k: torch.empty_like(v) for k, v in eager[0].items()}
+    Qs.copy_(inputs[0][0]); Ks.copy_(inputs[0][1])
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        binding.stream_prune_static(Qs, Ks, w.heads, w.kv_heads, w.block, w.topk[0], out)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.stream_prune_static(Qs, Ks, w.heads, w.kv_heads, w.block, w.topk[0], out)
+    for rep in range(5):
+        l = rep % 3
+        Qs.copy_(inputs[l][0]); Ks.copy_(inputs[l][1])         # eager work between replays
+        g.replay()
+        torch.cuda.synchronize()
+        for key in ("idx", "cnt", "score"):
+            assert torch.equal(out[key], eager[l][key]), (rep, key)
+        out["idx"].fill_(-7)
+        out["cnt"].fill_(-7)
