@@ -304,8 +304,8 @@ def probes():
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_2510_19875_amd", "libstream_probe.so"))
     lib.stream_probe_run.restype = ctypes.c_int
     lib.stream_probe_run.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int]
-    out = (ctypes.c_double * 20)()
-    rc = lib.stream_probe_run(out, 20)
+    out = (ctypes.c_double * 22)()
+    rc = lib.stream_probe_run(out, 22)
     if rc != 0:
         raise RuntimeError(f"stream_probe_run -> {rc}")
     v = list(out)
@@ -318,6 +318,8 @@ def probes():
                              "shader_clock_mhz": v[2 * i + 1]}
     res["mfma"]["2_waves_per_simd_long_zero_operands"] = {"tflops": v[18], "frac_of_2500": v[18] / PEAK_BF16_MFMA_TFLOPS,
                                                           "shader_clock_mhz": v[19]}
+    res["mfma"]["2_waves_per_simd_long_16x16x32_shape"] = {"tflops": v[20], "frac_of_2500": v[20] / PEAK_BF16_MFMA_TFLOPS,
+                                                           "shader_clock_mhz": v[21]}
     for i in range(5):
         tbs, ws = v[8 + 2 * i], v[9 + 2 * i]
         clk = res["mfma"]["2_waves_per_simd_long"]["shader_clock_mhz"] * 1e6

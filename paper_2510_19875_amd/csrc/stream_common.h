@@ -167,7 +167,11 @@ size_t align_up(size_t x, size_t a);
 int block_bitmap_words(const Problem &pb);
 stream_status launch_block_bitmaps(const Problem &pb, unsigned *any_bits, unsigned *all_bits, hipStream_t st);
 
+// Fragment shape of the packed copy: kPackFrag32 - a fragment is 32 rows x 32 bytes (operands of the
+// 32x32 MFMAs), kPackFrag16 - 16 rows x 64 bytes (operands of the 16x16x32 bf16 MFMA).
+enum PackLayout { kPackFrag32 = 0, kPackFrag16 = 1 };
+
 stream_status launch_pack(const void *src, long long stride_h, long long stride_t, void *dst,
-                          const Problem &pb, hipStream_t st);
+                          const Problem &pb, hipStream_t st, PackLayout layout = kPackFrag32);
 
 }  // namespace stream

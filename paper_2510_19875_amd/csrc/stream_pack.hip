@@ -102,6 +102,11 @@ stream_status make_problem(const stream_shape *s, int topk, const int *topk_per_
 // A block of b tokens is b/32 consecutive groups; tokens past the end of a sequence are zero
 // (they are masked out wherever they could matter).  Layout: [kv_head][global block][b * d].
 // The permutation is per 32-token group, so the same packed tensor serves every block size.
+// With kPackFrag16 (operands of the 16x16x32 bf16 MFMA: lane (g = lane / 16, n = lane % 16) supplies
+// row n and the g-th 16-byte chunk of the fragment's 64-byte slice) the group is cut into
+// fragments of 16 rows x 64 bytes instead:
+//
+//     dst chunk ((n / 16 * (row_bytes / 64) + cc / 4) * 64 + (cc % 4) * 16 + n % 16)  <-  src row n, chunk cc
 // ---------------------------------------------------------------------------------------------
 struct PackParams {
     const char *src;
@@ -109,6 +114,7 @@ struct PackParams {
     long long stride_h_bytes, stride_t_bytes;
     int row_bytes;   // d * esize
     int b, NB, Hkv;
+    int frag16;      // kPackFrag16 layout
     SeqTable seqs;
 };
 
@@ -134,14 +140,21 @@ __global__ void __launch_bounds__(256) pack_kernel(PackParams p)
         if (tok < sd.len)
             v = *reinterpret_cast<const uint4 *>(p.src + kvh * p.stride_h_bytes +
                                                  (sd.tok0 + tok) * p.stride_t_bytes + cc * 16);
-        *reinterpret_cast<uint4 *>(dst + ((fr * 64 + g * 32 + n) * 16)) = v;
+        int chunk = fr * 64 + g * 32 + n;
+        if (p.frag16) {
+            // fragment (16-row group n / 16, 64-byte slice cc / 4), lane (chunk cc % 4 of the slice, row n % 16)
+            const int kf = cpr >> 2;
+            chunk = ((n >> 4) * kf + (cc >> 2)) * 64 + (cc & 3) * 16 + (n & 15);
+        }
+        *reinterpret_cast<uint4 *>(dst + chunk * 16) = v;
     }
 }
 
 stream_status launch_pack(const void *src, long long stride_h, long long stride_t, void *dst,
-                          const Problem &pb, hipStream_t st)
+                          const Problem &pb, hipStream_t st, PackLayout layout)
 {
     PackParams p;
+    p.frag16 = layout == kPackFrag16 ? 1 : 0;
     p.src = (const char *)src;
     p.dst = (char *)dst;
     p.stride_h_bytes = stride_h * pb.esize;

@@ -68,6 +68,57 @@ __global__ void __launch_bounds__(256, OCC) mfma_probe(const uint4 *in, float *o
     }
 }
 
+// The same tile product from 16x16x32 MFMAs (64 per tile): does the smaller shape draw less power?
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256, 2) mfma16_probe(const uint4 *in, float *out, int ntiles, long long *clk)
+{
+    const int lane = threadIdx.x & 63;
+    uint4 q[4][4], kf[4][4];     // [16-row group][32-wide slice of the contraction axis]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            q[i][j] = in[lane + 64 * (i * 4 + j)];
+            kf[i][j] = in[lane + 64 * (16 + i * 4 + j)];
+        }
+    const long long c0 = (long long)__builtin_amdgcn_s_memtime();
+    const long long r0 = (long long)__builtin_amdgcn_s_memrealtime();
+    float res = 0.f;
+    for (int t = 0; t < ntiles; ++t) {
+        floatx4 acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[a][b][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, q[rb][ks]),
+                                                                          __builtin_bit_cast(bf16x8, kf[cb][ks]),
+                                                                          acc[rb][cb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) res += acc[a][b][(a + b) & 3];   // every product is used
+        kf[0][0].x += 1;
+    }
+    const long long c1 = (long long)__builtin_amdgcn_s_memtime();
+    const long long r1 = (long long)__builtin_amdgcn_s_memrealtime();
+    out[blockIdx.x * 256 + threadIdx.x] = res;
+    if (lane == 0) {
+        const long long w = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+        clk[2 * w] = c1 - c0;
+        clk[2 * w + 1] = r1 - r0;
+    }
+}
+
 // One wavefront reads `ntiles` tiles of 16 KiB (sixteen loads of 1 KiB in flight, refilled in
 // place as the level kernel does) from pseudo-random tile positions below `tile_mask`.
 __global__ void __launch_bounds__(256, 2) gather_probe(const char *base, unsigned region_bytes, int ntiles,
@@ -109,7 +160,7 @@ struct Timer {
     ~Timer() { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); }
 };
 
-template <int OCC>
+template <int OCC, bool SMALL = false>
 int run_mfma(int ntiles, uint4 *in, float *out, long long *clk, double *tflops, double *mhz)
 {
     const int wgs = 256 * OCC * 4;
@@ -117,7 +168,8 @@ int run_mfma(int ntiles, uint4 *in, float *out, long long *clk, double *tflops, 
     float ms = 0.f;
     for (int rep = 0; rep < 2; ++rep) {
         if (hipEventRecord(tm.e0) != hipSuccess) return 1;
-        hipLaunchKernelGGL(mfma_probe<OCC>, dim3(wgs), dim3(256), 0, 0, in, out, ntiles, clk);
+        if constexpr (SMALL) hipLaunchKernelGGL(mfma16_probe, dim3(wgs), dim3(256), 0, 0, in, out, ntiles, clk);
+        else hipLaunchKernelGGL(mfma_probe<OCC>, dim3(wgs), dim3(256), 0, 0, in, out, ntiles, clk);
         if (hipGetLastError() != hipSuccess) return 1;
         (void)hipEventRecord(tm.e1);
         if (hipEventSynchronize(tm.e1) != hipSuccess) return 1;
@@ -142,7 +194,8 @@ extern "C" {
 // out[0..7]: MFMA-only TFLOP/s and shader clock (MHz) for {2 waves/SIMD short run, 2 waves/SIMD long
 // run, 1 wave/SIMD short, 1 wave/SIMD long}; out[8 + 2i], out[9 + 2i]: tile-gather TB/s and bytes
 // per launch for working sets of 2 MiB, 16 MiB, 64 MiB, 128 MiB, 1 GiB; out[18], out[19]: the long
-// 2 waves/SIMD MFMA run again with all-zero operands.  Allocates its own buffers
+// 2 waves/SIMD MFMA run again with all-zero operands; out[20], out[21] (if n >= 22): the long run built from
+// 16x16x32 MFMAs on random operands.  Allocates its own buffers
 // (1 GiB) and synchronises.  Returns 0 on success.
 int stream_probe_run(double *out, int n)
 {
@@ -181,6 +234,7 @@ int stream_probe_run(double *out, int n)
     rc |= run_mfma<2>(8192, in, o, clk, &out[2], &out[3]);
     rc |= run_mfma<1>(512, in, o, clk, &out[4], &out[5]);
     rc |= run_mfma<1>(16384, in, o, clk, &out[6], &out[7]);
+    if (n >= 22) rc |= run_mfma<2, true>(8192, in, o, clk, &out[20], &out[21]);   // 16x16x32 MFMAs, random operands
     // the same long run on all-zero operands: multipliers that do not toggle draw far less power
     if (hipMemset(in, 0, 1 << 20) != hipSuccess) return 2;
     rc |= run_mfma<2>(8192, in, o, clk, &out[18], &out[19]);

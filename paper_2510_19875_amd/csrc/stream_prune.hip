@@ -29,6 +29,19 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int FR = D * ES / 32;                       // fragments per 32-token group
+    // bf16 tiles are multiplied with 16x16x32 MFMAs (S16): under the power limit that governs a
+    // kernel made of back-to-back MFMAs this shape sustains ~10 % more FLOP/s than 32x32x16 on
+    // the same data.  An operand fragment (64 lanes x 16 bytes) then covers 16 rows x 32
+    // contraction indices instead of 32 x 16: lane l supplies row l % 16, 16-byte chunk l / 16 of
+    // the fragment's 64-byte slice of the row.  fp32 keeps 32x32x2.
+    constexpr bool S16 = BF16;
+    constexpr int RG = S16 ? 2 * MB : MB;                 // row groups of the Q tile (16 or 32 rows each)
+    constexpr int CG = S16 ? 2 * NG : NG;                 // key groups of the K tile
+    constexpr int KF = S16 ? D / 32 : FR;                 // fragments of a group along the contraction axis
+    constexpr int GR = S16 ? 16 : 32;                     // rows / keys per group
+    constexpr int AE = S16 ? 4 : 16;                      // accumulator elements per lane and group pair
+    typedef float acc_t __attribute__((ext_vector_type(AE)));
+    static_assert(RG * KF == MB * FR && CG * KF == NG * FR, "same number of fragments either way");
     constexpr int BQ = 32 * MB * (WPR == 4 ? 2 : 1);      // query block b_q
     constexpr int BK = 32 * NG * (WPR == 4 ? 2 : 1);      // key block b_k
     constexpr long long TILE_BYTES = (long long)BK * D * ES;
@@ -72,9 +85,8 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     //      holds, for fragment fr, the 16 bytes at chunk 2*fr + gh of row mrow.  Issued first so
     //      that the loads overlap the node-state loads below; rows past the end of the sequence
     //      fall outside the buffer resource and read as zeros.
-    uint4 qf[MB][FR];
+    uint4 qf[RG][KF];
     {
-        const int mrow = lane & 31, gh = lane >> 5;
         // the resource starts at this wavefront's first query row (64-bit arithmetic) and spans
         // its real rows only, so per-lane offsets stay below 128 token strides whatever the
         // length of the sequence and the layout of Q
@@ -83,12 +95,16 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         const __amdgpu_buffer_rsrc_t qrs = make_tile_rsrc(
             p.Q + (long long)h * p.q_sh_b + (sd.tok0 + qrow0) * p.q_st_b,
             qrows > 0 ? (unsigned)((long long)(qrows - 1) * p.q_st_b + D * ES) : 0u);
+        // S16: lane (row l % 16, chunk l / 16 of the 64-byte slice); else (row l % 32, chunk l / 32
+        // of the 32-byte slice)
+        const int mrow = S16 ? (lane & 15) : (lane & 31), gh = S16 ? (lane >> 4) : (lane >> 5);
+        constexpr int SLICE = S16 ? 64 : 32;
 #pragma unroll
-        for (int rb = 0; rb < MB; ++rb) {
-            const unsigned voff = (unsigned)(rb * 32 + mrow) * (unsigned)p.q_st_b + gh * 16;
+        for (int rb = 0; rb < RG; ++rb) {
+            const unsigned voff = (unsigned)(rb * GR + mrow) * (unsigned)p.q_st_b + gh * 16;
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr) {
-                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * 32, 0, 0);
+            for (int fr = 0; fr < KF; ++fr) {
+                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * SLICE, 0, 0);
                 qf[rb][fr] = make_uint4(v[0], v[1], v[2], v[3]);
             }
         }
@@ -211,15 +227,15 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         if (need1) s_rep[wave][pos1] = rep1;
         wave_sync();
 
-        uint4 kf[NG][FR];
+        uint4 kf[CG][KF];
         if (nt > 0) {
             const int r0 = __builtin_amdgcn_readfirstlane(s_rep[wave][0]);
             // same order as the refills in the loop below: waits count loads in issue order
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr)
+            for (int fr = 0; fr < KF; ++fr)
 #pragma unroll
-                for (int cb = 0; cb < NG; ++cb) {
-                    kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * FR + fr);
+                for (int cb = 0; cb < CG; ++cb) {
+                    kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * KF + fr);
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
@@ -227,25 +243,31 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             const int r = __builtin_amdgcn_readfirstlane(s_rep[wave][t]);
             const int tn = t + 1 < nt ? t + 1 : t;
             const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[wave][tn]) * (unsigned)TILE_BYTES;
-            floatx16 acc[MB][NG];
+            acc_t acc[RG][CG];
 #pragma unroll
-            for (int rb = 0; rb < MB; ++rb)
+            for (int rb = 0; rb < RG; ++rb)
 #pragma unroll
-                for (int cb = 0; cb < NG; ++cb)
+                for (int cb = 0; cb < CG; ++cb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+                    for (int i = 0; i < AE; ++i) acc[rb][cb][i] = 0.f;
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr) {
+            for (int fr = 0; fr < KF; ++fr) {
 #pragma unroll
-                for (int cb = 0; cb < NG; ++cb) {
+                for (int cb = 0; cb < CG; ++cb) {
 #pragma unroll
-                    for (int rb = 0; rb < MB; ++rb)
-                        acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
+                    for (int rb = 0; rb < RG; ++rb) {
+                        if constexpr (S16)
+                            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8, qf[rb][fr]), __builtin_bit_cast(bf16x8, kf[cb][fr]),
+                                acc[rb][cb], 0, 0, 0);
+                        else
+                            acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
+                    }
                     // the fragment is consumed: refill its registers from the next tile right here,
                     // so that every fragment of the next tile has a whole tile of MFMA time to arrive
                     // (the scheduling barriers stop the compiler from sinking the loads to the end)
                     __builtin_amdgcn_sched_barrier(0);
-                    kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * FR + fr);
+                    kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * KF + fr);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -256,16 +278,15 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             if constexpr (ARB) cut = !((allrow[r >> 5] >> (r & 31)) & 1u);
             if (!cut) {
 #pragma unroll
-                for (int rb = 0; rb < MB; ++rb)
+                for (int rb = 0; rb < RG; ++rb)
 #pragma unroll
-                    for (int cb = 0; cb < NG; ++cb)
+                    for (int cb = 0; cb < CG; ++cb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
+                        for (int i = 0; i < AE; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
             } else {
                 // a block the mask cuts through (diagonal, window edge) or with padded rows/cols:
-                // token-level test.
-                // 32x32 accumulator layout: lane holds column (lane % 32); element i is row
-                // 8*(i/4) + 4*(lane/32) + (i%4).
+                // token-level test.  Accumulator layouts: 32x32 - lane holds column lane % 32, element
+                // i is row 8*(i/4) + 4*(lane/32) + (i%4); 16x16 - column lane % 16, row 4*(lane/16) + i.
                 const int ktok0 = r * BK + kh * 32 * NG;
                 // ARB: lane j fetches the mask words of query row j (and j + 64) of this tile, one per
                 // 32-key group; an element then takes its row's word from the lane that fetched it
@@ -283,18 +304,21 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                     }
                 }
 #pragma unroll
-                for (int rb = 0; rb < MB; ++rb)
+                for (int rb = 0; rb < RG; ++rb)
 #pragma unroll
-                    for (int cb = 0; cb < NG; ++cb)
+                    for (int cb = 0; cb < CG; ++cb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                            const int tk = ktok0 + cb * 32 + (lane & 31);
+                        for (int i = 0; i < AE; ++i) {
+                            // row of the wavefront's Q tile and key of its K tile this element belongs to
+                            const int qr = S16 ? rb * 16 + (lane >> 4) * 4 + i
+                                               : rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                            const int kc = S16 ? cb * 16 + (lane & 15) : cb * 32 + (lane & 31);
+                            const int tq = qtok0 + qr;
+                            const int tk = ktok0 + kc;
                             bool visible = (tq < L) & (tk < L);
                             if constexpr (ARB) {
-                                const int src = (rb & 1) * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                                const unsigned cwd = (unsigned)__shfl((int)rowword[rb >> 1][cb], src);
-                                visible = visible & ((cwd >> (lane & 31)) & 1u);
+                                const unsigned cwd = (unsigned)__shfl((int)rowword[qr >> 6][kc >> 5], qr & 63);
+                                visible = visible & ((cwd >> (kc & 31)) & 1u);
                             } else {
                                 visible = visible & mask_token(p.mask, p.window, tq, tk);
                             }
@@ -520,7 +544,9 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     hipStream_t st = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
 
-    stream_status rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st);
+    // the narrow kernel multiplies bf16 tiles with 16x16x32 MFMAs and reads K fragments of 16 keys
+    stream_status rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st,
+                                   !wide && pb.dtype == STREAM_BF16 ? kPackFrag16 : kPackFrag32);
     if (rc != STREAM_OK) return rc;
     if (pb.mask == STREAM_MASK_ARRAY) {
         rc = launch_block_bitmaps(pb, (unsigned *)(ws + w.cany), (unsigned *)(ws + w.call), st);
