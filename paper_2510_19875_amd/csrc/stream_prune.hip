@@ -544,9 +544,9 @@ static stream_status run_prune(const void *Q, const void *K, const stream_shape 
     hipStream_t st = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
 
-    // the narrow kernel multiplies bf16 tiles with 16x16x32 MFMAs and reads K fragments of 16 keys
+    // the refinement kernels multiply bf16 tiles with 16x16x32 MFMAs and read K fragments of 16 keys
     stream_status rc = launch_pack(K, k_sh, k_st, ws + w.kp, pb, st,
-                                   !wide && pb.dtype == STREAM_BF16 ? kPackFrag16 : kPackFrag32);
+                                   pb.dtype == STREAM_BF16 ? kPackFrag16 : kPackFrag32);
     if (rc != STREAM_OK) return rc;
     if (pb.mask == STREAM_MASK_ARRAY) {
         rc = launch_block_bitmaps(pb, (unsigned *)(ws + w.cany), (unsigned *)(ws + w.call), st);

@@ -34,6 +34,14 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
     constexpr int FR = D * ES / 32;
     constexpr int BQ = 32 * MB, BK = 32 * NG * KH;
     constexpr long long TILE_BYTES = (long long)BK * D * ES;
+    // bf16: 16x16x32 MFMAs on fragments of 16 rows x 64 bytes, as in the narrow kernel
+    constexpr bool S16 = BF16;
+    constexpr int RG = S16 ? 2 * MB : MB;                 // row groups of the Q tile (16 or 32 rows each)
+    constexpr int CG = S16 ? 2 * NG : NG;                 // key groups of a piece of the K tile
+    constexpr int KF = S16 ? D / 32 : FR;                 // fragments of a group along the contraction axis
+    constexpr int GR = S16 ? 16 : 32;
+    constexpr int AE = S16 ? 4 : 16;
+    typedef float acc_t __attribute__((ext_vector_type(AE)));
     extern __shared__ __align__(16) int smem[];
 
     const int lane = threadIdx.x & 63;
@@ -86,9 +94,10 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
     int *s_brep = base + 12 * KM;                         // [2 KM] per branch position: representative
 
     // ---- Q tile of this row as A-operand fragments (as in the narrow kernel)
-    uint4 qf[MB][FR];
+    uint4 qf[RG][KF];
     {
-        const int mrow = lane & 31, gh = lane >> 5;
+        const int mrow = S16 ? (lane & 15) : (lane & 31), gh = S16 ? (lane >> 4) : (lane >> 5);
+        constexpr int SLICE = S16 ? 64 : 32;
         // (resource from the row's first query on, 64-bit base: see the narrow kernel)
         const int qrow0 = q * BQ;
         const int qrows = L - qrow0 < 32 * MB ? L - qrow0 : 32 * MB;
@@ -96,11 +105,11 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
             p.Q + (long long)h * p.q_sh_b + (sd.tok0 + qrow0) * p.q_st_b,
             qrows > 0 ? (unsigned)((long long)(qrows - 1) * p.q_st_b + D * ES) : 0u);
 #pragma unroll
-        for (int rb = 0; rb < MB; ++rb) {
-            const unsigned voff = (unsigned)(rb * 32 + mrow) * (unsigned)p.q_st_b + gh * 16;
+        for (int rb = 0; rb < RG; ++rb) {
+            const unsigned voff = (unsigned)(rb * GR + mrow) * (unsigned)p.q_st_b + gh * 16;
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr) {
-                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * 32, 0, 0);
+            for (int fr = 0; fr < KF; ++fr) {
+                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * SLICE, 0, 0);
                 qf[rb][fr] = make_uint4(v[0], v[1], v[2], v[3]);
             }
         }
@@ -176,14 +185,14 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
         wave_sync();
 
         // ---- score the listed blocks (the narrow kernel's tile loop)
-        uint4 kf[NG][FR];
+        uint4 kf[CG][KF];
         if (nt > 0) {
             const int r0 = __builtin_amdgcn_readfirstlane(s_rep[0]);
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr)
+            for (int fr = 0; fr < KF; ++fr)
 #pragma unroll
-                for (int cb = 0; cb < NG; ++cb) {
-                    kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * FR + fr);
+                for (int cb = 0; cb < CG; ++cb) {
+                    kf[cb][fr] = load_frag(krs, lane_off, (unsigned)r0 * (unsigned)TILE_BYTES, cb * KF + fr);
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
@@ -194,22 +203,28 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
             const int un = u + 1 < nt * KH ? u + 1 : u;
             const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[un / KH]) * (unsigned)TILE_BYTES;
             const int nxt_frag = (un % KH) * NG * FR;
-            floatx16 acc[MB][NG];
+            acc_t acc[RG][CG];
 #pragma unroll
-            for (int rb = 0; rb < MB; ++rb)
+            for (int rb = 0; rb < RG; ++rb)
 #pragma unroll
-                for (int cb = 0; cb < NG; ++cb)
+                for (int cb = 0; cb < CG; ++cb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+                    for (int i = 0; i < AE; ++i) acc[rb][cb][i] = 0.f;
 #pragma unroll
-            for (int fr = 0; fr < FR; ++fr) {
+            for (int fr = 0; fr < KF; ++fr) {
 #pragma unroll
-                for (int cb = 0; cb < NG; ++cb) {
+                for (int cb = 0; cb < CG; ++cb) {
 #pragma unroll
-                    for (int rb = 0; rb < MB; ++rb)
-                        acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
+                    for (int rb = 0; rb < RG; ++rb) {
+                        if constexpr (S16)
+                            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8, qf[rb][fr]), __builtin_bit_cast(bf16x8, kf[cb][fr]),
+                                acc[rb][cb], 0, 0, 0);
+                        else
+                            acc[rb][cb] = mfma_frag<BF16>(qf[rb][fr], kf[cb][fr], acc[rb][cb]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
-                    kf[cb][fr] = load_frag(krs, lane_off, nxt, nxt_frag + cb * FR + fr);
+                    kf[cb][fr] = load_frag(krs, lane_off, nxt, nxt_frag + cb * KF + fr);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -219,11 +234,11 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
             if constexpr (ARB) cut = !((allrow[r >> 5] >> (r & 31)) & 1u);
             if (!cut) {
 #pragma unroll
-                for (int rb = 0; rb < MB; ++rb)
+                for (int rb = 0; rb < RG; ++rb)
 #pragma unroll
-                    for (int cb = 0; cb < NG; ++cb)
+                    for (int cb = 0; cb < CG; ++cb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
+                        for (int i = 0; i < AE; ++i) mx = fmaxf(mx, acc[rb][cb][i]);
             } else {
                 const int ktok0 = r * BK + piece * 32 * NG;
                 // ARB: lane j fetches the mask words of query row j (and j + 64) of this tile, one per
@@ -242,18 +257,21 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
                     }
                 }
 #pragma unroll
-                for (int rb = 0; rb < MB; ++rb)
+                for (int rb = 0; rb < RG; ++rb)
 #pragma unroll
-                    for (int cb = 0; cb < NG; ++cb)
+                    for (int cb = 0; cb < CG; ++cb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int tq = qtok0 + rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                            const int tk = ktok0 + cb * 32 + (lane & 31);
+                        for (int i = 0; i < AE; ++i) {
+                            // row of the Q tile and key of the piece this accumulator element belongs to
+                            const int qr = S16 ? rb * 16 + (lane >> 4) * 4 + i
+                                               : rb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+                            const int kc = S16 ? cb * 16 + (lane & 15) : cb * 32 + (lane & 31);
+                            const int tq = qtok0 + qr;
+                            const int tk = ktok0 + kc;
                             bool visible = (tq < L) & (tk < L);
                             if constexpr (ARB) {
-                                const int src = (rb & 1) * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-                                const unsigned cwd = (unsigned)__shfl((int)rowword[rb >> 1][cb], src);
-                                visible = visible & ((cwd >> (lane & 31)) & 1u);
+                                const unsigned cwd = (unsigned)__shfl((int)rowword[qr >> 6][kc >> 5], qr & 63);
+                                visible = visible & ((cwd >> (kc & 31)) & 1u);
                             } else {
                                 visible = visible & mask_token(p.mask, p.window, tq, tk);
                             }
