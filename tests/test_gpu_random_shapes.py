@@ -47,7 +47,8 @@ def draw_wide(seed):
     return dtype, d, bq, bk, kv, min(g, 2), lens, mask, window, ks
 
 
-@pytest.mark.parametrize("seed", [("narrow", s) for s in range(28)] + [("wide", s) for s in range(10)],
+@pytest.mark.parametrize("seed", [("narrow", s) for s in range(28)] + [("wide", s) for s in range(10)] +
+                         [("narrow", s) for s in range(600, 680)] + [("wide", s) for s in range(500, 520)],
                          ids=lambda x: f"{x[0]}{x[1]}")
 def test_random_configuration(seed):
     cfg = draw(seed[1]) if seed[0] == "narrow" else draw_wide(seed[1])
