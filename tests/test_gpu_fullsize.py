@@ -130,6 +130,11 @@ def test_config3_attention_and_prune_sampled():
     check_full(wl.config(3), heads_sampled=[2, 17, 30], n_rows=520, seed=11)
 
 
+def test_config3_another_seeded_layer_sampled():
+    """Config 3 is 32 independently seeded layers: one more of them (layer 17) against the oracle."""
+    check_full(wl.config(3).with_layer(17), heads_sampled=[0, 11, 23], n_rows=320, seed=21, check_sink=False)
+
+
 def test_config3_sliding_window_sampled():
     """The headline shape under a sliding window of 4096 tokens (65 valid key blocks per row,
     32 kept): the local layers of the Gemma 3 models the paper traces."""
