@@ -17,7 +17,9 @@
  * and what the paper builds around them: stream_prune_multi (the sweep over k of the tracing
  * driver), stream_prune_variable (a sparsity constant per row), stream_select_update (the
  * selection step alone), stream_mask_diff (difference of two estimated masks),
- * stream_receiver_stats (block means of the dense pattern and their vertical kurtosis).
+ * stream_receiver_stats (block means of the dense pattern and their vertical kurtosis), and
+ * stream_prune_static (stream_prune with the scratch in a device array of the library, for
+ * callers that cannot allocate).
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller unless it is
@@ -25,7 +27,8 @@
  *     synchronises: all work is enqueued on `hip_stream` (a hipStream_t passed
  *     as void*; NULL = the default stream).  Scratch memory comes from the
  *     caller as `workspace` (256-byte aligned, size from the *_workspace_bytes
- *     query); its contents are undefined afterwards.
+ *     query); its contents are undefined afterwards.  (stream_prune_static is
+ *     the one exception: its scratch is a device array of the library.)
  *   - Layouts: Q and O are [heads, T, head_dim], K and V are
  *     [kv_heads, T, head_dim], last dimension contiguous; the head and token
  *     strides (in elements) are given in stream_shape, 0 meaning the contiguous
