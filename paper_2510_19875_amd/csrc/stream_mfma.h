@@ -23,19 +23,29 @@ __device__ __forceinline__ float dpp_f(float v)
                                                                  0xf, 0xf, false));
 }
 
-// Maximum over the 64 lanes, returned in every lane.
+// Maximum over the 64 lanes, returned in every lane (wave-uniform).  Written out as DPP
+// instructions: max(v, v[permuted]) is one instruction per step (left to the compiler a step is a
+// DPP move, two canonicalising maxima and the maximum itself); pairs, quads, halves of a 16-lane
+// row, the row, then row 0 into row 1 and row 2 into row 3 (row_bcast:15), rows 0-1 into rows 2-3
+// (row_bcast:31): lane 63 holds the result.  A DPP read of a register that a vector instruction
+// has just written needs two wait states (s_nop 1).  NaN operands are dropped, as by fmaxf.
 __device__ __forceinline__ float wave_max(float v)
 {
-    v = fmaxf(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
-    v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror: every lane of a 16-lane row holds the row max
-    const int iv = __builtin_bit_cast(int, v);
-    const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
-    const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
-    const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
-    const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
-    return fmaxf(fmaxf(a, b), fmaxf(c, d));
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "s_nop 1"
+                 : "+v"(v));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // One operand fragment (16 bytes per lane) times another, accumulated into a 32x32 tile.

@@ -24,9 +24,14 @@ namespace stream {
 // ARB: the mask C is an explicit bit array (STREAM_MASK_ARRAY) instead of a rule: a branch's
 // representative is found by scanning the row's C^blk bits, and every block that is not wholly
 // visible takes the token-level test against the array.
-template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI, bool ARB = false>
+// KS: a key block is scored as KS sub-tiles of 32 * NG keys one after the other (its score is the
+// maximum over them): half the K registers and accumulators of the whole-block form, which lets a
+// third wavefront share the SIMD.  Used for short lists, where a level has a handful of tiles
+// and what a row waits for is memory and its own serial work between the tile loops.
+template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI, bool ARB = false, int KS = 1>
 __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
+    static_assert(KS == 1 || WPR == 1, "sub-tiles only in the one-wavefront-per-row form");
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int FR = D * ES / 32;                       // fragments per 32-token group
     // bf16 tiles are multiplied with 16x16x32 MFMAs (S16): under the power limit that governs a
@@ -43,7 +48,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     typedef float acc_t __attribute__((ext_vector_type(AE)));
     static_assert(RG * KF == MB * FR && CG * KF == NG * FR, "same number of fragments either way");
     constexpr int BQ = 32 * MB * (WPR == 4 ? 2 : 1);      // query block b_q
-    constexpr int BK = 32 * NG * (WPR == 4 ? 2 : 1);      // key block b_k
+    constexpr int BK = 32 * NG * KS * (WPR == 4 ? 2 : 1); // key block b_k
     constexpr long long TILE_BYTES = (long long)BK * D * ES;
     constexpr int GROUP_BYTES = 32 * D * ES;
     __shared__ int s_rep[4][2 * kMaxTopk];
@@ -152,9 +157,9 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     }
 
     // K tiles of this (kv head, sequence), from this wavefront's key half on
-    const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(
-        p.Kp + ((long long)kvh * p.NB + sd.blk0) * BQ * D * ES + (long long)kh * NG * GROUP_BYTES,
-        (unsigned)((long long)N * TILE_BYTES - (long long)kh * NG * GROUP_BYTES));
+    const char *kbase = p.Kp + ((long long)kvh * p.NB + sd.blk0) * BQ * D * ES + (long long)kh * NG * GROUP_BYTES;
+    const unsigned kbytes = (unsigned)((long long)N * TILE_BYTES - (long long)kh * NG * GROUP_BYTES);
+    const __amdgpu_buffer_rsrc_t krs = make_tile_rsrc(kbase, kbytes);
     const unsigned lane_off = lane * 16;
     const bool tail_row = (q + 1) * BQ > L;               // the query block has padded rows
     const int qtok0 = q * BQ + qh * 32 * MB;
@@ -164,6 +169,12 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     // blocks <= edge_hi hold a key that lies outside the window of the block's last query
     const int edge_num = q * BQ + BQ - 1 - p.window;
     const int edge_hi = p.mask == STREAM_MASK_SLIDING && edge_num >= 0 ? edge_num / BK : -1;
+    // ... and so do the blocks from cut_lo on: those that reach past the row's first query (causal
+    // rules: (r + 1) b_k - 1 > q b_q) or past the end of the sequence ((r + 1) b_k > L); every block
+    // when the query block itself has padded rows
+    int cut_lo = L / BK;
+    if (p.mask != STREAM_MASK_FULL && (q * BQ + 1) / BK < cut_lo) cut_lo = (q * BQ + 1) / BK;
+    if (tail_row) cut_lo = 0;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const long long o = row * p.kmax;
     // ARB: first key block of [a, b] that C^blk leaves to this row, or -1
@@ -239,10 +250,19 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
-        for (int t = 0; t < nt; ++t) {
+        float mx = -INFINITY;
+        for (int u = 0; u < nt * KS; ++u) {
+            // sub-tile sk of the t-th block to score; the one after it (the last repeats itself)
+            const int t = u / KS, sk = u % KS;
+            const bool more = u + 1 < nt * KS;
+            const int un = more ? u + 1 : u;
             const int r = __builtin_amdgcn_readfirstlane(s_rep[wave][t]);
-            const int tn = t + 1 < nt ? t + 1 : t;
-            const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[wave][tn]) * (unsigned)TILE_BYTES;
+            const unsigned nxt = (unsigned)__builtin_amdgcn_readfirstlane(s_rep[wave][un / KS]) * (unsigned)TILE_BYTES +
+                                 (unsigned)(un % KS) * (unsigned)(NG * GROUP_BYTES);
+            // after the level's last tile there is nothing to fetch ahead: the refills then go
+            // through a resource of zero bytes, which answers every load with zeros without a
+            // memory access (loads return in order: real ones would hold up the next level's first tile)
+            const __amdgpu_buffer_rsrc_t krs_next = make_tile_rsrc(kbase, more ? kbytes : 0u);
             acc_t acc[RG][CG];
 #pragma unroll
             for (int rb = 0; rb < RG; ++rb)
@@ -267,14 +287,12 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                     // so that every fragment of the next tile has a whole tile of MFMA time to arrive
                     // (the scheduling barriers stop the compiler from sinking the loads to the end)
                     __builtin_amdgcn_sched_barrier(0);
-                    kf[cb][fr] = load_frag(krs, lane_off, nxt, cb * KF + fr);
+                    kf[cb][fr] = load_frag(krs_next, lane_off, nxt, cb * KF + fr);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            float mx = -INFINITY;
             // the block reaches past the row's first query (causal rules) or past the sequence
-            bool cut = tail_row || (p.mask != STREAM_MASK_FULL && (r + 1) * BK - 1 > q * BQ) ||
-                       r <= edge_hi || (r + 1) * BK > L;
+            bool cut = (r <= edge_hi) | (r >= cut_lo);
             if constexpr (ARB) cut = !((allrow[r >> 5] >> (r & 31)) & 1u);
             if (!cut) {
 #pragma unroll
@@ -287,7 +305,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                 // a block the mask cuts through (diagonal, window edge) or with padded rows/cols:
                 // token-level test.  Accumulator layouts: 32x32 - lane holds column lane % 32, element
                 // i is row 8*(i/4) + 4*(lane/32) + (i%4); 16x16 - column lane % 16, row 4*(lane/16) + i.
-                const int ktok0 = r * BK + kh * 32 * NG;
+                const int ktok0 = r * BK + (kh + sk) * 32 * NG;
                 // ARB: lane j fetches the mask words of query row j (and j + 64) of this tile, one per
                 // 32-key group; an element then takes its row's word from the lane that fetched it
                 constexpr int RS = (32 * MB + 63) / 64;
@@ -325,8 +343,11 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
                             mx = visible ? fmaxf(mx, acc[rb][cb][i]) : mx;
                         }
             }
-            mx = wave_max(mx);
-            if (lane == 0) s_sc[wave][t] = mx;
+            if (sk == KS - 1) {
+                mx = wave_max(mx);
+                if (lane == 0) s_sc[wave][t] = mx;
+                mx = -INFINITY;
+            }
         }
         tiles_done += (unsigned long long)nt;
         wave_sync();
@@ -444,8 +465,11 @@ typedef void (*level_fn)(const PruneParams);
 // One wavefront per row holds MB x NG accumulator tiles; beyond 2 x 2 only one wavefront fits a
 // SIMD's registers.  fp32 fragments are twice as many: with d = 128 the 4 x 2 and 2 x 4 shapes do
 // not fit at all.
+// Lists this short take the sub-tile form of the 64 x 64 bf16 kernel (three wavefronts per SIMD).
+constexpr int kShortListTopk = 8;
+
 template <bool MULTI, bool BF16, int D, bool ARB>
-static level_fn pick_level_kernel_d(int bq, int bk, int &wpr)
+static level_fn pick_level_kernel_d(int bq, int bk, int kmax, int &wpr)
 {
     constexpr int OCC2 = (BF16 || D == 64) ? 2 : 1;
     constexpr bool BIG = BF16 || D == 64;           // 6 fragment groups + 8 accumulator tiles fit
@@ -453,6 +477,8 @@ static level_fn pick_level_kernel_d(int bq, int bk, int &wpr)
     const int mb = bq / 32, ng = bk / 32;
     if (mb == 4 && ng == 4) { wpr = 4; return level_kernel<BF16, D, 2, 2, 4, OCC2, MULTI, ARB>; }
     if (mb == 1 && ng == 1) return level_kernel<BF16, D, 1, 1, 1, 2, MULTI, ARB>;
+    if constexpr (BF16 && !MULTI && !ARB)
+        if (mb == 2 && ng == 2 && kmax <= kShortListTopk) return level_kernel<BF16, D, 2, 1, 1, 2, MULTI, ARB, 2>;
     if (mb == 2 && ng == 2) return level_kernel<BF16, D, 2, 2, 1, OCC2, MULTI, ARB>;
     if (mb == 1 && ng == 2) return level_kernel<BF16, D, 1, 2, 1, OCC2, MULTI, ARB>;
     if (mb == 2 && ng == 1) return level_kernel<BF16, D, 2, 1, 1, OCC2, MULTI, ARB>;
@@ -470,10 +496,10 @@ template <bool MULTI, bool ARB>
 static level_fn pick_level_kernel_t(const Problem &pb, int &wpr)
 {
     if (pb.dtype == STREAM_BF16)
-        return pb.d == 128 ? pick_level_kernel_d<MULTI, true, 128, ARB>(pb.b, pb.bk, wpr)
-                           : pick_level_kernel_d<MULTI, true, 64, ARB>(pb.b, pb.bk, wpr);
-    return pb.d == 128 ? pick_level_kernel_d<MULTI, false, 128, ARB>(pb.b, pb.bk, wpr)
-                       : pick_level_kernel_d<MULTI, false, 64, ARB>(pb.b, pb.bk, wpr);
+        return pb.d == 128 ? pick_level_kernel_d<MULTI, true, 128, ARB>(pb.b, pb.bk, pb.kmax, wpr)
+                           : pick_level_kernel_d<MULTI, true, 64, ARB>(pb.b, pb.bk, pb.kmax, wpr);
+    return pb.d == 128 ? pick_level_kernel_d<MULTI, false, 128, ARB>(pb.b, pb.bk, pb.kmax, wpr)
+                       : pick_level_kernel_d<MULTI, false, 64, ARB>(pb.b, pb.bk, pb.kmax, wpr);
 }
 
 static level_fn pick_level_kernel(const Problem &pb, bool multi, int &wpr)
