@@ -191,6 +191,10 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         return -1;
     };
 
+    // The Q tile has to be there before the first MFMA anyway; waiting for it here, once, lets
+    // the waits inside the tile loop count K fragments only (vmcnt(0), other counters untouched).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
     // A row runs its levels level_begin .. level_last back to back: the Q tile stays in
     // registers and the node list moves from one level to the next through LDS.
     for (int level = level_begin; level <= level_last; ++level) {
