@@ -581,15 +581,15 @@ def variable_k(w, layer, reps=3):
 
 
 def block_shapes(w, layer, scale, reps=3):
-    """The step with b_q != b_k on the same Q, K, V: k scaled so that every shape keeps the same
-    2048 keys per query row as the headline shape."""
+    """The step with the other block shapes (b_q, b_k in 32, 64, 128) on the same Q, K, V: k scaled
+    so that every shape keeps the same 2048 keys per query row as the headline shape."""
     import torch
 
     from paper_2510_19875_amd import binding
 
     Q, K, V = layer
     out = {}
-    for bq, bk in ((32, 128), (128, 32), (64, 128), (128, 64)):
+    for bq, bk in ((32, 32), (128, 128), (32, 64), (64, 32), (32, 128), (128, 32), (64, 128), (128, 64)):
         k = max(1, min(64, w.topk[0] * w.block // bk))        # the library keeps at most 64 blocks per row
         st = {}
 
