@@ -25,9 +25,10 @@ namespace stream {
 // representative is found by scanning the row's C^blk bits, and every block that is not wholly
 // visible takes the token-level test against the array.
 // KS: a key block is scored as KS sub-tiles of 32 * NG keys one after the other (its score is the
-// maximum over them): half the K registers and accumulators of the whole-block form, which lets a
-// third wavefront share the SIMD.  Used for short lists, where a level has a handful of tiles
-// and what a row waits for is memory and its own serial work between the tile loops.
+// maximum over them): half the K registers and accumulators of the whole-block form (no register
+// spills, and a level's first MFMAs start after half as many bytes have arrived).  Used for short
+// lists, where a level has a handful of tiles: measured 3-5 % faster there, 3-4 % slower on long
+// lists.  (A third wavefront per SIMD would fit only with ~30 spilled registers: slower.)
 template <bool BF16, int D, int MB, int NG, int WPR, int OCC, bool MULTI, bool ARB = false, int KS = 1>
 __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 {
@@ -469,7 +470,7 @@ typedef void (*level_fn)(const PruneParams);
 // One wavefront per row holds MB x NG accumulator tiles; beyond 2 x 2 only one wavefront fits a
 // SIMD's registers.  fp32 fragments are twice as many: with d = 128 the 4 x 2 and 2 x 4 shapes do
 // not fit at all.
-// Lists this short take the sub-tile form of the 64 x 64 bf16 kernel (three wavefronts per SIMD).
+// Lists this short take the two-sub-tile form (KS = 2) of the 64 x 64 bf16 kernel.
 constexpr int kShortListTopk = 8;
 
 template <bool MULTI, bool BF16, int D, bool ARB>
