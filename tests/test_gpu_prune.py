@@ -240,3 +240,38 @@ def test_token_major_q_spanning_more_than_4_gib():
     same = sum(int(np.array_equal(gi[h, q], ref["idx"][i])) for i, (h, q) in enumerate(rows))
     print(f"[prune] strided Q beyond 4 GiB: {same} of {len(rows)} sampled rows equal the oracle", flush=True)
     assert same >= len(rows) - 1
+
+
+@pytest.mark.parametrize("mask,window", [("causal", 0), ("sliding", 700), ("full", 0)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_short_list_form_equals_the_whole_block_form(mask, window, d):
+    """Lists of at most 8 blocks take a variant of the kernel that scores a 64 x 64 block as two
+    64 x 32 sub-tiles.  A second sequence that asks for 9 blocks switches the whole call to the
+    ordinary variant: the first sequence's lists and scores must not change by a bit, and both
+    agree with the oracle."""
+    lens = (64 * 37 + 11, 64 * 12)
+    H, kv = 4, 2
+    w = wl.scaled(wl.config(5), lens, topk=(8, 8), heads=H, kv_heads=kv, block=64, dtype="bf16",
+                  head_dim=d, anchors_per_seq=2)
+    print(f"[short lists] {mask}/{window} d={d} lens={lens}", flush=True)
+    Q, K, _, _ = wl.make_inputs(w, with_v=False)
+    Qd, Kd = Q.to(DEV), K.to(DEV)
+    Qf, Kf = Q.float().numpy(), K.float().numpy()
+    nb0 = w.blocks_per_seq[0]
+    for k0 in (8, 3, 1):
+        got = []
+        for ks in ((k0, 8), (k0, 9)):
+            o = binding.stream_prune(Qd, Kd, H, kv, 64, list(ks), cu_seqlens=w.cu_seqlens, want_score=True,
+                                     want_trace=True, mask=mask, window=window)
+            torch.cuda.synchronize()
+            got.append({x: o[x].cpu().numpy() for x in ("idx", "cnt", "score", "trace")})
+        short, whole = got
+        np.testing.assert_array_equal(short["idx"][:, :nb0, :k0], whole["idx"][:, :nb0, :k0])
+        np.testing.assert_array_equal(short["cnt"][:, :nb0], whole["cnt"][:, :nb0])
+        np.testing.assert_array_equal(short["score"][:, :nb0, :k0], whole["score"][:, :nb0, :k0])
+        assert (whole["idx"][:, :nb0, k0:] == -1).all()
+        ref = so.prune(Qf, Kf, H, kv, 64, [k0, 8], cu_seqlens=w.cu_seqlens, mask=mask, window=window)
+        res = parity.compare_prune(short, ref, Qf, Kf, H, kv, 64, [k0, 8], cu_seqlens=w.cu_seqlens,
+                                   mask=mask, window=window)
+        print(f"[short lists] k={k0} rows={res['rows']} equal={res['equal']} tie_rows={res['tie_rows']}", flush=True)
+        assert res["tie_rows"] <= max(2, res["rows"] // 100)
