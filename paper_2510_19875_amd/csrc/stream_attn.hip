@@ -257,6 +257,11 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // and is read with a scalar lane select: no memory access inside the tile loops
     const int my_blk = !WIDE && lane < n_blk ? my_idx[lane] : 0;
     __shared__ int s_blk[WIDE ? 4 : 1][WIDE ? kMaxTopkWide : 1];
+    // pass 1: staging of the output tile, 32 query rows of at most 256 bytes at a time (the pad
+    // of 16 bytes per row spreads the rows over the banks)
+    constexpr int O_NDBU = NDB < 256 / (32 * ES) ? NDB : 256 / (32 * ES);   // feature blocks per staged unit
+    constexpr int O_URB = O_NDBU * 32 * ES, O_URS = O_URB + 16;
+    __shared__ __align__(16) char s_o[PASS == 1 ? 4 * 32 * O_URS : 16];
     // ARB: "every pair of this query block and that key block is real and set in C", per key block
     const unsigned *allrow = ARB ? p.call + (long long)gb * p.cw : nullptr;
     auto all_bit = [&](int r) -> bool {          // (an entry outside the block range reads as "cut")
@@ -753,10 +758,13 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         lse2[cq] = l_tot > 0.f ? m_run[cq] + log2f(l_tot) : -INFINITY;
         if (!safe) {
             bad = bad | !(l_tot > 1e-30f) | !(l_tot < 3e38f) | !(lr_tot > 1e-30f) | !(lr_tot < 3e38f);
+            // (0 * x summed over the accumulators is NaN as soon as one of them is not finite)
+            float chk = 0.f;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) bad = bad | !(fabsf(acc_o[db][cq][i]) < 3e38f);
+                for (int i = 0; i < 16; ++i) chk = fmaf(acc_o[db][cq][i], 0.f, chk);
+            bad = bad | !(chk == 0.f);
         }
     }
     if (safe || !__any(bad)) break;
@@ -764,32 +772,54 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     }
 
     // ------------------------------------------------------------------ store O, lse
+    // O^T accumulator: lane holds query `col`; element i of block db is feature
+    // db*32 + 8*(i/4) + 4*gh + (i%4): four consecutive features per group of 4.  Written from
+    // here a store instruction would touch 32 rows with 8 or 16 bytes each; the normalised tile
+    // goes through LDS instead, 32 rows at a time, and leaves as whole rows (16 bytes per lane).
+    {
+        char *so = s_o + wave * 32 * O_URS;
+        constexpr int LPR = O_URB / 16, RPI = 64 / LPR;        // lanes per staged row, rows per store
+#pragma unroll
+        for (int cq = 0; cq < NQ; ++cq)
+#pragma unroll
+            for (int u = 0; u < NDB / O_NDBU; ++u) {
+#pragma unroll
+                for (int dbu = 0; dbu < O_NDBU; ++dbu)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const int db = u * O_NDBU + dbu;
+                        const int feat = dbu * 32 + i4 * 8 + gh * 4;      // within the unit
+                        const float a = acc_o[db][cq][i4 * 4 + 0] * inv[cq], b = acc_o[db][cq][i4 * 4 + 1] * inv[cq];
+                        const float c = acc_o[db][cq][i4 * 4 + 2] * inv[cq], d = acc_o[db][cq][i4 * 4 + 3] * inv[cq];
+                        if constexpr (BF16) {
+                            uint2 v;
+                            v.x = pack_bf16x2(a, b);
+                            v.y = pack_bf16x2(c, d);
+                            *reinterpret_cast<uint2 *>(so + col * O_URS + feat * 2) = v;
+                        } else {
+                            *reinterpret_cast<float4 *>(so + col * O_URS + feat * 4) = make_float4(a, b, c, d);
+                        }
+                    }
+                wave_sync();
+#pragma unroll
+                for (int j = 0; j < 32 / RPI; ++j) {
+                    const int r = j * RPI + lane / LPR, ch = lane % LPR;
+                    const int tok = qtok0 + cq * 32 + r;
+                    if (tok < L) {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(so + r * O_URS + ch * 16);
+                        *reinterpret_cast<uint4 *>(p.O + (long long)h * p.o_sh_b + (sd.tok0 + tok) * p.o_st_b +
+                                                   u * O_URB + ch * 16) = v;
+                    }
+                }
+                wave_sync();
+            }
+    }
 #pragma unroll
     for (int cq = 0; cq < NQ; ++cq) {
         const int tok = qtok0 + cq * 32 + col;
-        if (tok < L) {
-            char *dst = p.O + (long long)h * p.o_sh_b + (sd.tok0 + tok) * p.o_st_b;
-            // O^T accumulator: lane holds query `col`; element i of block db is feature
-            // db*32 + 8*(i/4) + 4*gh + (i%4): four consecutive features per group of 4
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const int feat = db * 32 + i4 * 8 + gh * 4;
-                    const float a = acc_o[db][cq][i4 * 4 + 0] * inv[cq], b = acc_o[db][cq][i4 * 4 + 1] * inv[cq];
-                    const float c = acc_o[db][cq][i4 * 4 + 2] * inv[cq], d = acc_o[db][cq][i4 * 4 + 3] * inv[cq];
-                    if constexpr (BF16) {
-                        uint2 v;
-                        v.x = pack_bf16x2(a, b);
-                        v.y = pack_bf16x2(c, d);
-                        *reinterpret_cast<uint2 *>(dst + feat * 2) = v;
-                    } else {
-                        *reinterpret_cast<float4 *>(dst + feat * 4) = make_float4(a, b, c, d);
-                    }
-                }
-            if (p.lse && gh == 0)
-                p.lse[(long long)h * p.T + sd.tok0 + tok] = lse2[cq] * 0.6931471805599453f;
-            if (p.lse2 && gh == 0) p.lse2[(long long)h * p.T + sd.tok0 + tok] = lse2[cq];
+        if (tok < L && gh == 0) {
+            if (p.lse) p.lse[(long long)h * p.T + sd.tok0 + tok] = lse2[cq] * 0.6931471805599453f;
+            if (p.lse2) p.lse2[(long long)h * p.T + sd.tok0 + tok] = lse2[cq];
         }
     }
     } else {
