@@ -207,24 +207,56 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keep it scalar
     const int col = lane & 31, gh = lane >> 5;
+    // The arguments a wavefront needs before its first tile, fetched together: left to itself the
+    // compiler loads each where it is first used and waits for it there - a dozen round trips to
+    // the scalar cache one after the other, at the start of every row, with nothing to hide them
+    // behind when a SIMD holds one wavefront.  (The empty asm makes them live here.)
+    WgMap a_map = p.map;
+    int a_NB = p.NB, a_g = p.g, a_kmax = p.kmax, a_nseq = p.seqs.n, a_mask = p.mask, a_window = p.window;
+    float a_scale = p.scale_log2e;
+    long long a_qsh = p.q_sh_b, a_qst = p.q_st_b;
+    const char *a_Q = p.Q, *a_Kp = p.Kp, *a_Vp = p.Vp;
+    unsigned long long u_idx = (unsigned long long)p.idx, u_cnt = (unsigned long long)p.cnt;
+    asm volatile("" : "+s"(a_map.mode), "+s"(a_map.per_kv), "+s"(a_map.kv_heads), "+s"(a_NB), "+s"(a_g),
+                      "+s"(a_kmax), "+s"(a_nseq), "+s"(a_qsh), "+s"(a_qst), "+s"(a_Q), "+s"(a_Kp), "+s"(a_Vp),
+                      "+s"(u_idx), "+s"(u_cnt), "+s"(a_mask), "+s"(a_window), "+s"(a_scale));
+    // (the two pointers that are dereferenced come back as pointers to global memory: through
+    // the asm the compiler no longer knows where they point and would use flat loads, whose
+    // completion it can only wait for together with every other load in flight)
+    typedef const int __attribute__((address_space(1))) *global_int_ptr;
+    const int *a_idx = (const int *)(global_int_ptr)u_idx, *a_cnt = (const int *)(global_int_ptr)u_cnt;
     int kvh, slot;
-    if (!wg_decode(p.map, blockIdx.x, kvh, slot)) return;
-    const long long items_per_kv = (long long)p.NB * p.g * QSUB;
+    if (!wg_decode(a_map, blockIdx.x, kvh, slot)) return;
+    const long long items_per_kv = (long long)a_NB * a_g * QSUB;
     const long long it = (long long)slot * 4 + wave;
     if (it >= items_per_kv) return;
-    const int qs = (int)(it % QSUB);
-    const long long rk = it / QSUB;
-    const int gb = p.NB - 1 - (int)(rk / p.g);
-    const int h = kvh * p.g + (int)(rk % p.g);
-    const int sq = seq_of_block(p.seqs, gb);
+    int qs, rk_blk, rk_head;
+    if (items_per_kv <= 0x7fffffffLL) {           // (a 64-bit division is ~100 instructions)
+        const unsigned rk = (unsigned)it / (unsigned)QSUB;
+        qs = (int)((unsigned)it % (unsigned)QSUB);
+        rk_blk = (int)(rk / (unsigned)a_g);
+        rk_head = (int)(rk - (unsigned)rk_blk * (unsigned)a_g);
+    } else {
+        const long long rk = it / QSUB;
+        qs = (int)(it % QSUB);
+        rk_blk = (int)(rk / a_g);
+        rk_head = (int)(rk % a_g);
+    }
+    const int gb = a_NB - 1 - rk_blk;
+    const int h = kvh * a_g + rk_head;
+    int sq = 0;
+    while (sq + 1 < a_nseq && gb >= p.seqs.d[sq + 1].blk0) ++sq;
     const SeqDesc sd = p.seqs.d[sq];
     const int q = gb - sd.blk0, L = sd.len;
-    const long long row = (long long)h * p.NB + gb;
+    const long long row = (long long)h * a_NB + gb;
     const int qtok0 = q * BQ + qs * QT;         // first query token (sequence-local) of this wavefront
     if (qtok0 >= L) return;
-    int n_blk = p.cnt[row];
-    n_blk = n_blk < 0 ? 0 : (n_blk > p.kmax ? p.kmax : n_blk);   // never read past the row's list
-    const int *my_idx = p.idx + row * p.kmax;
+    const int *my_idx = a_idx + row * a_kmax;
+    // (the list is fetched for every slot of the row, whatever its count, so that the load does
+    // not wait for the count)
+    const int my_raw = !WIDE && lane < a_kmax ? my_idx[lane] : 0;
+    int n_blk = a_cnt[row];
+    n_blk = n_blk < 0 ? 0 : (n_blk > a_kmax ? a_kmax : n_blk);   // never read past the row's list
 
     // key sub-tiles to visit: all of every listed block, except that under a causal rule the
     // sub-tiles of the diagonal block lying entirely after this wavefront's queries are dropped
@@ -233,29 +265,33 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     int n_tiles = n_blk * KSUB;
 
     // Q fragments (usable as A or B operand): lane (col, gh), fragment fr -> chunk 2*fr+gh of row col
+    // (through a resource that starts at the wavefront's first query and spans its real rows:
+    // rows past the end of the sequence read as zeros, no branch around any load)
     uint4 qf[NQ][FR];
+    {
+        const int qrows = L - qtok0 < QT ? L - qtok0 : QT;
+        const __amdgpu_buffer_rsrc_t qrs = make_tile_rsrc(
+            a_Q + (long long)h * a_qsh + (sd.tok0 + qtok0) * a_qst, (unsigned)((long long)(qrows - 1) * a_qst + D * ES));
 #pragma unroll
-    for (int cq = 0; cq < NQ; ++cq) {
-        const int tok = qtok0 + cq * 32 + col;
-        const bool ok = tok < L;
-        const char *src = p.Q + (long long)h * p.q_sh_b + (sd.tok0 + (ok ? tok : 0)) * p.q_st_b + gh * 16;
+        for (int cq = 0; cq < NQ; ++cq) {
+            const unsigned voff = (unsigned)(cq * 32 + col) * (unsigned)a_qst + gh * 16;
 #pragma unroll
-        for (int fr = 0; fr < FR; ++fr) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (ok) v = *reinterpret_cast<const uint4 *>(src + fr * 32);
-            qf[cq][fr] = v;
+            for (int fr = 0; fr < FR; ++fr) {
+                const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(qrs, voff + fr * 32, 0, 0);
+                qf[cq][fr] = make_uint4(v[0], v[1], v[2], v[3]);
+            }
         }
     }
     // packed K and V tiles of this (kv head, sequence)
     const unsigned region_bytes = (unsigned)((long long)sd.nblk * QBLK_BYTES);
     const __amdgpu_buffer_rsrc_t krs =
-        make_tile_rsrc(p.Kp + ((long long)kvh * p.NB + sd.blk0) * QBLK_BYTES, region_bytes);
+        make_tile_rsrc(a_Kp + ((long long)kvh * a_NB + sd.blk0) * QBLK_BYTES, region_bytes);
     const __amdgpu_buffer_rsrc_t vrs =
-        make_tile_rsrc(p.Vp + ((long long)kvh * p.NB + sd.blk0) * QBLK_BYTES, region_bytes);
+        make_tile_rsrc(a_Vp + ((long long)kvh * a_NB + sd.blk0) * QBLK_BYTES, region_bytes);
     const unsigned lane_off = lane * 16;
     // the row's block list lives in one register (lane j holds entry j; lists have <= 64 entries)
     // and is read with a scalar lane select: no memory access inside the tile loops
-    const int my_blk = !WIDE && lane < n_blk ? my_idx[lane] : 0;
+    const int my_blk = lane < n_blk ? my_raw : 0;
     __shared__ int s_blk[WIDE ? 4 : 1][WIDE ? kMaxTopkWide : 1];
     // pass 1: staging of the output tile, 32 query rows of at most 256 bytes at a time (the pad
     // of 16 bytes per row spreads the rows over the banks)
@@ -289,8 +325,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
         entry_bad = (lane < n_blk) & (((unsigned)my_blk >= (unsigned)nkb) | ((lane > 0) & (my_blk <= before)));
     }
     const bool plain_list = __ballot(entry_bad) != 0ull;          // wave-uniform
-    if (!ARB && !plain_list && n_blk > 0 && p.mask != STREAM_MASK_FULL) {
-        const int last_r = my_idx[n_blk - 1];
+    if (!ARB && !plain_list && n_blk > 0 && a_mask != STREAM_MASK_FULL) {
+        const int last_r = WIDE ? my_idx[n_blk - 1] : __builtin_amdgcn_readlane(my_blk, n_blk - 1);
         if (last_r * BK + (KSUB - 1) * KT > qtok0 + QT - 1) {
             int vis = (qtok0 + QT - 1 - last_r * BK) / KT + 1;
             vis = vis < 0 ? 0 : (vis > KSUB ? KSUB : vis);
@@ -317,8 +353,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // does the mask C (or the end of the sequence) cut through the sub-tile that starts at key k0?
     auto needs_mask = [&](int k0) -> bool {
         bool m = k0 + KT > L;
-        if (p.mask != STREAM_MASK_FULL) m = m || (k0 + KT - 1 > qtok0);                       // keys after a query
-        if (p.mask == STREAM_MASK_SLIDING) m = m || (k0 <= qtok0 + QT - 1 - p.window);         // keys before a window
+        if (a_mask != STREAM_MASK_FULL) m = m || (k0 + KT - 1 > qtok0);                       // keys after a query
+        if (a_mask == STREAM_MASK_SLIDING) m = m || (k0 <= qtok0 + QT - 1 - a_window);         // keys before a window
         return m;
     };
     // ARB: bit j = list entry j is wholly visible to this query block (every pair real and set in
@@ -343,7 +379,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // of those same rounded values (lr_run): a row dominated by one key then gets that key's V
     // exactly, whatever the rounding of its probability.  lse uses the unrounded sum (l_run).
     float lr_run[NQ];
-    const float c2 = p.scale_log2e;
+    const float c2 = a_scale;
     // (fp32 at d = 128 does not fit the double buffers in the register file: plain loop only)
     constexpr bool PIPE = NK == 1 && (BF16 || D == 64);
     // The pipelined loop reads the Q fragments from the accumulation registers (an MFMA takes
@@ -378,7 +414,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     if constexpr (PIPE) {
         t_end = n_tiles;
         while (t_end > 0 && tile_masked(t_end - 1)) --t_end;
-        if (p.mask == STREAM_MASK_SLIDING)
+        if (a_mask == STREAM_MASK_SLIDING)
             while (tb < t_end && tile_masked(tb)) ++tb;
         if constexpr (ARB) {
             // an array can cut any entry of the list: the pipeline takes the longest run of
@@ -452,7 +488,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                             const unsigned cwd = ((tq < L) & ((unsigned)(ktok0 + rb * 32) < (unsigned)L)) ? p.cbits[(long long)tq * p.cpitch + ((ktok0 >> 5) + rb)] : 0u;
                             visible = visible & ((cwd >> ((i >> 2) * 8 + gh * 4 + (i & 3))) & 1u);
                         } else {
-                            visible = visible & mask_token(p.mask, p.window, tq, tk);
+                            visible = visible & mask_token(a_mask, a_window, tq, tk);
                         }
                         acc_s[rb][cq][i] = visible ? acc_s[rb][cq][i] : -INFINITY;
                     }
@@ -824,7 +860,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     }
     } else {
     uint4 kreg[NK][FR];
-    const float c2 = p.scale_log2e;
+    const float c2 = a_scale;
     // ------------------------------------------------------------------ pass 2: received mass
     // S = Q K^T: a lane owns key column `col`; element i of row block rq is query
     // rq*32 + 8*(i/4) + 4*gh + (i%4).  Its normaliser:
@@ -903,7 +939,7 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                             const unsigned cwd = (unsigned)__shfl((int)rowword, rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3));
                             visible = visible & ((cwd >> col) & 1u);
                         } else {
-                            visible = visible & mask_token(p.mask, p.window, tq, tk);
+                            visible = visible & mask_token(a_mask, a_window, tq, tk);
                         }
                         colsum += visible ? e : 0.f;
                     }
@@ -1034,6 +1070,8 @@ stream_status stream_sparse_attn(const void *Q, const void *K, const void *V,
     if (q_st < pb.d || k_st < pb.d || v_st < pb.d || o_st < pb.d) return STREAM_EINVAL;
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return STREAM_EINVAL;
     if (((q_sh | q_st | k_sh | k_st | v_sh | v_st | o_sh | o_st) * pb.esize) & 15) return STREAM_EINVAL;
+    // the kernels address a wavefront's query rows with 32-bit offsets from its first row
+    if (q_st * pb.esize * 128 >= (1LL << 31)) return STREAM_EUNSUPPORTED;
     const AttnWorkspace w = attn_layout(pb);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return STREAM_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
