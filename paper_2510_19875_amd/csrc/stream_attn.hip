@@ -836,18 +836,24 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                             *reinterpret_cast<float4 *>(so + col * O_URS + feat * 4) = make_float4(a, b, c, d);
                         }
                     }
-                wave_sync();
+                // (LDS serves a wavefront's instructions in order: the reads below see these writes,
+                // and the next unit's writes come after these reads.  A fence here would also wait
+                // for the global stores of the unit before, a memory round trip per unit.)
+                __builtin_amdgcn_wave_barrier();
+                // (all reads of the unit first, then its stores: one LDS latency per unit, not per store)
+                uint4 ov[32 / RPI];
+#pragma unroll
+                for (int j = 0; j < 32 / RPI; ++j)
+                    ov[j] = *reinterpret_cast<const uint4 *>(so + (j * RPI + lane / LPR) * O_URS + (lane % LPR) * 16);
 #pragma unroll
                 for (int j = 0; j < 32 / RPI; ++j) {
                     const int r = j * RPI + lane / LPR, ch = lane % LPR;
                     const int tok = qtok0 + cq * 32 + r;
-                    if (tok < L) {
-                        const uint4 v = *reinterpret_cast<const uint4 *>(so + r * O_URS + ch * 16);
+                    if (tok < L)
                         *reinterpret_cast<uint4 *>(p.O + (long long)h * p.o_sh_b + (sd.tok0 + tok) * p.o_st_b +
-                                                   u * O_URB + ch * 16) = v;
-                    }
+                                                   u * O_URB + ch * 16) = ov[j];
                 }
-                wave_sync();
+                __builtin_amdgcn_wave_barrier();
             }
     }
 #pragma unroll
