@@ -837,8 +837,8 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
                         }
                     }
                 // (LDS serves a wavefront's instructions in order: the reads below see these writes,
-                // and the next unit's writes come after these reads.  A fence here would also wait
-                // for the global stores of the unit before, a memory round trip per unit.)
+                // and the next unit's writes come after these reads; the barrier only keeps the
+                // compiler from moving them across each other)
                 __builtin_amdgcn_wave_barrier();
                 // (all reads of the unit first, then its stores: one LDS latency per unit, not per store)
                 uint4 ov[32 / RPI];
