@@ -56,6 +56,9 @@ __global__ void __launch_bounds__(256) diff_kernel(const DiffParams p)
     const long long stride = (long long)gridDim.x * 4 * RPW;
     long long row = ((long long)blockIdx.x * 4 + wave) * RPW + sub;
     DiffRow nx = diff_load<RPW>(p, row, l);
+    // (the first rows' loads are waited for here, once: with them still pending at the loop's
+    // entry the compiler waited, in every iteration, for the next rows' loads right after issuing them)
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), the other counters untouched
     for (int i = 0; i < kDiffRowsPerWave; ++i, row += stride) {
         if (row - sub >= p.rows) break;                // wave-uniform: the step's first row
         const DiffRow cur = nx;
@@ -81,6 +84,11 @@ __global__ void __launch_bounds__(256) diff_kernel(const DiffParams p)
         const unsigned long long kb = RPW == 1 ? kb_all : ((kb_all >> (sub * LPR)) & 0xffffffffull);
         const int pos = __popcll(kb & ((1ull << l) - 1ull));
         const int n = __popcll(kb);
+        // The next rows' data is taken here, before these rows' stores are issued: stores and loads
+        // share one counter and complete in order, so a wait for the loads placed after the stores
+        // would wait for the stores' acknowledgements as well.
+        // (the count as an operand keeps the compiler from moving this, and the wait, above the search)
+        asm volatile("" : "+v"(nx.ca), "+v"(nx.cb), "+v"(nx.a), "+v"(nx.b), "+v"(nx.s) : "s"(n));
         if (row < p.rows) {
             const long long o = row * p.ka;
             if (keep) {

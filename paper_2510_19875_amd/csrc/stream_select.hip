@@ -125,6 +125,10 @@ __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
     long long row = (long long)blockIdx.x * 4 + wave;
     const int node = NB == 2 ? lane : lane >> 1;
     SelectRow<NB> nx = select_load<NB>(p, row, lane);
+    // (the first row's loads are waited for here, once: with them still pending at the loop's
+    // entry the compiler waited, in every iteration, for the loads of the next row right after
+    // issuing them; now those stay in flight during the search and are waited for after it)
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), the other counters untouched
     for (int i = 0; i < kSelectRowsPerWave && row < p.rows; ++i, row += stride) {
         const SelectRow<NB> cur = nx;
         nx = select_load<NB>(p, row + stride, lane);
@@ -155,6 +159,12 @@ __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
             pos += __popcll(kb[j] & lt);
             total += __popcll(kb[j]);
         }
+        // The next row's data is taken here, before this row's stores are issued: stores and loads
+        // share one counter and complete in order, so a wait for the loads placed after the stores
+        // would wait for the stores' acknowledgements as well.  (The count as an operand keeps
+        // the compiler from moving this, and the wait, above the search.)
+        asm volatile("" : "+v"(nx.c), "+v"(nx.f), "+v"(nx.l), "+v"(nx.s[0]) : "s"(total));
+        if constexpr (NB == 2) asm volatile("" : "+v"(nx.s[1]) : "s"(total));
         const long long o = row * p.kmax;
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
