@@ -29,26 +29,34 @@ struct SelectRow {
     float s[NB];
 };
 
+// The row's loads go through buffer resources over the whole arrays: the address of a load is a
+// scalar row offset plus the lane's constant offset, so a row costs no vector address arithmetic,
+// and what lies past the arrays (the prefetch after the last row) reads as zeros.  A lane past
+// the row's slots reads its neighbour row's data, which is never used: such a lane is not live.
+struct SelectBuffers {
+    __amdgpu_buffer_rsrc_t nf, nl, sc, cnt;
+    unsigned voff_node, voff_score;      // this lane's byte offsets inside a row
+    unsigned kmax;
+};
+
 template <int NB>
-__device__ __forceinline__ SelectRow<NB> select_load(const SelectParams &p, long long row, int lane)
+__device__ __forceinline__ SelectRow<NB> select_load(const SelectBuffers &b, unsigned row)
 {
     SelectRow<NB> r;
-    r.c = 0; r.f = 0; r.l = -1;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) r.s[i] = -INFINITY;
-    const int node = NB == 2 ? lane : lane >> 1;
-    if (row < p.rows && node < p.kmax) {
-        // none of the loads waits for another: slots past the live count are allocated, just unused
-        const long long o = row * p.kmax;
-        r.c = p.ncnt[row];
-        r.f = p.nf[o + node];
-        r.l = p.nl[o + node];
-        if constexpr (NB == 2) {
-            const float2 s = *reinterpret_cast<const float2 *>(p.score + 2 * (o + lane));
-            r.s[0] = s.x; r.s[1] = s.y;
-        } else {
-            r.s[0] = p.score[2 * o + lane];
-        }
+    const unsigned so = row * b.kmax * 4u;                 // the row's byte offset in nf / nl (scalar)
+    r.c = (int)__builtin_amdgcn_raw_buffer_load_b32(b.cnt, 0, row * 4u, 0);
+    r.f = (int)__builtin_amdgcn_raw_buffer_load_b32(b.nf, b.voff_node, so, 0);
+    r.l = (int)__builtin_amdgcn_raw_buffer_load_b32(b.nl, b.voff_node, so, 0);
+    if constexpr (NB == 2) {
+        typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+        const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(b.sc, b.voff_score, 2u * so, 0);
+        // (elements copied out by value first: __builtin_bit_cast applied directly to an element
+        // of an ext_vector_type lvalue reads element 0 whatever the index, with this compiler)
+        const unsigned s0 = v[0], s1 = v[1];
+        r.s[0] = __builtin_bit_cast(float, s0);
+        r.s[1] = __builtin_bit_cast(float, s1);
+    } else {
+        r.s[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(b.sc, b.voff_score, 2u * so, 0));
     }
     return r;
 }
@@ -115,23 +123,33 @@ __device__ __forceinline__ void select_topk_wave_v(const float (&s)[NB], const b
     }
 }
 
+// p.rows here is one launch's share of the rows, few enough that every byte offset fits 31 bits.
 template <int NB>
 __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // consecutive wavefronts take consecutive rows; a wavefront's own rows are a grid apart
-    const long long stride = (long long)gridDim.x * 4;
-    long long row = (long long)blockIdx.x * 4 + wave;
+    const unsigned rows = (unsigned)p.rows;
+    const unsigned stride = gridDim.x * 4u;
+    unsigned row = blockIdx.x * 4u + (unsigned)wave;
     const int node = NB == 2 ? lane : lane >> 1;
-    SelectRow<NB> nx = select_load<NB>(p, row, lane);
+    SelectBuffers b;
+    b.kmax = (unsigned)p.kmax;
+    b.nf = make_tile_rsrc(p.nf, rows * b.kmax * 4u);
+    b.nl = make_tile_rsrc(p.nl, rows * b.kmax * 4u);
+    b.sc = make_tile_rsrc(p.score, rows * b.kmax * 8u);
+    b.cnt = make_tile_rsrc(p.ncnt, rows * 4u);
+    b.voff_node = (unsigned)node * 4u;
+    b.voff_score = NB == 2 ? (unsigned)lane * 8u : (unsigned)lane * 4u;
+    SelectRow<NB> nx = select_load<NB>(b, row);
     // (the first row's loads are waited for here, once: with them still pending at the loop's
     // entry the compiler waited, in every iteration, for the loads of the next row right after
     // issuing them; now those stay in flight during the search and are waited for after it)
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), the other counters untouched
-    for (int i = 0; i < kSelectRowsPerWave && row < p.rows; ++i, row += stride) {
+    for (int i = 0; i < kSelectRowsPerWave && row < rows; ++i, row += stride) {
         const SelectRow<NB> cur = nx;
-        nx = select_load<NB>(p, row + stride, lane);
+        nx = select_load<NB>(b, row + stride);
         int c = __builtin_amdgcn_readfirstlane(cur.c);
         c = c < 0 ? 0 : (c > p.kmax ? p.kmax : c);
         const int f = cur.f, l = cur.l;
@@ -165,13 +183,16 @@ __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
         // the compiler from moving this, and the wait, above the search.)
         asm volatile("" : "+v"(nx.c), "+v"(nx.f), "+v"(nx.l), "+v"(nx.s[0]) : "s"(total));
         if constexpr (NB == 2) asm volatile("" : "+v"(nx.s[1]) : "s"(total));
-        const long long o = row * p.kmax;
+        const unsigned so = row * b.kmax * 4u;
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            if (keep[j]) { p.nf[o + pos] = first[j]; p.nl[o + pos] = last[j]; }
+            if (keep[j]) {
+                __builtin_amdgcn_raw_buffer_store_b32((unsigned)first[j], b.nf, (unsigned)pos * 4u, so, 0);
+                __builtin_amdgcn_raw_buffer_store_b32((unsigned)last[j], b.nl, (unsigned)pos * 4u, so, 0);
+            }
             pos += keep[j] ? 1 : 0;
         }
-        if (lane == 0) p.ncnt[row] = total;
+        if (lane == 0) __builtin_amdgcn_raw_buffer_store_b32((unsigned)total, b.cnt, 0, row * 4u, 0);
     }
 }
 
@@ -280,9 +301,24 @@ extern "C" stream_status stream_select_update(const float *branch_score, int *no
     SelectParams p;
     p.score = branch_score; p.nf = node_first; p.nl = node_last; p.ncnt = node_count;
     p.rows = rows; p.k = topk; p.kmax = topk_max;
-    if (wide)
+    if (wide) {
         hipLaunchKernelGGL(select_wide_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
-    else
-        hipLaunchKernelGGL(topk_max <= 32 ? select_kernel<1> : select_kernel<2>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)hip_stream, p);
-    return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+        return hipGetLastError() == hipSuccess ? STREAM_OK : STREAM_EDEVICE;
+    }
+    // The narrow kernel addresses a launch's rows with 32-bit byte offsets: at most 2^31 bytes of
+    // scores (8 bytes per node slot) per launch, more rows in further launches behind it.
+    const long long chunk = ((1LL << 31) / (8LL * topk_max)) & ~3LL;
+    for (long long r0 = 0; r0 < rows; r0 += chunk) {
+        const long long n = rows - r0 < chunk ? rows - r0 : chunk;
+        p.score = branch_score + 2 * r0 * topk_max;
+        p.nf = node_first + r0 * topk_max;
+        p.nl = node_last + r0 * topk_max;
+        p.ncnt = node_count + r0;
+        p.rows = n;
+        const long long g = (n + per_wg - 1) / per_wg;
+        hipLaunchKernelGGL(topk_max <= 32 ? select_kernel<1> : select_kernel<2>, dim3((unsigned)g), dim3(256), 0,
+                           (hipStream_t)hip_stream, p);
+        if (hipGetLastError() != hipSuccess) return STREAM_EDEVICE;
+    }
+    return STREAM_OK;
 }

@@ -122,3 +122,33 @@ def test_full_size_sampled_rows():
     np.testing.assert_array_equal(gl[live], ol[live])
     # law at full size: count = min(k, number of valid branches)
     assert int(nc.max()) <= k and int(nc.min()) >= 0
+
+
+def test_more_rows_than_one_launch_addresses():
+    """A launch of the narrow kernel addresses its rows with 32-bit byte offsets (2 GiB of scores);
+    the entry point takes more rows in further launches.  4.3 M rows at kmax = 64: rows on both
+    sides of the seam, the last rows and random ones against the oracle."""
+    kmax, k = 64, 24
+    seam = (1 << 31) // (8 * kmax)                   # rows of the first launch
+    rows = seam + 100_003
+    g = torch.Generator(device=DEV); g.manual_seed(77)
+    sc = torch.randn((rows, 2 * kmax), device=DEV, generator=g)
+    sc = torch.where(torch.rand(sc.shape, device=DEV, generator=g) < 0.2, torch.full_like(sc, -float("inf")), sc)
+    sc = (sc * 2).round() / 2                        # ties
+    nf = (torch.arange(kmax, device=DEV, dtype=torch.int32) * 8).repeat(rows, 1).contiguous()
+    nl = nf + torch.randint(0, 8, (rows, kmax), device=DEV, generator=g, dtype=torch.int32)
+    nc = torch.randint(0, kmax + 1, (rows,), device=DEV, generator=g, dtype=torch.int32)
+    pick = np.unique(np.concatenate([np.arange(0, 8), np.arange(seam - 40, seam + 40), np.arange(rows - 40, rows),
+                                     np.random.default_rng(5).integers(0, rows, 1500)]))
+    before = [t[pick].cpu().numpy() for t in (sc, nf, nl, nc)]
+    print(f"[select] {rows} rows, kmax {kmax}: seam at row {seam}, {len(pick)} rows against the oracle", flush=True)
+    binding.stream_select_update(sc, nf, nl, nc, k)
+    torch.cuda.synchronize()
+    of, ol, oc = select_update(*before, k)
+    gf, gl, gc = [t[pick].cpu().numpy() for t in (nf, nl, nc)]
+    np.testing.assert_array_equal(gc, oc)
+    live = np.arange(kmax)[None, :] < oc[:, None]
+    np.testing.assert_array_equal(gf[live], of[live])
+    np.testing.assert_array_equal(gl[live], ol[live])
+    np.testing.assert_array_equal(gf[~live], before[1][~live])
+    assert int(nc.max()) <= k and int(nc.min()) >= 0
