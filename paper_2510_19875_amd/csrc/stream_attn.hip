@@ -870,14 +870,21 @@ __global__ void __launch_bounds__(256, OCC) attn_kernel(const AttnParams p)
     // ------------------------------------------------------------------ pass 2: received mass
     // S = Q K^T: a lane owns key column `col`; element i of row block rq is query
     // rq*32 + 8*(i/4) + 4*gh + (i%4).  Its normaliser:
+    // (through a resource over the wavefront's real queries: rows past the end of the sequence
+    // read as zeros, and no load sits behind a branch)
     float lq[NQ][16];
+    {
+        const int qrows = L - qtok0 < QT ? L - qtok0 : QT;
+        const __amdgpu_buffer_rsrc_t lrs =
+            make_tile_rsrc(p.lse2 + (long long)h * p.T + sd.tok0 + qtok0, (unsigned)qrows * 4u);
 #pragma unroll
-    for (int rq = 0; rq < NQ; ++rq)
+        for (int rq = 0; rq < NQ; ++rq)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int tq = qtok0 + rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3);
-            lq[rq][i] = tq < L ? p.lse2[(long long)h * p.T + sd.tok0 + tq] : 0.f;
-        }
+            for (int i = 0; i < 16; ++i) {
+                const unsigned voff = (unsigned)(rq * 32 + (i >> 2) * 8 + gh * 4 + (i & 3)) * 4u;
+                lq[rq][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(lrs, voff, 0, 0));
+            }
+    }
     float *mass_h = p.mass + (long long)h * p.T + sd.tok0;
     if (n_tiles > 0) {
         const unsigned off0 = tile_off(0);
