@@ -140,6 +140,9 @@ __global__ void __launch_bounds__(128, OCC) level_wide_kernel(const PruneParams 
     }
     wave_sync();
 
+    // The Q tile has to be there before the first MFMA anyway; waiting for it here, once, lets
+    // the waits inside the tile loop count K fragments only (vmcnt(0), other counters untouched).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     unsigned long long tiles_done = 0;
     for (int level = 1; level <= levels; ++level) {
         const bool first = level == 1;
