@@ -48,6 +48,13 @@ __device__ __forceinline__ float wave_max(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// Number of set bits of a wavefront mask at lanes below this one (v_mbcnt: two instructions, and no
+// per-lane mask constant to keep in registers).
+__device__ __forceinline__ int lanes_below(unsigned long long m)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+}
+
 // One operand fragment (16 bytes per lane) times another, accumulated into a 32x32 tile.
 template <bool BF16>
 __device__ __forceinline__ floatx16 mfma_frag(const uint4 &a, const uint4 &b, floatx16 c)

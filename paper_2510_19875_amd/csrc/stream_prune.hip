@@ -176,7 +176,6 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
     int cut_lo = L / BK;
     if (p.mask != STREAM_MASK_FULL && (q * BQ + 1) / BK < cut_lo) cut_lo = (q * BQ + 1) / BK;
     if (tail_row) cut_lo = 0;
-    const unsigned long long lt = (1ull << lane) - 1ull;
     const long long o = row * p.kmax;
     // ARB: first key block of [a, b] that C^blk leaves to this row, or -1
     const unsigned *anyrow = ARB ? p.cany + (long long)gb * p.cw : nullptr;
@@ -238,7 +237,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
 
         const unsigned long long b0 = __ballot(need0), b1 = __ballot(need1);
         const int n0 = __popcll(b0), nt = n0 + __popcll(b1);
-        const int pos0 = __popcll(b0 & lt), pos1 = n0 + __popcll(b1 & lt);
+        const int pos0 = lanes_below(b0), pos1 = n0 + lanes_below(b1);
         if (need0) s_rep[wave][pos0] = rep0;
         if (need1) s_rep[wave][pos1] = rep1;
         wave_sync();
@@ -382,7 +381,7 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
         select_topk_wave<2>(sel_s, sel_v, k, lane, sel_keep);
         const bool keep0 = sel_keep[0], keep1 = sel_keep[1];
         const unsigned long long kb0 = __ballot(keep0), kb1 = __ballot(keep1);
-        const int before = __popcll(kb0 & lt) + __popcll(kb1 & lt);
+        const int before = lanes_below(kb0) + lanes_below(kb1);
         const int p0 = before, p1 = before + (keep0 ? 1 : 0);
         const int newcnt = __popcll(kb0) + __popcll(kb1);
         const bool writer = WPR == 1 || wave == 0;

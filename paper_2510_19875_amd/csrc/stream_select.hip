@@ -168,13 +168,12 @@ __global__ void __launch_bounds__(256) select_kernel(const SelectParams p)
         }
         select_topk_wave_v<NB>(cur.s, v, p.k, lane, keep);
         // update: survivors overwrite the row's node list in positional order
-        const unsigned long long lt = (1ull << lane) - 1ull;
         unsigned long long kb[NB];
         int pos = 0, total = 0;
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             kb[j] = __ballot(keep[j]);
-            pos += __popcll(kb[j] & lt);
+            pos += lanes_below(kb[j]);
             total += __popcll(kb[j]);
         }
         // The next row's data is taken here, before this row's stores are issued: stores and loads
