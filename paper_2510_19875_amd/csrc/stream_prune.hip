@@ -425,9 +425,14 @@ __global__ void __launch_bounds__(256, OCC) level_kernel(const PruneParams p)
             if (keep1) { s_nf[wave][p1] = m; s_nl[wave][p1] = l;     s_ns[wave][p1] = s1; }
             wave_sync();
             live = lane < newcnt;
-            f = live ? s_nf[wave][lane] : 0;
-            l = live ? s_nl[wave][lane] : -1;
-            sc = live ? s_ns[wave][lane] : -INFINITY;
+            // (the lane's LDS address is formed here, from an opaque copy of the lane number: hoisted
+            // out of the level loop it does not fit the registers and comes back from scratch, a
+            // memory round trip per level)
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            f = live ? s_nf[wave][ln] : 0;
+            l = live ? s_nl[wave][ln] : -1;
+            sc = live ? s_ns[wave][ln] : -INFINITY;
             wave_sync();
         }
     }
